@@ -1,0 +1,212 @@
+/*
+ * lsm_index.h -- C ABI of the GPU key index of a key-value-separated LSM-tree.
+ *
+ * The index stores one 64-byte record per 16-token block of a cached token prefix: a
+ * 32-byte prefix-preserving key, a sequence number, a put/tombstone flag and a pointer
+ * (file id + offset, length) into separate append-only tensor files (arXiv 2511.16138,
+ * section 3.1 "disk index layer" / "tensor-log layer", section 3.2).  This library runs the
+ * data-parallel part of that index on one AMD MI355X (gfx950):
+ *
+ *   lsm_compact       merge sorted runs into one run (section 2.2, compaction)
+ *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
+ *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
+ *                     section 2.2, "Point Lookups")
+ *   lsm_policy_*      the adaptive controller's cost model (section 2.2 costs, section 3.3)
+ *
+ * Conventions
+ *   - Pointers marked DEVICE are HIP device memory on the current device; pointers marked
+ *     HOST are ordinary host memory read during the call only.  The library never allocates
+ *     or frees device memory and keeps no state between calls; the caller owns every buffer.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
+ *     Calls return as soon as the work is enqueued unless stated otherwise; outputs are
+ *     valid once the stream has been synchronised.
+ *   - Every function returns 0 (LSM_OK) or a negative lsm_status; nothing throws or aborts.
+ *     Argument errors are detected on the host before anything is launched, so a failed
+ *     call has written nothing.
+ *   - Keys are ordered as 32-byte big-endian byte strings (memcmp order).  All other fields
+ *     are little-endian.  There is no floating point on the device.
+ */
+#ifndef LSM_INDEX_H
+#define LSM_INDEX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* One index record.  64 bytes, natural alignment, no packing pragma needed. */
+typedef struct {
+    uint8_t  key[32]; /* prefix-preserving key; order = memcmp(a.key, b.key, 32)           */
+    uint64_t seqno;   /* larger = newer (unsigned)                                          */
+    uint8_t  type;    /* LSM_PUT or LSM_TOMBSTONE                                           */
+    uint8_t  pad0[7]; /* carried through verbatim                                           */
+    uint64_t vptr;    /* (file_id << 32) | offset in the tensor log; opaque to this library */
+    uint32_t vlen;    /* bytes of the tensor block; opaque                                  */
+    uint32_t pad1;    /* carried through verbatim                                           */
+} lsm_entry_t;
+
+enum { LSM_PUT = 0, LSM_TOMBSTONE = 1 };
+
+/* flags of lsm_compact */
+enum {
+    LSM_BOTTOMMOST = 1, /* output is the last level: winning tombstones are dropped too   */
+    LSM_VALIDATE = 2    /* check inputs (strictly ascending runs, type byte); synchronises */
+};
+
+typedef enum {
+    LSM_OK = 0,
+    LSM_ERR_NULL = -1,      /* a required pointer is NULL                                  */
+    LSM_ERR_BAD_ARG = -2,   /* n_runs == 0 or too large, stride == 0, max_blocks too large */
+    LSM_ERR_CAPACITY = -3,  /* out->capacity < total number of input entries               */
+    LSM_ERR_WORKSPACE = -4, /* workspace missing, misaligned or too small                  */
+    LSM_ERR_UNSORTED = -5,  /* LSM_VALIDATE: a run is not strictly ascending by key        */
+    LSM_ERR_BAD_ENTRY = -6, /* LSM_VALIDATE: a type byte is neither PUT nor TOMBSTONE      */
+    LSM_ERR_HIP = -7,       /* a HIP call failed                                           */
+    LSM_ERR_INTERNAL = -8   /* a device-side consistency check failed (see lsm_compact)    */
+} lsm_status;
+
+enum {
+    LSM_MAX_RUNS = 64,          /* runs per lsm_compact call and per lsm_tree_t            */
+    LSM_MAX_BLOCKS = 256,       /* block keys per probe request                            */
+    LSM_KEY_BYTES = 32,
+    LSM_DEFAULT_FENCE_STRIDE = 64 /* one fence per 4 KiB page of entries                   */
+};
+
+/* A sorted run: n entries, strictly ascending by key (one version per key per run). */
+typedef struct {
+    const lsm_entry_t* entries; /* DEVICE, 64-byte aligned */
+    uint64_t n;
+} lsm_run_t;
+
+/* Destination of a compaction. */
+typedef struct {
+    lsm_entry_t* entries; /* DEVICE, 64-byte aligned, room for `capacity` entries           */
+    uint64_t capacity;    /* must be >= the total number of input entries                   */
+    uint64_t* n_out;      /* DEVICE, one uint64: number of entries written                  */
+} lsm_out_t;
+
+/* Fence index of a run: fence i is the key of entry i*stride. */
+typedef struct {
+    const uint8_t* keys; /* DEVICE, n x 32 bytes, n = ceil(run.n / stride); may be NULL if run.n == 0 */
+    uint64_t n;
+    uint32_t stride;
+} lsm_fence_t;
+
+typedef struct {
+    lsm_run_t run;
+    lsm_fence_t fence;
+    uint32_t level; /* informational */
+} lsm_tree_run_t;
+
+/* A tree = its runs ordered NEWEST -> OLDEST (shallow level first; within a level, the most
+ * recently written run first).  Precondition (LSM invariant): if a key is present in several
+ * runs, the run that comes earlier in this array holds the larger seqno. */
+typedef struct {
+    const lsm_tree_run_t* runs; /* HOST array */
+    uint32_t n_runs;            /* <= LSM_MAX_RUNS */
+} lsm_tree_t;
+
+/* A batch of probe requests; request r asks for n_blocks[r] consecutive block keys. */
+typedef struct {
+    const uint8_t* keys;      /* DEVICE, n_req x max_blocks x 32 bytes, row-major           */
+    const uint32_t* n_blocks; /* DEVICE, n_req values, each <= max_blocks                   */
+    uint32_t n_req;
+    uint32_t max_blocks;      /* row pitch in keys; <= LSM_MAX_BLOCKS                       */
+} lsm_queries_t;
+
+typedef struct {
+    uint64_t vptr;
+    uint32_t vlen;
+    uint32_t run_idx; /* index into tree.runs of the run that held the newest version       */
+} lsm_hit_t;
+
+typedef struct {
+    uint32_t* hit_len; /* DEVICE, n_req                                                     */
+    lsm_hit_t* hits;   /* DEVICE, n_req x max_blocks; all-zero at and beyond hit_len[r]     */
+} lsm_hits_t;
+
+/*
+ * lsm_compact -- merge n_runs sorted runs into one sorted run (section 2.2: data of smaller
+ * levels is merged into larger ones, sorted order is kept, obsolete entries are removed).
+ *
+ * Result: for every distinct key of the inputs, the version with the largest seqno (equal
+ * seqnos: the one from the lowest run index; runs[0] is the newest run) -- except that a
+ * winning TOMBSTONE is dropped when LSM_BOTTOMMOST is set.  Survivors are written to
+ * out->entries in strictly ascending key order as byte-for-byte copies of the winning 64
+ * input bytes, and their count is stored to *out->n_out.  The inputs are not modified and
+ * must not overlap the output.
+ *
+ * runs        HOST array of n_runs descriptors (1 <= n_runs <= LSM_MAX_RUNS); empty runs allowed.
+ * workspace   DEVICE scratch of at least lsm_compact_workspace_bytes(...) bytes, 256-byte
+ *             aligned; contents on entry are irrelevant.
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG, LSM_ERR_CAPACITY, LSM_ERR_WORKSPACE, LSM_ERR_HIP.
+ * With LSM_VALIDATE the call synchronises the stream and additionally returns
+ * LSM_ERR_UNSORTED / LSM_ERR_BAD_ENTRY (checked before merging; nothing is written then) or
+ * LSM_ERR_INTERNAL.  Without it, inputs that violate the precondition give an unspecified
+ * (but in-bounds) result.  If a device-side wait ever exceeds its bound, *out->n_out is set
+ * to UINT64_MAX instead of a count.
+ */
+int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments. */
+size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
+
+/*
+ * lsm_build_fences -- fence_keys_out[i] = run->entries[i*stride].key for 0 <= i < ceil(n/stride)
+ * (fence pointers, section 2.2: one key per page of `stride` entries, used to find the page
+ * that may hold a key without reading the run).
+ * fence_keys_out: DEVICE, ceil(n/stride) x 32 bytes.  Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (stride == 0).
+ */
+int lsm_build_fences(const lsm_run_t* run, uint32_t stride, uint8_t* fence_keys_out, void* stream);
+
+/*
+ * lsm_probe -- batched longest-cached-prefix lookup (appendix B "Probe": find the longest
+ * cached prefix of a request; section 2.2 "Point Lookups": levels are checked in order and
+ * the first match is the result).
+ *
+ * For request r with keys q[0..n): newest(q[j]) is the version of q[j] in the first run of
+ * `tree` (newest -> oldest) that contains it; q[j] is live if that version exists and is a PUT.
+ * hit_len[r] = number of leading live keys (first-miss semantics: a hole ends the prefix even
+ * if later blocks are present).  hits[r][j] = {vptr, vlen, run index} of newest(q[j]) for
+ * j < hit_len[r], and 16 zero bytes for hit_len[r] <= j < max_blocks.
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (max_blocks == 0 or > LSM_MAX_BLOCKS, n_runs > LSM_MAX_RUNS,
+ * a run with n > 0 whose fence index is missing or has n != ceil(run.n/stride)), LSM_ERR_HIP.
+ * n_req == 0 and n_runs == 0 are legal (every request then has hit_len 0).
+ */
+int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, const lsm_hits_t* out_hits, void* stream);
+
+/*
+ * Cost model of the adaptive controller (host only, double arithmetic).
+ *   L = smallest integer >= 1 with buffer_entries * T^L >= n_entries     (section 2.2: L = log_T(N e / M))
+ *   W = T L / (B K)   update;  Z = K L p  empty point lookup;  R = K L p + 1  non-empty point
+ *   lookup;  S = K L + d / B  range lookup                                (section 2.2)
+ *   cost = w W + s S + r R + z Z                                         (section 3.3)
+ * w, s, r, z are the observed shares of writes, range reads, successful point reads and empty
+ * probes in the current window.  lsm_policy_choose scans T in [t_min, t_max], K in [1, T-1]
+ * (K = 1 leveling ... K = T-1 tiering) and returns the cheapest pair; equal costs go to the
+ * smaller K, then the smaller T.  Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (t_min < 2, t_max < t_min,
+ * buffer_entries == 0, B <= 0).
+ */
+typedef struct {
+    double w, s, r, z;       /* workload mix                                   */
+    uint64_t n_entries;      /* N                                              */
+    uint64_t buffer_entries; /* M / e                                          */
+    double B;                /* entries per page                               */
+    double p;                /* Bloom-filter false-positive rate (1 = no filter) */
+    double d;                /* entries returned by a range lookup             */
+} lsm_policy_input_t;
+
+uint32_t lsm_policy_levels(uint64_t n_entries, uint64_t buffer_entries, uint32_t T);
+double lsm_policy_cost(const lsm_policy_input_t* in, uint32_t T, uint32_t K);
+int lsm_policy_choose(const lsm_policy_input_t* in, uint32_t t_min, uint32_t t_max, uint32_t* best_T,
+                      uint32_t* best_K);
+
+const char* lsm_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSM_INDEX_H */

@@ -1,0 +1,216 @@
+"""ctypes binding of liblsm_index.so (same names as the C entry points, marshalling only).
+
+Tensors are torch tensors on the GPU:
+  run       int64 [n, 8]   (64-byte entries; see include/lsm_index.h for the field layout)
+  fences    int64 [n_f, 4] (32-byte keys)
+  queries   int64 [n_req, max_blocks, 4] keys + int32 [n_req] block counts
+  hits      int64 [n_req, max_blocks, 2] (vptr | vlen + run_idx << 32), int32 [n_req] hit_len
+The library must have been built (python -c "import __graft_entry__ as g; g.build()");
+there is no fallback: a missing library raises at the first call.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+LSM_BOTTOMMOST = 1
+LSM_VALIDATE = 2
+LSM_MAX_RUNS = 64
+LSM_MAX_BLOCKS = 256
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "liblsm_index.so")
+
+
+class LsmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {lsm_strerror(code)} ({code})")
+
+
+class _Run(C.Structure):
+    _fields_ = [("entries", C.c_void_p), ("n", C.c_uint64)]
+
+
+class _Out(C.Structure):
+    _fields_ = [("entries", C.c_void_p), ("capacity", C.c_uint64), ("n_out", C.c_void_p)]
+
+
+class _Fence(C.Structure):
+    _fields_ = [("keys", C.c_void_p), ("n", C.c_uint64), ("stride", C.c_uint32)]
+
+
+class _TreeRun(C.Structure):
+    _fields_ = [("run", _Run), ("fence", _Fence), ("level", C.c_uint32)]
+
+
+class _Tree(C.Structure):
+    _fields_ = [("runs", C.POINTER(_TreeRun)), ("n_runs", C.c_uint32)]
+
+
+class _Queries(C.Structure):
+    _fields_ = [("keys", C.c_void_p), ("n_blocks", C.c_void_p), ("n_req", C.c_uint32), ("max_blocks", C.c_uint32)]
+
+
+class _Hits(C.Structure):
+    _fields_ = [("hit_len", C.c_void_p), ("hits", C.c_void_p)]
+
+
+class _PolicyInput(C.Structure):
+    _fields_ = [("w", C.c_double), ("s", C.c_double), ("r", C.c_double), ("z", C.c_double), ("n_entries", C.c_uint64),
+                ("buffer_entries", C.c_uint64), ("B", C.c_double), ("p", C.c_double), ("d", C.c_double)]
+
+
+_lib: Optional[C.CDLL] = None
+
+
+def _load(path: Optional[str] = None) -> C.CDLL:
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it first (__graft_entry__.build()); there is no CPU fallback")
+    L = C.CDLL(path)
+    L.lsm_compact.restype = C.c_int
+    L.lsm_compact.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_uint32, C.POINTER(_Out), C.c_void_p, C.c_size_t, C.c_void_p]
+    L.lsm_compact_workspace_bytes.restype = C.c_size_t
+    L.lsm_compact_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), C.c_uint32]
+    L.lsm_build_fences.restype = C.c_int
+    L.lsm_build_fences.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_void_p, C.c_void_p]
+    L.lsm_probe.restype = C.c_int
+    L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
+    L.lsm_policy_levels.restype = C.c_uint32
+    L.lsm_policy_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
+    L.lsm_policy_cost.restype = C.c_double
+    L.lsm_policy_cost.argtypes = [C.POINTER(_PolicyInput), C.c_uint32, C.c_uint32]
+    L.lsm_policy_choose.restype = C.c_int
+    L.lsm_policy_choose.argtypes = [C.POINTER(_PolicyInput), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    L.lsm_strerror.restype = C.c_char_p
+    L.lsm_strerror.argtypes = [C.c_int]
+    _lib = L
+    return L
+
+
+def _dev(t: torch.Tensor, what: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{what} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def lsm_strerror(code: int) -> str:
+    return _load().lsm_strerror(code).decode()
+
+
+def lsm_compact_workspace_bytes(run_lens: Sequence[int]) -> int:
+    arr = (C.c_uint64 * max(1, len(run_lens)))(*run_lens)
+    return int(_load().lsm_compact_workspace_bytes(arr, len(run_lens)))
+
+
+def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torch.Tensor] = None,
+                n_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None
+                ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Merge sorted runs (runs[0] newest).  Returns (out, n_out): out is int64 [capacity, 8]
+    whose first n_out rows are the result, n_out a one-element int64 tensor on the device."""
+    L = _load()
+    runs = [_dev(r, "run") for r in runs]
+    total = sum(int(r.shape[0]) for r in runs)
+    dev = runs[0].device if runs else torch.device("cuda")
+    if out is None:
+        out = torch.empty((max(total, 1), 8), dtype=torch.int64, device=dev)
+    if n_out is None:
+        n_out = torch.empty(1, dtype=torch.int64, device=dev)
+    need = lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs]) if runs else 0
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
+    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr())
+    rc = L.lsm_compact(rd, len(runs), flags, C.byref(od), _dev(workspace, "workspace").data_ptr(),
+                       workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_compact")
+    return out, n_out
+
+
+def lsm_build_fences(run: torch.Tensor, stride: int = 64, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """fence[i] = key of entry i*stride; returns int64 [ceil(n/stride), 4]."""
+    L = _load()
+    n = int(_dev(run, "run").shape[0])
+    n_f = (n + stride - 1) // stride if stride > 0 else 0
+    if out is None:
+        out = torch.empty((n_f, 4), dtype=torch.int64, device=run.device)
+    rd = _Run(run.data_ptr(), n)
+    rc = L.lsm_build_fences(C.byref(rd), stride, _dev(out, "fences").data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_build_fences")
+    return out
+
+
+@dataclass
+class TreeRun:
+    run: torch.Tensor      # int64 [n, 8]
+    fences: torch.Tensor   # int64 [ceil(n/stride), 4]
+    stride: int = 64
+    level: int = 0
+
+
+def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],
+              hit_len: Optional[torch.Tensor] = None, hits: Optional[torch.Tensor] = None, stream=None
+              ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Longest cached prefix of every request against `tree` (runs newest -> oldest)."""
+    L = _load()
+    _dev(qkeys, "qkeys")
+    n_req, max_blocks = int(qkeys.shape[0]), int(qkeys.shape[1])
+    if hit_len is None:
+        hit_len = torch.empty(n_req, dtype=torch.int32, device=qkeys.device)
+    if hits is None:
+        hits = torch.empty((n_req, max_blocks, 2), dtype=torch.int64, device=qkeys.device)
+    tr = (_TreeRun * max(1, len(tree)))()
+    for i, t in enumerate(tree):
+        tr[i].run = _Run(_dev(t.run, "tree run").data_ptr(), int(t.run.shape[0]))
+        tr[i].fence = _Fence(_dev(t.fences, "fences").data_ptr(), int(t.fences.shape[0]), t.stride)
+        tr[i].level = t.level
+    td = _Tree(tr, len(tree))
+    qd = _Queries(qkeys.data_ptr(), _dev(n_blocks, "n_blocks").data_ptr(), n_req, max_blocks)
+    hd = _Hits(_dev(hit_len, "hit_len").data_ptr(), _dev(hits, "hits").data_ptr())
+    rc = L.lsm_probe(C.byref(qd), C.byref(td), C.byref(hd), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_probe")
+    return hit_len, hits
+
+
+def _policy_input(w, s, r, z, n_entries, buffer_entries, B, p, d) -> _PolicyInput:
+    return _PolicyInput(w, s, r, z, n_entries, buffer_entries, B, p, d)
+
+
+def lsm_policy_levels(n_entries: int, buffer_entries: int, T: int) -> int:
+    return int(_load().lsm_policy_levels(n_entries, buffer_entries, T))
+
+
+def lsm_policy_cost(w, s, r, z, n_entries, buffer_entries, T, K, B, p, d) -> float:
+    pin = _policy_input(w, s, r, z, n_entries, buffer_entries, B, p, d)
+    return float(_load().lsm_policy_cost(C.byref(pin), T, K))
+
+
+def lsm_policy_choose(w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d) -> Tuple[int, int]:
+    pin = _policy_input(w, s, r, z, n_entries, buffer_entries, B, p, d)
+    bt, bk = C.c_uint32(0), C.c_uint32(0)
+    rc = _load().lsm_policy_choose(C.byref(pin), t_min, t_max, C.byref(bt), C.byref(bk))
+    if rc != 0:
+        raise LsmError(rc, "lsm_policy_choose")
+    return int(bt.value), int(bk.value)

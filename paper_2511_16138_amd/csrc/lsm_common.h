@@ -1,0 +1,77 @@
+// Shared device-side definitions of the LSM key-index kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lsm_index.h"
+
+namespace lsm {
+
+constexpr int kWave = 64;
+
+// A key as four big-endian-numeric words: comparing w[0], w[1], ... as unsigned integers is
+// byte-string (memcmp) order of the 32 key bytes.
+struct Key {
+    uint64_t w[4];
+};
+
+__device__ __forceinline__ Key key_from_raw(uint4 lo, uint4 hi) {
+    Key k;
+    k.w[0] = __builtin_bswap64(((uint64_t)lo.y << 32) | lo.x);
+    k.w[1] = __builtin_bswap64(((uint64_t)lo.w << 32) | lo.z);
+    k.w[2] = __builtin_bswap64(((uint64_t)hi.y << 32) | hi.x);
+    k.w[3] = __builtin_bswap64(((uint64_t)hi.w << 32) | hi.z);
+    return k;
+}
+
+// Key of an entry (or of a 32-byte key record) in global or shared memory; p is 16-byte aligned.
+__device__ __forceinline__ Key load_key(const void* p) {
+    const uint4* q = reinterpret_cast<const uint4*>(p);
+    return key_from_raw(q[0], q[1]);
+}
+
+__device__ __forceinline__ bool key_less(const Key& a, const Key& b) {
+    if (a.w[0] != b.w[0]) return a.w[0] < b.w[0];
+    if (a.w[1] != b.w[1]) return a.w[1] < b.w[1];
+    if (a.w[2] != b.w[2]) return a.w[2] < b.w[2];
+    return a.w[3] < b.w[3];
+}
+
+__device__ __forceinline__ bool key_equal(const Key& a, const Key& b) {
+    return ((a.w[0] ^ b.w[0]) | (a.w[1] ^ b.w[1]) | (a.w[2] ^ b.w[2]) | (a.w[3] ^ b.w[3])) == 0;
+}
+
+__device__ __forceinline__ bool key_less_equal(const Key& a, const Key& b) { return !key_less(b, a); }
+
+// Number of entries of run[lo, hi) whose key is < k, plus lo.  Global memory.
+__device__ __forceinline__ uint64_t lower_bound_run(const lsm_entry_t* run, uint64_t lo, uint64_t hi, const Key& k) {
+    while (lo < hi) {
+        uint64_t mid = lo + ((hi - lo) >> 1);
+        if (key_less(load_key(run + mid), k)) lo = mid + 1;
+        else hi = mid;
+    }
+    return lo;
+}
+
+// Sum / max over the 64 lanes of a wave; every lane must call.
+__device__ __forceinline__ uint64_t wave_sum_u64(uint64_t v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Run descriptors passed to kernels by value.
+struct RunTable {
+    const lsm_entry_t* ptr[LSM_MAX_RUNS];
+    uint64_t n[LSM_MAX_RUNS];
+    uint32_t k;
+};
+
+}  // namespace lsm

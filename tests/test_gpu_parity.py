@@ -1,0 +1,260 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU checker, bit for bit.
+
+Sizes here are ones the checker finishes in seconds; they still span many tiles (a tile is
+about a thousand entries) and ragged tails.  Full-size cases are in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+import torch
+
+import brute
+from brute import PUT, TOMBSTONE
+from gpu_util import as_bytes, assert_probe_equal, build_tree, compact_gpu, dev, probe_gpu, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2511_16138_amd as lsmgpu
+    lsmgpu.binding._load()  # raises if the HIP library has not been built
+    assert torch.cuda.is_available()
+    return lsmgpu
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    from workloads import lsm
+    return lsm.config1(device=dev())
+
+
+def _check_compact(g, oracle, runs, flags):
+    got = compact_gpu(g, runs, flags)
+    want = oracle.compact([r.cpu() for r in runs], flags & 1)
+    assert got.shape[0] == want.shape[0]
+    assert np.array_equal(as_bytes(got).reshape(-1, 64), want)
+    return got
+
+
+# ------------------------------------------------------------------ compaction
+@pytest.mark.parametrize("flags", [0, 1])
+def test_config1_compaction(g, oracle, cfg1, flags):
+    print("config1 compaction flags", flags, flush=True)
+    _check_compact(g, oracle, cfg1.runs, flags)
+
+
+def test_generator_is_identical_on_cpu_and_gpu(cfg1):
+    from workloads import lsm
+    w = lsm.config1(device="cpu")
+    assert all(torch.equal(a.cpu(), b) for a, b in zip(cfg1.runs, w.runs))
+
+
+@pytest.mark.parametrize("scale,flags", [(256, 1), (256, 0), (64, 1)])
+def test_scaled_config3_tiered_16way(g, oracle, scale, flags):
+    from workloads import lsm
+    print("config3 scale", scale, "flags", flags, flush=True)
+    w = lsm.config3(device=dev(), scale=scale)
+    _check_compact(g, oracle, w.runs, flags)
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+def test_scaled_config2_leveled_two_way(g, oracle, flags):
+    from workloads import lsm
+    print("config2 scale 50 flags", flags, flush=True)
+    w = lsm.config2(device=dev(), scale=50)  # 40,000 + 400,000 entries
+    _check_compact(g, oracle, w.runs, flags)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 5, 7, 16, 17, 33, 64])
+def test_run_counts_and_ragged_lengths(g, oracle, k):
+    """Any run count up to the maximum, uneven and empty runs, lengths that are not tile multiples."""
+    from workloads import lsm
+    print("ragged k", k, flush=True)
+    w = lsm.config3(device=dev(), scale=1024)  # 16 runs x 4096
+    rs = np.random.RandomState(k)
+    runs = []
+    for j in range(k):
+        src = w.runs[j % 16]
+        n = int(rs.choice([0, 1, 7, 959, 960, 961, 1024, 2500, 4096]))
+        start = int(rs.randint(0, 4096 - n + 1))
+        r = src[start:start + n].clone()
+        r[:, 4] = r[:, 4] ^ (j * 0x9E3779B1)  # different versions in different runs
+        runs.append(r)
+    for flags in (0, 1):
+        _check_compact(g, oracle, runs, flags)
+
+
+def test_degenerate_inputs(g, oracle):
+    from workloads import lsm
+    print("degenerate inputs", flush=True)
+    w = lsm.config3(device=dev(), scale=1024)
+    a = w.runs[0]
+    empty = a[:0]
+    assert compact_gpu(g, [empty], 1).shape[0] == 0
+    assert compact_gpu(g, [empty, empty, empty], 0).shape[0] == 0
+    _check_compact(g, oracle, [empty, a[:5], empty], 0)
+    _check_compact(g, oracle, [a], 1)  # single run: tombstone filter
+    _check_compact(g, oracle, [a], 0)  # single run: copy
+    # k identical key sets: the run with the largest seqnos survives whole
+    runs = []
+    for j, base in enumerate([300, 900, 100, 500]):
+        r = a.clone()
+        r[:, 4] = base * 100000 + torch.arange(a.shape[0], device=a.device)
+        r[:, 6] = j
+        runs.append(r)
+    got = _check_compact(g, oracle, runs, 0)
+    assert bool((got[:, 6] == 1).all())
+    # all tombstones into the last level: nothing survives
+    t = a.clone()
+    t[:, 5] = 1
+    assert compact_gpu(g, [t, t[:100].clone()], 1).shape[0] == 0
+    # equal seqnos: lowest run index wins
+    r0, r1 = a.clone(), a.clone()
+    r0[:, 6], r1[:, 6] = 111, 222
+    got = _check_compact(g, oracle, [r0, r1], 0)
+    assert bool((got[:, 6] == 111).all())
+    # disjoint key ranges given in the "wrong" order: concatenation
+    _check_compact(g, oracle, [a[3000:], a[:1000], a[1000:3000]], 0)
+
+
+def test_adversarial_keys_long_common_prefixes(g, oracle):
+    """Keys that differ only in their last bytes, and heavy duplication across runs."""
+    print("adversarial keys", flush=True)
+    rs = np.random.RandomState(77)
+    runs = []
+    for j in range(6):
+        codes = np.unique(rs.randint(0, 6000, size=4000))
+        raws = []
+        for c in codes:
+            key = b"\xAB" * 29 + bytes([(c >> 16) & 0xFF, (c >> 8) & 0xFF, c & 0xFF])
+            raws.append(brute.pack_entry(key, int(rs.randint(0, 1 << 62)), TOMBSTONE if rs.rand() < 0.2 else PUT,
+                                         vptr=int(rs.randint(1 << 60)), vlen=j, pad0=bytes([j] * 7), pad1=j))
+        runs.append(to_dev(brute.run_from_raw(raws)))
+    for flags in (0, 1):
+        _check_compact(g, oracle, runs, flags)
+
+
+def test_results_do_not_depend_on_repetition(g, cfg1):
+    print("determinism", flush=True)
+    first = compact_gpu(g, cfg1.runs, 1).clone()
+    for _ in range(5):
+        assert torch.equal(compact_gpu(g, cfg1.runs, 1), first)
+
+
+def test_compaction_is_associative_on_gpu(g, oracle, cfg1):
+    print("associativity", flush=True)
+    newest_first = cfg1.runs
+    inner = compact_gpu(g, newest_first[2:], 0).contiguous()        # the two oldest runs
+    nested = compact_gpu(g, [newest_first[0], newest_first[1], inner], 1)
+    flat = compact_gpu(g, newest_first, 1)
+    assert torch.equal(nested, flat)
+
+
+def test_validate_flag(g, cfg1):
+    print("validate", flush=True)
+    a = cfg1.runs[0].clone()
+    out, n_out = g.lsm_compact([a, cfg1.runs[1]], g.LSM_VALIDATE)
+    assert int(n_out.item()) > 0
+    bad = a.clone()
+    bad[[10, 11]] = bad[[11, 10]]
+    with pytest.raises(g.LsmError) as e:
+        g.lsm_compact([bad, cfg1.runs[1]], g.LSM_VALIDATE)
+    assert e.value.code == -5
+    bad = a.clone()
+    bad[5, 5] = 7
+    with pytest.raises(g.LsmError) as e:
+        g.lsm_compact([cfg1.runs[1], bad], g.LSM_VALIDATE)
+    assert e.value.code == -6
+    small = torch.empty((10, 8), dtype=torch.int64, device=a.device)
+    with pytest.raises(g.LsmError) as e:
+        g.lsm_compact([a], 0, out=small)
+    assert e.value.code == -3
+
+
+# ------------------------------------------------------------------ fences
+@pytest.mark.parametrize("stride", [1, 3, 64, 100, 16383, 16384, 100000])
+def test_fences(g, oracle, cfg1, stride):
+    print("fences stride", stride, flush=True)
+    run = cfg1.runs[0]
+    f = g.lsm_build_fences(run, stride)
+    torch.cuda.synchronize()
+    assert np.array_equal(as_bytes(f).reshape(-1, 32), oracle.build_fences(run.cpu(), stride))
+
+
+# ------------------------------------------------------------------ probe
+def test_config1_probe_before_and_after_compaction(g, oracle, cfg1):
+    from workloads import lsm
+    print("config1 probe", flush=True)
+    q, nb = lsm.queries_config1(cfg1, 4096)
+    runs_cpu = [r.cpu() for r in cfg1.runs]
+    want = oracle.probe(q, nb, runs_cpu)
+    got = probe_gpu(g, q, nb, build_tree(g, cfg1.runs))
+    assert_probe_equal(oracle, got, want)
+    assert 0.05 < float((want[0] == 0).mean()) < 0.6 and want[0].max() > 32
+    for flags in (0, 1):
+        merged = compact_gpu(g, cfg1.runs, flags).contiguous()
+        got2 = probe_gpu(g, q, nb, build_tree(g, [merged]))
+        assert_probe_equal(oracle, got2, oracle.probe(q, nb, [merged.cpu()]))
+        assert np.array_equal(got2[0], got[0])                      # same prefix lengths
+        assert np.array_equal(got2[1][..., 0], got[1][..., 0])      # same pointers
+        assert np.array_equal(got2[1][..., 1] & 0xFFFFFFFF, got[1][..., 1] & 0xFFFFFFFF)  # same lengths
+
+
+@pytest.mark.parametrize("stride", [1, 7, 64, 1000])
+def test_probe_fence_strides_and_row_pitches(g, oracle, cfg1, stride):
+    from workloads import lsm
+    print("probe stride", stride, flush=True)
+    q, nb = lsm.make_queries(cfg1.universe, 300, 1, 100, 0.6, 0.3, None, stream=5, row_blocks=100)
+    want = oracle.probe(q, nb, [r.cpu() for r in cfg1.runs])
+    assert_probe_equal(oracle, probe_gpu(g, q, nb, build_tree(g, cfg1.runs, stride)), want)
+
+
+def test_probe_holes_absent_keys_and_edges(g, oracle):
+    """A hole ends the prefix even if later blocks are present; keys between, below and above
+    the stored keys miss; tombstoned keys are not live; repeated keys are fine."""
+    print("probe holes", flush=True)
+    rs = np.random.RandomState(21)
+    runs_raw = brute.random_runs(rs, 5, 400, 3000, (30, 31), tomb_p=0.25)
+    runs = [to_dev(brute.run_from_raw(r)) for r in runs_raw]
+    present = sorted({r[:32] for run in runs_raw for r in run})
+    requests = []
+    for _ in range(600):
+        n = int(rs.randint(0, 41))
+        req = []
+        for _ in range(n):
+            u = rs.rand()
+            if u < 0.8:
+                req.append(present[int(rs.randint(len(present)))])
+            elif u < 0.9:
+                k = bytearray(present[int(rs.randint(len(present)))]); k[29] = 1; req.append(bytes(k))
+            else:
+                req.append(bytes(rs.randint(0, 256, size=32).astype(np.uint8)))
+        requests.append(req)
+    requests += [[b"\x00" * 32], [b"\xff" * 32], []]
+    q = np.zeros((len(requests), 40, 32), dtype=np.uint8)
+    nb = np.zeros(len(requests), dtype=np.int32)
+    for i, req in enumerate(requests):
+        nb[i] = len(req)
+        for j, k in enumerate(req):
+            q[i, j] = np.frombuffer(k, dtype=np.uint8)
+    qd = torch.from_numpy(q.view(np.int64).reshape(len(requests), 40, 4).copy()).to(dev())
+    nbd = torch.from_numpy(nb).to(dev())
+    # random_runs draws seqnos at random; the tree precondition wants newer runs to hold larger ones
+    ordered = []
+    for j, r in enumerate(runs):
+        r = r.clone(); r[:, 4] = (len(runs) - j) * (1 << 40) + (r[:, 4] & 0xFFFFF); ordered.append(r)
+    want = oracle.probe(q, nb.astype(np.uint32), [r.cpu() for r in ordered])
+    assert_probe_equal(oracle, probe_gpu(g, qd, nbd, build_tree(g, ordered)), want)
+    assert (want[0] > 3).any() and (want[0] == 0).any()
+
+
+def test_probe_empty_tree_and_empty_runs(g, oracle, cfg1):
+    from workloads import lsm
+    print("probe empty", flush=True)
+    q, nb = lsm.queries_config1(cfg1, 64)
+    hl, hits = probe_gpu(g, q, nb, [])
+    assert (hl == 0).all() and (hits == 0).all()
+    empty = cfg1.runs[0][:0]
+    tree = build_tree(g, [empty, cfg1.runs[3], empty])
+    want = oracle.probe(q, nb, [empty.cpu(), cfg1.runs[3].cpu(), empty.cpu()])
+    assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)

@@ -1,0 +1,107 @@
+"""CPU-only checks of the GPU library: it loads, exports the declared C ABI, and its host-side
+logic (argument validation, workspace sizing, cost model) behaves as include/lsm_index.h says.
+No kernel is launched here."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2511_16138_amd.binding as B
+    if not os.path.exists(B.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    return B._load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "lsm_index.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lsm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_entry_point_is_exported(lib):
+    names = declared_functions()
+    assert {"lsm_compact", "lsm_compact_workspace_bytes", "lsm_build_fences", "lsm_probe", "lsm_strerror",
+            "lsm_policy_levels", "lsm_policy_cost", "lsm_policy_choose"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in lsm_index.h but not exported"
+
+
+def test_struct_sizes_match_the_header():
+    import paper_2511_16138_amd.binding as B
+    assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 24 and C.sizeof(B._Fence) == 24
+    assert C.sizeof(B._TreeRun) == 48 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
+    assert C.sizeof(B._PolicyInput) == 72
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    import paper_2511_16138_amd.binding as B
+    n_out = C.c_uint64(123)
+    run = B._Run(None, 0)
+    out = B._Out(None, 0, C.addressof(n_out))
+    assert lib.lsm_compact(None, 1, 0, C.byref(out), None, 0, None) == -1          # NULL runs
+    assert lib.lsm_compact(C.byref(run), 0, 0, C.byref(out), None, 0, None) == -2  # n_runs == 0
+    assert lib.lsm_compact(C.byref(run), 65, 0, C.byref(out), None, 0, None) == -2
+    bad = B._Run(None, 5)
+    assert lib.lsm_compact(C.byref(bad), 1, 0, C.byref(out), None, 0, None) == -1  # n > 0 but no entries
+    fake = B._Run(64 * 1000, 10)
+    small = B._Out(64 * 2000, 9, C.addressof(n_out))
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(small), None, 0, None) == -3  # capacity
+    big = B._Out(64 * 2000, 10, C.addressof(n_out))
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(big), None, 0, None) == -4    # workspace
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 16, None) == -4
+    misaligned = B._Run(64 * 1000 + 8, 10)
+    assert lib.lsm_compact(C.byref(misaligned), 1, 0, C.byref(big), 256 * 7, 1 << 20, None) == -2
+    assert n_out.value == 123
+    assert lib.lsm_build_fences(C.byref(fake), 0, 4096, None) == -2
+    assert lib.lsm_build_fences(None, 64, 4096, None) == -1
+    assert lib.lsm_build_fences(C.byref(run), 64, None, None) == 0  # empty run: nothing to do
+    q = B._Queries(4096, 8192, 4, 257)
+    tree = B._Tree(None, 0)
+    hits = B._Hits(4096, 8192)
+    assert lib.lsm_probe(C.byref(q), C.byref(tree), C.byref(hits), None) == -2  # max_blocks > 256
+    q = B._Queries(None, None, 0, 16)
+    assert lib.lsm_probe(C.byref(q), C.byref(tree), C.byref(hits), None) == 0   # empty batch
+    tr = (B._TreeRun * 1)()
+    tr[0].run, tr[0].fence = B._Run(64 * 1000, 100), B._Fence(4096, 1, 64)        # needs 2 fences
+    q = B._Queries(4096, 8192, 4, 16)
+    assert lib.lsm_probe(C.byref(q), C.byref(B._Tree(tr, 1)), C.byref(hits), None) == -2
+    for code in range(-8, 1):
+        assert lib.lsm_strerror(code) and lib.lsm_strerror(code) != b"unknown status"
+    assert lib.lsm_strerror(-99) == b"unknown status"
+
+
+def test_workspace_size_is_monotone_and_small(lib):
+    import paper_2511_16138_amd as g
+    assert g.lsm_compact_workspace_bytes([]) == 0
+    a = g.lsm_compact_workspace_bytes([0, 0])
+    b = g.lsm_compact_workspace_bytes([1 << 22] * 16)
+    assert 256 <= a < b < (1 << 22) * 16 * 64 // 50  # a few percent of the data at most
+
+
+def test_cost_model_matches_the_checker(lib, oracle):
+    import paper_2511_16138_amd as g
+    rs = np.random.RandomState(5)
+    for _ in range(200):
+        w, s, r, z = rs.dirichlet([1, 1, 1, 1])
+        N, M = int(rs.randint(1, 1 << 40)), int(rs.randint(1, 1 << 16))
+        T = int(rs.randint(2, 17))
+        K = int(rs.randint(1, T)) if T > 2 else 1
+        B_, p, d = float(rs.choice([16, 64, 256])), float(rs.choice([1.0, 0.1, 0.01])), float(rs.randint(0, 512))
+        assert g.lsm_policy_levels(N, M, T) == oracle.levels(N, M, T)
+        assert g.lsm_policy_cost(w, s, r, z, N, M, T, K, B_, p, d) == oracle.cost(w, s, r, z, N, M, T, K, B_, p, d)
+        assert g.lsm_policy_choose(w, s, r, z, N, M, 2, 16, B_, p, d) == oracle.policy_choose(w, s, r, z, N, M, 2, 16, B_, p, d)
+    for T in (2, 10):
+        for e in range(1, 15):
+            assert g.lsm_policy_levels(T ** e, 1, T) == e and g.lsm_policy_levels(T ** e + 1, 1, T) == e + 1
+    assert g.lsm_policy_choose(1, 0, 0, 0, 400_000_000, 3600, 10, 10, 64.0, 1.0, 64.0) == (10, 9)
+    assert g.lsm_policy_choose(0, 0.3, 0.3, 0.4, 400_000_000, 3600, 10, 10, 64.0, 1.0, 64.0) == (10, 1)
+    with pytest.raises(g.LsmError):
+        g.lsm_policy_choose(1, 0, 0, 0, 10, 0, 2, 4, 64.0, 1.0, 0.0)
