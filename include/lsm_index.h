@@ -151,6 +151,21 @@ typedef struct {
 int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                 size_t workspace_bytes, void* stream);
 
+/*
+ * lsm_compact_timed -- lsm_compact with optional timing hooks: the three HIP events (hipEvent_t
+ * handles owned by the caller, any of them may be NULL) are recorded on `stream` before the
+ * partition kernel, before the tile-merge kernel and after it, so a caller can measure the
+ * kernels of one call with hipEventElapsedTime.  ev == NULL is exactly lsm_compact.
+ */
+typedef struct {
+    void* before_partition;
+    void* before_merge;
+    void* after_merge;
+} lsm_compact_events_t;
+
+int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                      size_t workspace_bytes, void* stream, const lsm_compact_events_t* ev);
+
 /* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments. */
 size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
 

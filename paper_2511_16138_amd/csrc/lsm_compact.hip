@@ -402,7 +402,12 @@ extern "C" size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t
 }
 
 extern "C" int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
-                           size_t workspace_bytes, void* stream_v) {
+                           size_t workspace_bytes, void* stream) {
+    return lsm_compact_timed(runs, n_runs, flags, out, workspace, workspace_bytes, stream, nullptr);
+}
+
+extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                                 size_t workspace_bytes, void* stream_v, const lsm_compact_events_t* ev) {
     using namespace lsm;
     if (runs == nullptr || out == nullptr || out->n_out == nullptr) return LSM_ERR_NULL;
     if (n_runs == 0 || n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
@@ -447,14 +452,20 @@ extern "C" int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flag
         if (vs & 1) return LSM_ERR_UNSORTED;
         if (vs & 2) return LSM_ERR_BAD_ENTRY;
     }
+    if (ev && ev->before_partition && hipEventRecord(static_cast<hipEvent_t>(ev->before_partition), stream) != hipSuccess)
+        return LSM_ERR_HIP;
     if (n_tiles > 1) {
         uint32_t waves_per_block = 256 / kWave;
         uint32_t blocks = (uint32_t)((n_tiles - 1 + waves_per_block - 1) / waves_per_block);
         hipLaunchKernelGGL(partition_kernel, dim3(blocks), dim3(256), 0, stream, rt, ws, n_tiles);
     }
+    if (ev && ev->before_merge && hipEventRecord(static_cast<hipEvent_t>(ev->before_merge), stream) != hipSuccess)
+        return LSM_ERR_HIP;
     if (n_tiles > 0)
         hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
                            out->entries, out->n_out);
+    if (ev && ev->after_merge && hipEventRecord(static_cast<hipEvent_t>(ev->after_merge), stream) != hipSuccess)
+        return LSM_ERR_HIP;
     if (hipGetLastError() != hipSuccess) return LSM_ERR_HIP;
     if (flags & LSM_VALIDATE) {
         uint64_t n = 0;
