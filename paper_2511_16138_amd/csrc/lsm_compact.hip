@@ -9,23 +9,24 @@
 //                     the k lower bounds.  Boundaries are therefore key-aligned (all versions
 //                     of a key fall into the same tile) and tile sizes are within k of the
 //                     nominal size.
-//   merge_kernel      one workgroup per tile: stage the tile's entries in LDS, merge the k
-//                     sorted pieces by ceil(log2 k) rounds of stable two-way merge-path merges
-//                     over 16-bit indices, mark the newest version of every key, drop the rest
-//                     (and winning tombstones when the output is the last level), compact the
-//                     survivors with a block prefix sum, obtain the tile's output offset by a
-//                     decoupled look-back over the tile status words, and copy the survivors
-//                     out with coalesced 16-byte stores.  Every input byte is read once and
-//                     every surviving byte written once.
+//   merge_kernel      one workgroup per tile: every thread loads its share of the tile's entries
+//                     into registers, 16-byte surrogates (14 key bytes + index) are merged in LDS
+//                     by ceil(log2 k) rounds of stable two-way merge-path merges, the newest
+//                     version of every key is marked, the rest (and winning tombstones when the
+//                     output is the last level) dropped, survivors are counted with a block
+//                     prefix sum, the tile's output offset comes from a decoupled look-back over
+//                     the tile status words, and the survivors leave through an LDS stage with
+//                     contiguous 16-byte stores.  Every input byte is read once and every
+//                     surviving byte written once.
 #include <hip/hip_runtime.h>
 
 #include "lsm_common.h"
 
 namespace lsm {
 
-constexpr int kMergeThreads = 256;
+constexpr int kMergeThreads = 512;
 constexpr int kMergeItems = 4;
-constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries staged in LDS per tile
+constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
 constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
 
@@ -108,26 +109,60 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
 
 // ---------------------------------------------------------------------------------------
 // Tile merge.
+//
+// Every thread owns kMergeItems entries of the tile and keeps their 64 bytes in registers
+// from the load to the final store.  What moves through LDS during the merge rounds is one
+// 16-byte "surrogate" per entry: the first 14 key bytes (as a 112-bit big-endian number) and
+// the entry's tile-local index in the low 16 bits.  Surrogates are merged with stable
+// two-way merge-path merges (the left list = lower run indices wins ties).  Afterwards each
+// merged position gets the rest of its key (bytes 14..31), its seqno and its type, so that
+// neighbours can be compared exactly: equal surrogates with different key tails mean the
+// 14-byte order was not enough, and the tile is redone by the exact path below (ranks by
+// binary search over the tile's pieces in global memory with full 32-byte compares).
 // ---------------------------------------------------------------------------------------
+enum : uint8_t { kFlagEq = 1, kFlagFullEq = 2, kFlagSurvive = 4 };
+constexpr int kStageEntries = kTileCap / 2;  // output staging: 64 bytes per survivor, two passes at most
+
 struct MergeShared {
-    uint4 ent[kTileCap][4];      // staged entries, 64 bytes each
-    uint16_t ord[2][kTileCap];   // ping-pong index lists; later ord[x] = survivor list
-    uint8_t same[kTileCap + 1];  // same[i] = key at merged position i equals key at i-1
+    uint4 buf[2][kTileCap];          // surrogate ping-pong; then 2 x uint4 of key tail/seqno/type per position; then output staging
+    uint16_t rank[kTileCap];         // tile-local entry index -> merged position
+    uint16_t prefix[kTileCap];       // survivors before this merged position
+    uint8_t flag[kTileCap + 8];      // per merged position: kFlagEq | kFlagFullEq | kFlagSurvive
     uint32_t seg[LSM_MAX_RUNS + 1];  // start of each run's piece in tile-local index space
     uint64_t lo[LSM_MAX_RUNS];       // first entry of each run's piece
     uint32_t wave_count[kMergeThreads / kWave];
     uint32_t tile;
     uint32_t n;
-    uint64_t base;
     uint32_t failed;
+    uint32_t inexact;                // some position has an equal surrogate but a different key tail
+    uint64_t base;
 };
 
-__device__ __forceinline__ Key lds_key(const MergeShared& s, uint32_t e) { return key_from_raw(s.ent[e][0], s.ent[e][1]); }
-__device__ __forceinline__ uint64_t lds_seqno(const MergeShared& s, uint32_t e) {
-    uint4 v = s.ent[e][2];
-    return ((uint64_t)v.y << 32) | v.x;
+struct Sur {  // hi = key bytes 0..7, lo = key bytes 8..13 << 16 | index
+    uint64_t hi, lo;
+};
+__device__ __forceinline__ Sur sur_load(const uint4* p) {
+    uint4 v = *p;
+    Sur r;
+    r.hi = ((uint64_t)v.y << 32) | v.x;
+    r.lo = ((uint64_t)v.w << 32) | v.z;
+    return r;
 }
-__device__ __forceinline__ uint32_t lds_type(const MergeShared& s, uint32_t e) { return s.ent[e][2].z & 0xFF; }
+__device__ __forceinline__ void sur_store(uint4* p, const Sur& v) {
+    *p = make_uint4((uint32_t)v.hi, (uint32_t)(v.hi >> 32), (uint32_t)v.lo, (uint32_t)(v.lo >> 32));
+}
+// key part of a <= key part of b (the index bits never decide)
+__device__ __forceinline__ bool sur_le(const Sur& a, const Sur& b) {
+    return a.hi < b.hi || (a.hi == b.hi && (a.lo >> 16) <= (b.lo >> 16));
+}
+__device__ __forceinline__ bool sur_same_key(const Sur& a, const Sur& b) { return a.hi == b.hi && ((a.lo ^ b.lo) >> 16) == 0; }
+
+__device__ __forceinline__ uint32_t piece_of(const uint32_t* seg, uint32_t k, uint32_t e) {
+    uint32_t j = 0;  // last j with seg[j] <= e (empty pieces share an offset with their successor)
+    for (uint32_t step = 32; step > 0; step >>= 1)
+        if (j + step < k && seg[j + step] <= e) j += step;
+    return j;
+}
 
 // Publish this tile's survivor count and return the number of survivors in all earlier tiles
 // (decoupled look-back).  Called by wave 0 only, all 64 lanes.  Tiles take their numbers from
@@ -196,7 +231,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     if (tid < (int)k) {
         uint64_t a = ws.splits[tile * k + tid], b = ws.splits[(tile + 1) * k + tid];
         s.lo[tid] = a;
-        s.seg[tid + 1] = (uint32_t)(b >= a ? b - a : 0);
+        s.seg[tid + 1] = (uint32_t)(b >= a && b - a <= (uint64_t)kTileCap ? b - a : kTileCap + 1);
     }
     __syncthreads();
     if (tid == 0) {
@@ -205,7 +240,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         bool ok = true;
         for (uint32_t j = 0; j < k; j++) {
             uint32_t len = s.seg[j + 1];
-            if (len > (uint32_t)kTileCap || s.lo[j] + len > rt.n[j]) {
+            if (len > (uint32_t)kTileCap || s.lo[j] + len > rt.n[j]) {  // only inputs that break the precondition
                 ok = false;
                 len = 0;
             }
@@ -215,131 +250,205 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         if (acc > (uint32_t)kTileCap) ok = false;
         s.n = ok ? acc : 0;
         s.failed = ok ? 0 : 1;
+        s.inexact = 0;
     }
     __syncthreads();
     const uint32_t n = s.n;
 
-    // ---- stage the tile in LDS: 4 lanes per entry, 16 bytes each, coalesced
-    for (uint32_t c = tid; c < n * 4; c += kMergeThreads) {
-        uint32_t e = c >> 2, part = c & 3;
-        uint32_t j = 0;
-        for (uint32_t step = 32; step > 0; step >>= 1)  // last j with seg[j] <= e
-            if (j + step < k && s.seg[j + step] <= e) j += step;
-        while (j + 1 < k && s.seg[j + 1] <= e) j++;  // skip empty pieces that start at the same offset
-        const uint4* src = reinterpret_cast<const uint4*>(rt.ptr[j] + s.lo[j] + (e - s.seg[j]));
-        s.ent[e][part] = src[part];
+    // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
+    uint4 ent[kMergeItems][4];
+    uint32_t pos[kMergeItems];  // merged position of the entry
+#pragma unroll
+    for (int i = 0; i < kMergeItems; i++) {
+        const uint32_t e = tid + i * kMergeThreads;
+        pos[i] = 0;
+        if (e < n) {
+            const uint32_t j = piece_of(s.seg, k, e);
+            const uint4* src = reinterpret_cast<const uint4*>(rt.ptr[j] + s.lo[j] + (e - s.seg[j]));
+#pragma unroll
+            for (int part = 0; part < 4; part++) ent[i][part] = src[part];
+        } else {
+#pragma unroll
+            for (int part = 0; part < 4; part++) ent[i][part] = make_uint4(0, 0, 0, 0);
+        }
     }
-    for (uint32_t e = tid; e < n; e += kMergeThreads) s.ord[0][e] = (uint16_t)e;
+#pragma unroll
+    for (int i = 0; i < kMergeItems; i++) {
+        const uint32_t e = tid + i * kMergeThreads;
+        if (e < n) {
+            Key kk = key_from_raw(ent[i][0], ent[i][1]);
+            Sur v;
+            v.hi = kk.w[0];
+            v.lo = (kk.w[1] & ~0xFFFFull) | e;
+            sur_store(&s.buf[0][e], v);
+        }
+    }
+    if (tid == 0) s.flag[n] = 0;
     __syncthreads();
 
     // ---- merge rounds: lists of `width` runs each are merged pairwise, stable (left list first)
     int cur = 0;
     for (uint32_t width = 1; width < k; width <<= 1) {
-        const uint16_t* in = s.ord[cur];
-        uint16_t* dst = s.ord[cur ^ 1];
+        const uint4* in = s.buf[cur];
+        uint4* dst = s.buf[cur ^ 1];
         uint32_t o = tid * kMergeItems;
         const uint32_t o_end = min(o + (uint32_t)kMergeItems, n);
         while (o < o_end) {
             // the pair of lists whose output range contains position o
-            uint32_t j = 0;
-            for (uint32_t step = 32; step > 0; step >>= 1)
-                if (j + step < k && s.seg[j + step] <= o) j += step;
-            while (j + 1 < k && s.seg[j + 1] <= o) j++;
-            uint32_t pair = j / (2 * width);
-            uint32_t ra = pair * 2 * width, rb = min(ra + width, k), rc = min(ra + 2 * width, k);
-            uint32_t sa = s.seg[ra], sb = s.seg[rb], sc = s.seg[rc];
-            uint32_t len_a = sb - sa, len_b = sc - sb;
-            uint32_t stop = min(o_end, sc);
+            const uint32_t j = piece_of(s.seg, k, o);
+            const uint32_t ra = (j / (2 * width)) * 2 * width, rb = min(ra + width, k), rc = min(ra + 2 * width, k);
+            const uint32_t sa = s.seg[ra], sb = s.seg[rb], sc = s.seg[rc];
+            const uint32_t len_a = sb - sa, len_b = sc - sb;
+            const uint32_t stop = min(o_end, sc);
             // co-rank of diagonal d: how many of the first d outputs come from the left list
-            uint32_t d = o - sa;
+            const uint32_t d = o - sa;
             uint32_t lo = d > len_b ? d - len_b : 0, hi = min(d, len_a);
             while (lo < hi) {
-                uint32_t mid = (lo + hi) >> 1;
-                Key ka = lds_key(s, in[sa + mid]);
-                Key kb = lds_key(s, in[sb + (d - 1 - mid)]);
-                if (key_less_equal(ka, kb)) lo = mid + 1;
+                const uint32_t mid = (lo + hi) >> 1;
+                if (sur_le(sur_load(&in[sa + mid]), sur_load(&in[sb + (d - 1 - mid)]))) lo = mid + 1;
                 else hi = mid;
             }
             uint32_t a = lo, b = d - lo;
-            uint32_t ia = a < len_a ? in[sa + a] : 0, ib = b < len_b ? in[sb + b] : 0;
-            Key ka = lds_key(s, ia), kb = lds_key(s, ib);
+            Sur va = sur_load(&in[a < len_a ? sa + a : sa]), vb = sur_load(&in[b < len_b ? sb + b : sa]);
             for (; o < stop; o++) {
-                bool take_a = b >= len_b || (a < len_a && key_less_equal(ka, kb));
-                dst[o] = (uint16_t)(take_a ? ia : ib);
+                const bool take_a = b >= len_b || (a < len_a && sur_le(va, vb));
+                sur_store(&dst[o], take_a ? va : vb);
                 if (take_a) {
                     a++;
-                    ia = a < len_a ? in[sa + a] : 0;
-                    ka = lds_key(s, ia);
+                    va = sur_load(&in[a < len_a ? sa + a : sa]);
                 } else {
                     b++;
-                    ib = b < len_b ? in[sb + b] : 0;
-                    kb = lds_key(s, ib);
+                    vb = sur_load(&in[b < len_b ? sb + b : sa]);
                 }
             }
         }
         __syncthreads();
         cur ^= 1;
     }
-    const uint16_t* ord = s.ord[cur];
-    uint16_t* surv = s.ord[cur ^ 1];
 
-    // ---- same[i]: merged position i repeats the key of position i-1
+    // ---- merged position p <-> entry index; does p repeat the 14-byte key prefix of p-1?
     {
-        uint32_t o = tid * kMergeItems;
-        const uint32_t o_end = min(o + (uint32_t)kMergeItems, n);
-        if (o < o_end) {
-            Key prev = lds_key(s, ord[o > 0 ? o - 1 : 0]);
-            for (; o < o_end; o++) {
-                Key kk = lds_key(s, ord[o]);
-                s.same[o] = (o > 0 && key_equal(prev, kk)) ? 1 : 0;
-                prev = kk;
+        const uint4* fin = s.buf[cur];
+        const uint32_t o0 = tid * kMergeItems;
+        if (o0 < n) {
+            Sur prev = sur_load(&fin[o0 > 0 ? o0 - 1 : 0]);
+            for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
+                Sur v = sur_load(&fin[o]);
+                s.flag[o] = (o > 0 && sur_same_key(prev, v)) ? kFlagEq : 0;
+                s.rank[v.lo & 0xFFFF] = (uint16_t)o;
+                prev = v;
             }
         }
-        if (tid == 0) s.same[n] = 0;
     }
     __syncthreads();
 
-    // ---- survivors: newest version of each key (largest seqno, ties to the earlier = lower run),
-    //      minus winning tombstones when the output is the last level
-    uint32_t keep_mask = 0, my_count = 0;
+    // ---- every owner posts key bytes 14..31, seqno and type of its entries at their merged positions
+    uint4* info = &s.buf[0][0];  // info[2p] = {seqno lo, seqno hi, type | bytes 14..15 << 8, 0}, info[2p+1] = key bytes 16..31
+#pragma unroll
+    for (int i = 0; i < kMergeItems; i++) {
+        const uint32_t e = tid + i * kMergeThreads;
+        if (e < n) {
+            const uint32_t p = s.rank[e];
+            pos[i] = p;
+            info[2 * p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, 0);
+            info[2 * p + 1] = ent[i][1];
+        }
+    }
+    __syncthreads();
+
+    // ---- exact equality with the previous position; a differing tail under an equal prefix makes the tile inexact
     {
         const uint32_t o0 = tid * kMergeItems;
-        for (uint32_t i = 0; i < (uint32_t)kMergeItems; i++) {
-            uint32_t o = o0 + i;
-            if (o >= n) break;
-            uint32_t e = ord[o];
-            uint64_t seq = lds_seqno(s, e);
+        bool inexact = false;
+        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
+            if (s.flag[o] & kFlagEq) {
+                uint4 a0 = info[2 * o], a1 = info[2 * o + 1], b0 = info[2 * o - 2], b1 = info[2 * o - 1];
+                bool same = ((a0.z ^ b0.z) >> 8) == 0 && a1.x == b1.x && a1.y == b1.y && a1.z == b1.z && a1.w == b1.w;
+                if (same) s.flag[o] = kFlagEq | kFlagFullEq;
+                else inexact = true;
+            }
+        }
+        if (inexact) s.inexact = 1;
+    }
+    __syncthreads();
+
+    if (s.inexact == 0) {
+        // ---- survivors: newest version of each key (largest seqno, ties to the earlier = lower run),
+        //      minus winning tombstones when the output is the last level
+        const uint32_t o0 = tid * kMergeItems;
+        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
+            const uint4 me = info[2 * o];
+            const uint64_t seq = ((uint64_t)me.y << 32) | me.x;
             bool win = true;
-            for (uint32_t p = o; s.same[p]; p--)  // earlier members of the group (same[0] is 0)
-                if (lds_seqno(s, ord[p - 1]) >= seq) win = false;
-            for (uint32_t p = o + 1; s.same[p]; p++)  // later members (same[n] is 0)
-                if (lds_seqno(s, ord[p]) > seq) win = false;
-            if (win && (flags & LSM_BOTTOMMOST) && lds_type(s, e) == LSM_TOMBSTONE) win = false;
-            if (win) {
-                keep_mask |= 1u << i;
-                my_count++;
+            for (uint32_t p = o; s.flag[p] & kFlagFullEq; p--) {  // earlier members of the group (flag[0] has no Eq bit)
+                const uint4 v = info[2 * p - 2];
+                if ((((uint64_t)v.y << 32) | v.x) >= seq) win = false;
+            }
+            for (uint32_t p = o + 1; s.flag[p] & kFlagFullEq; p++) {  // later members (flag[n] is 0)
+                const uint4 v = info[2 * p];
+                if ((((uint64_t)v.y << 32) | v.x) > seq) win = false;
+            }
+            if (win && (flags & LSM_BOTTOMMOST) && (me.z & 0xFF) == LSM_TOMBSTONE) win = false;
+            if (win) s.flag[o] |= kFlagSurvive;
+        }
+    } else {
+        // ---- exact path: merged position and winner of every entry by binary search over the
+        //      tile's pieces in global memory, full 32-byte compares, order (key, run index)
+        __syncthreads();
+        for (uint32_t o = tid; o <= n; o += kMergeThreads) s.flag[o] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < kMergeItems; i++) {
+            const uint32_t e = tid + i * kMergeThreads;
+            if (e < n) {
+                const uint32_t j = piece_of(s.seg, k, e);
+                const Key x = key_from_raw(ent[i][0], ent[i][1]);
+                const uint64_t seq = ((uint64_t)ent[i][2].y << 32) | ent[i][2].x;
+                uint32_t p = e - s.seg[j];
+                bool win = true;
+                for (uint32_t j2 = 0; j2 < k; j2++) {
+                    if (j2 == j) continue;
+                    const lsm_entry_t* run = rt.ptr[j2];
+                    const uint64_t first = s.lo[j2], last = first + (s.seg[j2 + 1] - s.seg[j2]);
+                    const uint64_t lb = lower_bound_run(run, first, last, x);
+                    p += (uint32_t)(lb - first);
+                    if (lb < last && key_equal(load_key(run + lb), x)) {
+                        const uint64_t other = run[lb].seqno;
+                        if (other > seq || (other == seq && j2 < j)) win = false;
+                        if (j2 < j) p++;
+                    }
+                }
+                if (win && (flags & LSM_BOTTOMMOST) && (ent[i][2].z & 0xFF) == LSM_TOMBSTONE) win = false;
+                pos[i] = p;
+                if (win) s.flag[p] = kFlagSurvive;
             }
         }
     }
-    // block-wide exclusive prefix of my_count
-    uint32_t incl = my_count;
-    for (int off = 1; off < kWave; off <<= 1) {
-        uint32_t v = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += v;
-    }
-    if (lane == kWave - 1) s.wave_count[wave] = incl;
     __syncthreads();
-    uint32_t wave_base = 0, total = 0;
-    for (int w = 0; w < kMergeThreads / kWave; w++) {
-        uint32_t c = s.wave_count[w];
-        if (w < wave) wave_base += c;
-        total += c;
-    }
+
+    // ---- survivors before each merged position (block-wide exclusive prefix sum in position order)
+    uint32_t total = 0;
     {
-        uint32_t pos = wave_base + incl - my_count;
         const uint32_t o0 = tid * kMergeItems;
-        for (uint32_t i = 0; i < (uint32_t)kMergeItems; i++)
-            if (keep_mask & (1u << i)) surv[pos++] = ord[o0 + i];
+        uint32_t my_count = 0;
+        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) my_count += (s.flag[o] & kFlagSurvive) ? 1 : 0;
+        uint32_t incl = my_count;
+        for (int off = 1; off < kWave; off <<= 1) {
+            uint32_t v = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += v;
+        }
+        if (lane == kWave - 1) s.wave_count[wave] = incl;
+        __syncthreads();
+        uint32_t before = incl - my_count;
+        for (int w = 0; w < kMergeThreads / kWave; w++) {
+            const uint32_t c = s.wave_count[w];
+            if (w < wave) before += c;
+            total += c;
+        }
+        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
+            s.prefix[o] = (uint16_t)before;
+            before += (s.flag[o] & kFlagSurvive) ? 1 : 0;
+        }
     }
 
     // ---- output offset of this tile
@@ -351,15 +460,32 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
             if (failed) s.failed = 1;
         }
     }
-    __syncthreads();
+    __syncthreads();  // also orders prefix[] and the last reads of info[] before the staging writes below
     const bool failed = s.failed != 0;
     const uint64_t base = s.base;
     if (tile == n_tiles - 1 && tid == 0) *n_out = failed ? ~0ull : base + total;
     if (failed) return;
 
-    // ---- copy survivors out: 4 lanes per entry, 16 bytes each
-    uint4* dst = reinterpret_cast<uint4*>(out + base);
-    for (uint32_t c = tid; c < total * 4; c += kMergeThreads) dst[c] = s.ent[surv[c >> 2]][c & 3];
+    // ---- survivors leave through an LDS stage so that the global stores are contiguous
+    uint4* stage = &s.buf[0][0];
+    for (uint32_t first = 0; first < total; first += kStageEntries) {
+#pragma unroll
+        for (int i = 0; i < kMergeItems; i++) {
+            const uint32_t e = tid + i * kMergeThreads;
+            if (e < n && (s.flag[pos[i]] & kFlagSurvive)) {
+                const uint32_t slot = (uint32_t)s.prefix[pos[i]] - first;  // wraps for slots before this pass
+                if (slot < (uint32_t)kStageEntries) {
+#pragma unroll
+                    for (int part = 0; part < 4; part++) stage[slot * 4 + part] = ent[i][part];
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t count = min(total - first, (uint32_t)kStageEntries);
+        uint4* dst = reinterpret_cast<uint4*>(out + base + first);
+        for (uint32_t c = tid; c < count * 4; c += kMergeThreads) dst[c] = stage[c];
+        __syncthreads();
+    }
 }
 
 // ---------------------------------------------------------------------------------------
