@@ -44,11 +44,26 @@ __device__ __forceinline__ bool key_equal(const Key& a, const Key& b) {
 
 __device__ __forceinline__ bool key_less_equal(const Key& a, const Key& b) { return !key_less(b, a); }
 
+// key of entry e < k, reading the second half of e's key only when the first 16 bytes tie
+__device__ __forceinline__ bool entry_key_less(const lsm_entry_t* e, const Key& k) {
+    const uint4* q = reinterpret_cast<const uint4*>(e);
+    const uint4 lo = q[0];
+    const uint64_t w0 = __builtin_bswap64(((uint64_t)lo.y << 32) | lo.x);
+    const uint64_t w1 = __builtin_bswap64(((uint64_t)lo.w << 32) | lo.z);
+    if (w0 != k.w[0]) return w0 < k.w[0];
+    if (w1 != k.w[1]) return w1 < k.w[1];
+    const uint4 hi = q[1];
+    const uint64_t w2 = __builtin_bswap64(((uint64_t)hi.y << 32) | hi.x);
+    const uint64_t w3 = __builtin_bswap64(((uint64_t)hi.w << 32) | hi.z);
+    if (w2 != k.w[2]) return w2 < k.w[2];
+    return w3 < k.w[3];
+}
+
 // Number of entries of run[lo, hi) whose key is < k, plus lo.  Global memory.
 __device__ __forceinline__ uint64_t lower_bound_run(const lsm_entry_t* run, uint64_t lo, uint64_t hi, const Key& k) {
     while (lo < hi) {
         uint64_t mid = lo + ((hi - lo) >> 1);
-        if (key_less(load_key(run + mid), k)) lo = mid + 1;
+        if (entry_key_less(run + mid, k)) lo = mid + 1;
         else hi = mid;
     }
     return lo;

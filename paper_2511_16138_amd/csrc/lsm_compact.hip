@@ -3,8 +3,8 @@
 // Three kernels on one stream:
 //   init_kernel       clears the per-call scratch (ticket, tile status words) and writes the
 //                     first and last partition rows.
-//   partition_kernel  one wave per interior tile boundary: multi-sequence selection over the
-//                     k runs.  For target rank r it finds the key x with the largest
+//   partition_kernel  one group of lanes per interior tile boundary: multi-sequence selection
+//                     over the k runs.  For target rank r it finds the key x with the largest
 //                     L(x) = sum_j |{e in run j : e.key < x}| that is still <= r, and stores
 //                     the k lower bounds.  Boundaries are therefore key-aligned (all versions
 //                     of a key fall into the same tile) and tile sizes are within k of the
@@ -28,6 +28,7 @@ constexpr int kMergeThreads = 512;
 constexpr int kMergeItems = 4;
 constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
 constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
+constexpr uint64_t kCoarseStride = 32;                 // every 32nd boundary is searched over whole runs first
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
 
 // Tile status word: top two bits = state, low 62 bits = value.
@@ -66,45 +67,101 @@ __global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_
 }
 
 // ---------------------------------------------------------------------------------------
-// Partition: lane j of a wave owns run j.  Candidates for x are the entries still inside
-// [lo_j, hi_j) of every run; each step takes the middle entry of the widest range as pivot,
-// every lane finds the pivot's lower bound in its own range, and the sum decides which side
-// of the pivot survives.  The pivot itself always leaves its range, so the loop ends.
+// Partition: a group of G lanes (G = smallest power of two >= k) works on one boundary, lane
+// j of the group owns run j, and a wave handles 64/G boundaries at once.  Candidates for x are
+// the entries still inside [lo_j, hi_j) of every run; each step takes the middle entry of the
+// widest range as pivot, every lane finds the pivot's lower bound in its own range, and the
+// sum over the group decides which side of the pivot survives.  The pivot always leaves its
+// range and the widest range at least halves, so the loop ends after at most
+// k * log2(longest run) steps whatever the input.
 // ---------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles) {
+__device__ __forceinline__ uint64_t group_sum_u64(uint64_t v, int group) {
+    for (int off = group >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+__device__ __forceinline__ uint64_t group_max_u64(uint64_t v, int group) {
+    for (int off = group >> 1; off > 0; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// The kernel runs twice: first for the boundaries that are multiples of `coarse` (search over
+// whole runs), then for the others, whose search starts from the enclosing coarse boundaries
+// (splits are monotone in the boundary number, so those are valid bounds).
+__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group,
+                                                         uint64_t coarse, int fine_pass) {
     const int lane = threadIdx.x & (kWave - 1);
-    const uint64_t b = (uint64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave + 1;  // boundary 1..n_tiles-1
-    if (b >= n_tiles) return;  // whole wave leaves together
+    const int member = lane & (group - 1);   // run owned by this lane
+    const int group_base = lane - member;
+    const uint64_t wave_id = (uint64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    const uint64_t slot = wave_id * (uint64_t)(kWave / group) + (uint64_t)(lane / group);
+    // coarse pass: b = coarse, 2*coarse, ...; fine pass: every b in 1..n_tiles-1 that is not a multiple of coarse
+    const uint64_t b = fine_pass ? slot + slot / (coarse - 1) + 1 : (slot + 1) * coarse;
+    const bool valid = b < n_tiles;
     const uint64_t r = b * (uint64_t)kTileNominal;
-    const bool own = lane < (int)rt.k;
-    const lsm_entry_t* run = own ? rt.ptr[lane] : nullptr;
-    uint64_t lo = 0, hi = own ? rt.n[lane] : 0, best = 0;
-    for (;;) {
-        uint64_t width = hi - lo;
-        uint64_t widest = wave_max_u64((width << 6) | (uint64_t)lane);
-        if ((widest >> 6) == 0) break;
-        int src = (int)(widest & 63);
+    const bool own = valid && member < (int)rt.k;
+    const lsm_entry_t* run = own ? rt.ptr[member] : nullptr;
+    uint64_t lo = 0, hi = own ? rt.n[member] : 0, best = 0;
+    if (fine_pass && own) {
+        const uint64_t below = b - b % coarse, above = below + coarse < n_tiles ? below + coarse : n_tiles;
+        lo = best = ws.splits[below * rt.k + member];
+        hi = ws.splits[above * rt.k + member];
+        if (hi > rt.n[member]) hi = rt.n[member];  // only inputs that break the precondition
+        if (lo > hi) lo = best = hi;
+    }
+    for (uint32_t iter = 0;; iter++) {
+        const uint64_t width = hi - lo;
+        const uint64_t widest = group_max_u64((width << 6) | (uint64_t)member, group);
+        const bool active = (widest >> 6) != 0;
+        if (__ballot(active) == 0) break;
+        const int src = (int)(widest & 63);
         uint64_t mid = lo + (width >> 1);
+        if (iter % 3 != 2) {
+            // interpolation steps: the candidates are the merged ranks [sum lo, sum hi); aim the pivot at
+            // the same fraction of the widest range as a target rank is of that interval.  The target
+            // is r minus, then r plus, about two standard deviations of the estimate (2 * sqrt of the
+            // interval), so that two steps bracket x from both sides.  Every third step stays at the
+            // middle of the widest range, which keeps the worst case logarithmic.
+            const uint64_t rank_lo = group_sum_u64(own ? lo : 0, group), rank_hi = group_sum_u64(own ? hi : 0, group);
+            uint64_t span = rank_hi - rank_lo, ahead = r > rank_lo ? r - rank_lo : 0;
+            const uint64_t margin = span ? 2ull << ((64 - __builtin_clzll(span)) >> 1) : 0;
+            if (iter % 3 == 0) ahead = ahead > margin ? ahead - margin : 0;
+            else ahead += margin;
+            if (ahead > span) ahead = span;
+            const int shift = span >> 31 ? 64 - __builtin_clzll(span) - 31 : 0;
+            span >>= shift;
+            ahead >>= shift;
+            uint64_t frac = span ? (ahead << 32) / span : 0;  // 32.32 fixed point in [0, 1]
+            if (frac > 0xFFFFFFFFull) frac = 0xFFFFFFFFull;
+            if (rank_hi - rank_lo >= 256 && width > 0 && width <= 0xFFFFFFFFull) {  // few candidates left: plain bisection
+                mid = lo + ((width * frac) >> 32);
+                if (mid >= hi) mid = hi - 1;
+            }
+        }
         Key pivot = {{0, 0, 0, 0}};
-        if (lane == src) pivot = load_key(run + mid);
-        for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], src, kWave);
+        if (active && member == src) pivot = load_key(run + mid);
+        for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], group_base + src, kWave);
         uint64_t lb = lo, ub = lo;
-        if (own) {
+        if (own && active) {
             lb = lower_bound_run(run, lo, hi, pivot);
             ub = lb;
             if (lb < hi && key_equal(load_key(run + lb), pivot)) ub = lb + 1;
         }
-        uint64_t total = wave_sum_u64(own ? lb : 0);
-        // on sorted input the pivot's own lane has lb == mid; the clamps only matter for
-        // inputs that break the precondition, where they still halve the widest range
-        if (total <= r) {
-            best = lb;
-            lo = (lane == src && ub < mid + 1) ? mid + 1 : ub;
-        } else {
-            hi = (lane == src && lb > mid) ? mid : lb;
+        const uint64_t total = group_sum_u64(own ? lb : 0, group);
+        if (active) {
+            // on sorted input the pivot's own lane has lb == mid; the clamps only matter for
+            // inputs that break the precondition, where they still halve the widest range
+            if (total <= r) {
+                best = lb;
+                lo = (member == src && ub < mid + 1) ? mid + 1 : ub;
+            } else {
+                hi = (member == src && lb > mid) ? mid : lb;
+            }
         }
     }
-    if (own) ws.splits[b * rt.k + lane] = best;
+    if (own) ws.splits[b * rt.k + member] = best;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -581,9 +638,18 @@ extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_
     if (ev && ev->before_partition && hipEventRecord(static_cast<hipEvent_t>(ev->before_partition), stream) != hipSuccess)
         return LSM_ERR_HIP;
     if (n_tiles > 1) {
-        uint32_t waves_per_block = 256 / kWave;
-        uint32_t blocks = (uint32_t)((n_tiles - 1 + waves_per_block - 1) / waves_per_block);
-        hipLaunchKernelGGL(partition_kernel, dim3(blocks), dim3(256), 0, stream, rt, ws, n_tiles);
+        int group = 1;
+        while (group < (int)n_runs) group <<= 1;
+        const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);  // boundaries per workgroup
+        const uint64_t coarse = kCoarseStride;
+        const uint64_t n_coarse = (n_tiles - 1) / coarse;  // boundaries coarse, 2*coarse, ... < n_tiles
+        const uint64_t n_fine = (n_tiles - 1) - n_coarse;
+        if (n_coarse > 0)
+            hipLaunchKernelGGL(partition_kernel, dim3((uint32_t)((n_coarse + per_block - 1) / per_block)), dim3(256), 0, stream,
+                               rt, ws, n_tiles, group, coarse, 0);
+        if (n_fine > 0)
+            hipLaunchKernelGGL(partition_kernel, dim3((uint32_t)((n_fine + per_block - 1) / per_block)), dim3(256), 0, stream,
+                               rt, ws, n_tiles, group, coarse, 1);
     }
     if (ev && ev->before_merge && hipEventRecord(static_cast<hipEvent_t>(ev->before_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
