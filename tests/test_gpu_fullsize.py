@@ -1,0 +1,74 @@
+"""GPU parity at the full sizes of the configurations, in the launch configuration bench.py times.
+
+The CPU checker is fast enough (tens of millions of entries per second per core on the GPU
+box's host) to merge the full inputs, so compaction outputs are compared entry by entry.
+Probes against the 100M-entry tree are compared on sampled batches.
+"""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import as_bytes, assert_probe_equal, build_tree, compact_gpu, dev, probe_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def g():
+    import paper_2511_16138_amd as lsmgpu
+    lsmgpu.binding._load()
+    return lsmgpu
+
+
+def _full_compare(g, oracle, runs, flags):
+    got = compact_gpu(g, runs, flags)
+    runs_cpu = [oracle.as_run(r.cpu()) for r in runs]
+    want = oracle.compact(runs_cpu, flags & 1)
+    assert got.shape[0] == want.shape[0]
+    got_np = as_bytes(got).reshape(-1, 64)
+    step = 1 << 22
+    for i in range(0, want.shape[0], step):
+        assert np.array_equal(got_np[i:i + step], want[i:i + step]), f"mismatch in rows {i}..{i + step}"
+    return got
+
+
+def test_config2_full_leveled_2m_into_20m(g, oracle):
+    from workloads import lsm
+    print("config2 full", flush=True)
+    w = lsm.config2(device=dev())
+    assert [int(r.shape[0]) for r in w.runs] == [2_000_000, 20_000_000]
+    _full_compare(g, oracle, w.runs, 0)
+
+
+def test_config3_full_tiered_16_way(g, oracle):
+    from workloads import lsm
+    print("config3 full", flush=True)
+    w = lsm.config3(device=dev())
+    assert [int(r.shape[0]) for r in w.runs] == [4_194_304] * 16
+    del w.universe
+    torch.cuda.empty_cache()
+    got = _full_compare(g, oracle, w.runs, 1)
+    ratio = got.shape[0] / (16 * 4_194_304)
+    assert 0.66 < ratio < 0.70  # about 0.95 / 1.4 of the inputs survive
+
+
+def test_config4_full_tree_sampled_probe_batches(g, oracle):
+    """5-level, 100M-entry tree; 3 of the 256 batches of 4,096 requests are checked in full."""
+    from workloads import lsm
+    print("config4 full tree", flush=True)
+    w = lsm.config4(device=dev())
+    assert sum(int(r.shape[0]) for r in w.runs) == 100_000_000 and len(w.runs) == 5
+    tree = build_tree(g, w.runs)
+    runs_cpu = [oracle.as_run(r.cpu()) for r in w.runs]
+    for f, r in zip(tree, runs_cpu):  # fence index of every level, sampled rows
+        got_f = as_bytes(f.fences).reshape(-1, 32)
+        idx = np.unique(np.linspace(0, got_f.shape[0] - 1, 4096).astype(np.int64))
+        assert np.array_equal(got_f[idx], r[idx * 64, :32])
+    for stream in (0, 101, 255):
+        print("  batch", stream, flush=True)
+        q, nb = lsm.queries_config4(w, 4096, stream=stream)
+        got = probe_gpu(g, q, nb, tree)
+        want = oracle.probe(q, nb, runs_cpu)
+        assert_probe_equal(oracle, got, want)
+        miss = float((want[0] == 0).mean())
+        assert 0.25 < miss < 0.45 and want[0].max() >= 32
