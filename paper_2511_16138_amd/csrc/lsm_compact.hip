@@ -187,6 +187,7 @@ struct MergeShared {
     uint8_t flag[kTileCap + 8];      // per merged position: kFlagEq | kFlagFullEq | kFlagSurvive
     uint32_t seg[LSM_MAX_RUNS + 1];  // start of each run's piece in tile-local index space
     uint64_t lo[LSM_MAX_RUNS];       // first entry of each run's piece
+    const lsm_entry_t* run[LSM_MAX_RUNS];  // copy of the run pointers (indexed per lane)
     uint32_t wave_count[kMergeThreads / kWave];
     uint32_t tile;
     uint32_t n;
@@ -288,6 +289,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     if (tid < (int)k) {
         uint64_t a = ws.splits[tile * k + tid], b = ws.splits[(tile + 1) * k + tid];
         s.lo[tid] = a;
+        s.run[tid] = rt.ptr[tid];
         s.seg[tid + 1] = (uint32_t)(b >= a && b - a <= (uint64_t)kTileCap ? b - a : kTileCap + 1);
     }
     __syncthreads();
@@ -321,7 +323,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         pos[i] = 0;
         if (e < n) {
             const uint32_t j = piece_of(s.seg, k, e);
-            const uint4* src = reinterpret_cast<const uint4*>(rt.ptr[j] + s.lo[j] + (e - s.seg[j]));
+            const uint4* src = reinterpret_cast<const uint4*>(s.run[j] + s.lo[j] + (e - s.seg[j]));
 #pragma unroll
             for (int part = 0; part < 4; part++) ent[i][part] = src[part];
         } else {
@@ -400,15 +402,16 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     __syncthreads();
 
     // ---- every owner posts key bytes 14..31, seqno and type of its entries at their merged positions
-    uint4* info = &s.buf[0][0];  // info[2p] = {seqno lo, seqno hi, type | bytes 14..15 << 8, 0}, info[2p+1] = key bytes 16..31
+    uint4* info0 = s.buf[0];  // {seqno lo, seqno hi, type | key bytes 14..15 << 8, 0} of the entry at a position
+    uint4* info1 = s.buf[1];  // its key bytes 16..31
 #pragma unroll
     for (int i = 0; i < kMergeItems; i++) {
         const uint32_t e = tid + i * kMergeThreads;
         if (e < n) {
             const uint32_t p = s.rank[e];
             pos[i] = p;
-            info[2 * p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, 0);
-            info[2 * p + 1] = ent[i][1];
+            info0[p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, 0);
+            info1[p] = ent[i][1];
         }
     }
     __syncthreads();
@@ -419,7 +422,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         bool inexact = false;
         for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
             if (s.flag[o] & kFlagEq) {
-                uint4 a0 = info[2 * o], a1 = info[2 * o + 1], b0 = info[2 * o - 2], b1 = info[2 * o - 1];
+                const uint4 a0 = info0[o], a1 = info1[o], b0 = info0[o - 1], b1 = info1[o - 1];
                 bool same = ((a0.z ^ b0.z) >> 8) == 0 && a1.x == b1.x && a1.y == b1.y && a1.z == b1.z && a1.w == b1.w;
                 if (same) s.flag[o] = kFlagEq | kFlagFullEq;
                 else inexact = true;
@@ -434,15 +437,15 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         //      minus winning tombstones when the output is the last level
         const uint32_t o0 = tid * kMergeItems;
         for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
-            const uint4 me = info[2 * o];
+            const uint4 me = info0[o];
             const uint64_t seq = ((uint64_t)me.y << 32) | me.x;
             bool win = true;
             for (uint32_t p = o; s.flag[p] & kFlagFullEq; p--) {  // earlier members of the group (flag[0] has no Eq bit)
-                const uint4 v = info[2 * p - 2];
+                const uint4 v = info0[p - 1];
                 if ((((uint64_t)v.y << 32) | v.x) >= seq) win = false;
             }
             for (uint32_t p = o + 1; s.flag[p] & kFlagFullEq; p++) {  // later members (flag[n] is 0)
-                const uint4 v = info[2 * p];
+                const uint4 v = info0[p];
                 if ((((uint64_t)v.y << 32) | v.x) > seq) win = false;
             }
             if (win && (flags & LSM_BOTTOMMOST) && (me.z & 0xFF) == LSM_TOMBSTONE) win = false;
@@ -465,7 +468,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
                 bool win = true;
                 for (uint32_t j2 = 0; j2 < k; j2++) {
                     if (j2 == j) continue;
-                    const lsm_entry_t* run = rt.ptr[j2];
+                    const lsm_entry_t* run = s.run[j2];
                     const uint64_t first = s.lo[j2], last = first + (s.seg[j2 + 1] - s.seg[j2]);
                     const uint64_t lb = lower_bound_run(run, first, last, x);
                     p += (uint32_t)(lb - first);
@@ -523,7 +526,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     if (tile == n_tiles - 1 && tid == 0) *n_out = failed ? ~0ull : base + total;
     if (failed) return;
 
-    // ---- survivors leave through an LDS stage so that the global stores are contiguous
+    // ---- survivors leave through an LDS stage so that the global stores are contiguous; the four
+    //      16-byte parts of a slot are rotated by the slot number to spread them over the banks
     uint4* stage = &s.buf[0][0];
     for (uint32_t first = 0; first < total; first += kStageEntries) {
 #pragma unroll
@@ -533,14 +537,14 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
                 const uint32_t slot = (uint32_t)s.prefix[pos[i]] - first;  // wraps for slots before this pass
                 if (slot < (uint32_t)kStageEntries) {
 #pragma unroll
-                    for (int part = 0; part < 4; part++) stage[slot * 4 + part] = ent[i][part];
+                    for (int part = 0; part < 4; part++) stage[slot * 4 + (part ^ (slot & 3))] = ent[i][part];
                 }
             }
         }
         __syncthreads();
         const uint32_t count = min(total - first, (uint32_t)kStageEntries);
         uint4* dst = reinterpret_cast<uint4*>(out + base + first);
-        for (uint32_t c = tid; c < count * 4; c += kMergeThreads) dst[c] = stage[c];
+        for (uint32_t c = tid; c < count * 4; c += kMergeThreads) dst[(c & ~3u) | ((c ^ (c >> 2)) & 3)] = stage[c];
         __syncthreads();
     }
 }
