@@ -82,6 +82,10 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
     return v;
 }
 
+// 16-byte load through a pointer that is known to be global memory (it went through LDS or a
+// table, so the compiler cannot tell): a global instead of a flat load.
+__device__ __forceinline__ uint4 load_global_u4(const uint4* p) { typedef uint32_t v4 __attribute__((ext_vector_type(4))); const v4 v = *(const __attribute__((address_space(1))) v4*)p; return make_uint4(v.x, v.y, v.z, v.w); }
+
 // Run descriptors passed to kernels by value.
 struct RunTable {
     const lsm_entry_t* ptr[LSM_MAX_RUNS];

@@ -215,10 +215,15 @@ __device__ __forceinline__ bool sur_le(const Sur& a, const Sur& b) {
 }
 __device__ __forceinline__ bool sur_same_key(const Sur& a, const Sur& b) { return a.hi == b.hi && ((a.lo ^ b.lo) >> 16) == 0; }
 
-__device__ __forceinline__ uint32_t piece_of(const uint32_t* seg, uint32_t k, uint32_t e) {
-    uint32_t j = 0;  // last j with seg[j] <= e (empty pieces share an offset with their successor)
-    for (uint32_t step = 32; step > 0; step >>= 1)
-        if (j + step < k && seg[j + step] <= e) j += step;
+// Last j < k with seg[j] <= e (empty pieces share an offset with their successor).  Branch-free;
+// top_step = largest power of two below k (0 for k = 1).
+__device__ __forceinline__ uint32_t piece_of(const uint32_t* seg, uint32_t k, uint32_t top_step, uint32_t e) {
+    uint32_t j = 0;
+    for (uint32_t step = top_step; step > 0; step >>= 1) {
+        const uint32_t c = j + step;
+        const uint32_t v = seg[min(c, k - 1)];
+        j = ((c < k) & (v <= e)) ? c : j;
+    }
     return j;
 }
 
@@ -280,6 +285,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
     const uint32_t k = rt.k;
+    const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
     // ---- tile number (ticket order = output order) and its k pieces
     if (tid == 0) s.tile = atomicAdd(&ws.hdr->ticket, 1u);
@@ -317,18 +323,28 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
     uint4 ent[kMergeItems][4];
     uint32_t pos[kMergeItems];  // merged position of the entry
+    {
+        // all addresses first, then all loads, so that the loads of one thread are in flight together
+        // (threads without an entry re-read entry 0 and never use it; an unusable tile has n = 0)
+        const uint4* src[kMergeItems];
 #pragma unroll
-    for (int i = 0; i < kMergeItems; i++) {
-        const uint32_t e = tid + i * kMergeThreads;
-        pos[i] = 0;
-        if (e < n) {
-            const uint32_t j = piece_of(s.seg, k, e);
-            const uint4* src = reinterpret_cast<const uint4*>(s.run[j] + s.lo[j] + (e - s.seg[j]));
+        for (int i = 0; i < kMergeItems; i++) {
+            const uint32_t e = tid + i * kMergeThreads;
+            const uint32_t ee = e < n ? e : 0;
+            const uint32_t j = piece_of(s.seg, k, top_step, ee);
+            src[i] = reinterpret_cast<const uint4*>(s.run[j] + s.lo[j] + (ee - s.seg[j]));
+            pos[i] = 0;
+        }
+        if (n > 0) {
 #pragma unroll
-            for (int part = 0; part < 4; part++) ent[i][part] = src[part];
+            for (int i = 0; i < kMergeItems; i++)
+#pragma unroll
+                for (int part = 0; part < 4; part++) ent[i][part] = load_global_u4(src[i] + part);
         } else {
 #pragma unroll
-            for (int part = 0; part < 4; part++) ent[i][part] = make_uint4(0, 0, 0, 0);
+            for (int i = 0; i < kMergeItems; i++)
+#pragma unroll
+                for (int part = 0; part < 4; part++) ent[i][part] = make_uint4(0, 0, 0, 0);
         }
     }
 #pragma unroll
@@ -354,7 +370,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         const uint32_t o_end = min(o + (uint32_t)kMergeItems, n);
         while (o < o_end) {
             // the pair of lists whose output range contains position o
-            const uint32_t j = piece_of(s.seg, k, o);
+            const uint32_t j = piece_of(s.seg, k, top_step, o);
             const uint32_t ra = (j / (2 * width)) * 2 * width, rb = min(ra + width, k), rc = min(ra + 2 * width, k);
             const uint32_t sa = s.seg[ra], sb = s.seg[rb], sc = s.seg[rc];
             const uint32_t len_a = sb - sa, len_b = sc - sb;
@@ -367,18 +383,23 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
                 if (sur_le(sur_load(&in[sa + mid]), sur_load(&in[sb + (d - 1 - mid)]))) lo = mid + 1;
                 else hi = mid;
             }
+            // serial merge, written without branches: one dependent LDS read per output
             uint32_t a = lo, b = d - lo;
             Sur va = sur_load(&in[a < len_a ? sa + a : sa]), vb = sur_load(&in[b < len_b ? sb + b : sa]);
             for (; o < stop; o++) {
-                const bool take_a = b >= len_b || (a < len_a && sur_le(va, vb));
-                sur_store(&dst[o], take_a ? va : vb);
-                if (take_a) {
-                    a++;
-                    va = sur_load(&in[a < len_a ? sa + a : sa]);
-                } else {
-                    b++;
-                    vb = sur_load(&in[b < len_b ? sb + b : sa]);
-                }
+                const bool take_a = (b >= len_b) | ((a < len_a) & sur_le(va, vb));
+                Sur w;
+                w.hi = take_a ? va.hi : vb.hi;
+                w.lo = take_a ? va.lo : vb.lo;
+                sur_store(&dst[o], w);
+                a += take_a ? 1 : 0;
+                b += take_a ? 0 : 1;
+                const uint32_t ia = a < len_a ? sa + a : sa, ib = b < len_b ? sb + b : sa;
+                const Sur nv = sur_load(&in[take_a ? ia : ib]);
+                va.hi = take_a ? nv.hi : va.hi;
+                va.lo = take_a ? nv.lo : va.lo;
+                vb.hi = take_a ? vb.hi : nv.hi;
+                vb.lo = take_a ? vb.lo : nv.lo;
             }
         }
         __syncthreads();
@@ -461,7 +482,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         for (int i = 0; i < kMergeItems; i++) {
             const uint32_t e = tid + i * kMergeThreads;
             if (e < n) {
-                const uint32_t j = piece_of(s.seg, k, e);
+                const uint32_t j = piece_of(s.seg, k, top_step, e);
                 const Key x = key_from_raw(ent[i][0], ent[i][1]);
                 const uint64_t seq = ((uint64_t)ent[i][2].y << 32) | ent[i][2].x;
                 uint32_t p = e - s.seg[j];
