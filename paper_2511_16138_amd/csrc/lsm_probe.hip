@@ -1,10 +1,14 @@
 // lsm_probe: batched longest-cached-prefix lookup (paper appendix B, "Probe"; section 2.2,
 // "Point Lookups": runs are checked newest to oldest and the first match is the result).
 //
-// One wave per request.  The request's block keys are handled 64 at a time, one key per
-// lane: a lane walks the runs newest -> oldest, finds the page through the run's fence keys,
-// searches the page, and stops at the first run that holds the key.  A ballot over the lanes
-// gives the first block that is not live; later chunks of the request are then skipped.
+// One wave per request, requests taken round-robin by the waves of a fixed-size grid.  Every
+// workgroup first copies a top-level fence table into LDS: for each run of the tree, an evenly
+// spaced subset of its fence keys (all of them for small runs).  A request's block keys are
+// handled 64 at a time, one key per lane.  A lane walks the runs newest -> oldest (kRunGroup at a
+// time) and stops at the first run that holds the key: top-level fences in LDS, then the
+// remaining fence range and the 64-entry page in global memory, reading the first 16 key bytes
+// and the second half only on a tie.  A ballot over the lanes gives the first block that is not live; later chunks of
+// the request are skipped and zero-filled.
 #include <hip/hip_runtime.h>
 
 #include "lsm_common.h"
@@ -26,68 +30,208 @@ struct TreeTable {
 };
 
 constexpr int kProbeThreads = 256;
+constexpr int kTopSlots = 1024;  // top-level fence keys held in LDS per workgroup (32 KB)
+constexpr int kRunGroup = 1;     // runs searched together by one lane (more only adds memory traffic: the search is bound by cold lines)
 
-// Index of the entry with this key in the run, or ~0 if absent.
-__device__ __forceinline__ uint64_t find_in_run(const TreeRun& tr, const Key& q) {
-    // page = last fence <= q
-    uint64_t lo = 0, hi = tr.n_fences;
-    while (lo < hi) {
-        uint64_t mid = lo + ((hi - lo) >> 1);
-        if (key_less(q, load_key(tr.fences + mid * LSM_KEY_BYTES))) hi = mid;
-        else lo = mid + 1;
-    }
-    if (lo == 0) return ~0ull;  // q is below the first key of the run
-    uint64_t first = (lo - 1) * (uint64_t)tr.stride;
-    uint64_t last = first + tr.stride < tr.n ? first + tr.stride : tr.n;
-    uint64_t i = lower_bound_run(tr.entries, first, last, q);
-    if (i < last && key_equal(load_key(tr.entries + i), q)) return i;
-    return ~0ull;
+struct ProbeShared {
+    uint4 top_lo[kTopSlots];  // first 16 bytes of each top-level fence key
+    uint4 top_hi[kTopSlots];  // last 16 bytes
+    uint32_t first_slot[LSM_MAX_RUNS];  // slots of run r: [first_slot[r], first_slot[r] + n_top[r])
+    uint32_t n_top[LSM_MAX_RUNS];
+    uint32_t top_stride[LSM_MAX_RUNS];  // top key i of run r = fence i * top_stride[r]
+};
+
+// -1 / 0 / +1 for q < / == / > the 32-byte key whose halves are (lo, hi); hi is only fetched on a tie
+template <typename LoadHi>
+__device__ __forceinline__ int compare_key(const Key& q, uint4 lo, LoadHi load_hi) {
+    const uint64_t w0 = __builtin_bswap64(((uint64_t)lo.y << 32) | lo.x);
+    const uint64_t w1 = __builtin_bswap64(((uint64_t)lo.w << 32) | lo.z);
+    if (q.w[0] != w0) return q.w[0] < w0 ? -1 : 1;
+    if (q.w[1] != w1) return q.w[1] < w1 ? -1 : 1;
+    const uint4 hi = load_hi();
+    const uint64_t w2 = __builtin_bswap64(((uint64_t)hi.y << 32) | hi.x);
+    const uint64_t w3 = __builtin_bswap64(((uint64_t)hi.w << 32) | hi.z);
+    if (q.w[2] != w2) return q.w[2] < w2 ? -1 : 1;
+    if (q.w[3] != w3) return q.w[3] < w3 ? -1 : 1;
+    return 0;
 }
 
 __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
                                                                uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len,
                                                                lsm_hit_t* hits) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t req = blockIdx.x * (kProbeThreads / kWave) + threadIdx.x / kWave;
-    if (req >= n_req) return;  // whole wave
-    uint32_t nb = n_blocks[req];
-    if (nb > max_blocks) nb = max_blocks;
-    const uint8_t* qrow = qkeys + (uint64_t)req * max_blocks * LSM_KEY_BYTES;
-    uint4* hrow = reinterpret_cast<uint4*>(hits + (uint64_t)req * max_blocks);
-    uint32_t result = nb;
-    bool done = false;
-    for (uint32_t c0 = 0; c0 < max_blocks; c0 += kWave) {
-        const uint32_t j = c0 + lane;
-        uint4 h = make_uint4(0, 0, 0, 0);
-        if (!done && c0 < nb) {
-            bool live = true;  // lanes past the request's length do not end the prefix
-            if (j < nb) {
-                live = false;
-                Key q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
-                for (uint32_t r = 0; r < tree.n_runs; r++) {
-                    uint64_t i = find_in_run(tree.run[r], q);
-                    if (i != ~0ull) {
-                        const uint4* e = reinterpret_cast<const uint4*>(tree.run[r].entries + i);
-                        uint4 meta = e[2], val = e[3];  // seqno | type+pad, vptr | vlen+pad
-                        if ((meta.z & 0xFF) == LSM_PUT) {
-                            live = true;
-                            h = make_uint4(val.x, val.y, val.z, r);
+    __shared__ ProbeShared s;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const uint32_t n_runs = tree.n_runs;
+
+    // ---- top-level fence table: an equal share of the slots for every run
+    const uint32_t share = n_runs ? kTopSlots / n_runs : 0;
+    if (tid < (int)n_runs) {
+        const uint64_t nf = tree.run[tid].n_fences;
+        const uint32_t ts = share ? (uint32_t)((nf + share - 1) / share) : 1;
+        s.first_slot[tid] = tid * share;
+        s.top_stride[tid] = ts ? ts : 1;
+        s.n_top[tid] = ts ? (uint32_t)((nf + ts - 1) / ts) : 0;
+    }
+    __syncthreads();
+    for (uint32_t slot = tid; slot < share * n_runs; slot += kProbeThreads) {
+        const uint32_t r = slot / share, i = slot - r * share;
+        if (i < s.n_top[r]) {
+            const uint4* f = reinterpret_cast<const uint4*>(tree.run[r].fences + (uint64_t)i * s.top_stride[r] * LSM_KEY_BYTES);
+            s.top_lo[slot] = f[0];
+            s.top_hi[slot] = f[1];
+        }
+    }
+    __syncthreads();
+
+    const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
+    for (uint32_t req = blockIdx.x * (kProbeThreads / kWave) + tid / kWave; req < n_req; req += waves) {
+        uint32_t nb = n_blocks[req];
+        if (nb > max_blocks) nb = max_blocks;
+        const uint8_t* qrow = qkeys + (uint64_t)req * max_blocks * LSM_KEY_BYTES;
+        uint4* hrow = reinterpret_cast<uint4*>(hits + (uint64_t)req * max_blocks);
+        uint32_t result = nb;
+        bool done = false;
+        for (uint32_t c0 = 0; c0 < max_blocks; c0 += kWave) {
+            const uint32_t j = c0 + lane;
+            uint4 h = make_uint4(0, 0, 0, 0);
+            if (!done && c0 < nb) {
+                const bool mine = j < nb;
+                bool live = !mine;  // lanes past the request's length do not end the prefix
+                bool found = !mine;
+                Key q = {{0, 0, 0, 0}};
+                if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
+                for (uint32_t r0 = 0; r0 < n_runs && __ballot(!found) != 0; r0 += kRunGroup) {
+                    // searches in runs r0 .. r0 + kRunGroup - 1 proceed in lockstep; lo/hi are fence numbers, then entry offsets in the page
+                    uint32_t lo[kRunGroup], hi[kRunGroup];
+                    // (1) top-level fences in LDS: number of top keys <= q
+#pragma unroll
+                    for (int g = 0; g < kRunGroup; g++) {
+                        const uint32_t r = r0 + g;
+                        lo[g] = 0;
+                        hi[g] = (!found && r < n_runs) ? s.n_top[r] : 0;
+                    }
+                    for (;;) {
+                        bool any = false;
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) {
+                            if (lo[g] < hi[g]) {
+                                any = true;
+                                const uint32_t mid = (lo[g] + hi[g]) >> 1, slot = s.first_slot[r0 + g] + mid;
+                                const int c = compare_key(q, s.top_lo[slot], [&] { return s.top_hi[slot]; });
+                                if (c < 0) hi[g] = mid;
+                                else lo[g] = mid + 1;
+                            }
                         }
-                        break;
+                        if (!any) break;
+                    }
+                    // (2) the fences between two top keys, in global memory: number of fences <= q
+#pragma unroll
+                    for (int g = 0; g < kRunGroup; g++) {
+                        const uint32_t r = r0 + g;
+                        if (lo[g] > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the run is skipped)
+                            const uint32_t ts = s.top_stride[r];
+                            const uint64_t nf = tree.run[r].n_fences;
+                            const uint64_t end = (uint64_t)lo[g] * ts;
+                            hi[g] = (uint32_t)(end < nf ? end : nf);
+                            lo[g] = (lo[g] - 1) * ts + 1;  // fence (lo-1)*ts is <= q
+                        } else {
+                            hi[g] = 0;
+                        }
+                    }
+                    for (;;) {
+                        bool any = false;
+                        uint4 f[kRunGroup];
+                        uint32_t mid[kRunGroup];
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) {
+                            mid[g] = (lo[g] + hi[g]) >> 1;
+                            if (lo[g] < hi[g]) {
+                                any = true;
+                                f[g] = *reinterpret_cast<const uint4*>(tree.run[r0 + g].fences + (uint64_t)mid[g] * LSM_KEY_BYTES);
+                            }
+                        }
+                        if (!any) break;
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) {
+                            if (lo[g] < hi[g]) {
+                                const uint8_t* fp = tree.run[r0 + g].fences + (uint64_t)mid[g] * LSM_KEY_BYTES;
+                                const int c = compare_key(q, f[g], [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
+                                if (c < 0) hi[g] = mid[g];
+                                else lo[g] = mid[g] + 1;
+                            }
+                        }
+                    }
+                    // (3) the page of the last fence <= q: first entry whose key is >= q
+                    uint64_t page[kRunGroup];
+#pragma unroll
+                    for (int g = 0; g < kRunGroup; g++) {
+                        const uint32_t r = r0 + g;
+                        page[g] = 0;
+                        if (lo[g] > 0) {  // lo = fences <= q
+                            const uint32_t stride = tree.run[r].stride;
+                            page[g] = (uint64_t)(lo[g] - 1) * stride;
+                            const uint64_t left = tree.run[r].n - page[g];
+                            hi[g] = (uint32_t)(left < stride ? left : stride);
+                            lo[g] = 0;
+                        } else {
+                            hi[g] = 0;
+                        }
+                    }
+                    uint32_t page_len[kRunGroup];
+#pragma unroll
+                    for (int g = 0; g < kRunGroup; g++) page_len[g] = hi[g];
+                    for (;;) {
+                        bool any = false;
+                        uint4 f[kRunGroup];
+                        uint32_t mid[kRunGroup];
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) {
+                            mid[g] = (lo[g] + hi[g]) >> 1;
+                            if (lo[g] < hi[g]) {
+                                any = true;
+                                f[g] = *reinterpret_cast<const uint4*>(tree.run[r0 + g].entries + page[g] + mid[g]);
+                            }
+                        }
+                        if (!any) break;
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) {
+                            if (lo[g] < hi[g]) {
+                                const lsm_entry_t* ep = tree.run[r0 + g].entries + page[g] + mid[g];
+                                const int c = compare_key(q, f[g], [&] { return reinterpret_cast<const uint4*>(ep)[1]; });
+                                if (c > 0) lo[g] = mid[g] + 1;
+                                else hi[g] = mid[g];
+                            }
+                        }
+                    }
+                    // (4) newest run of the group that holds the key
+#pragma unroll
+                    for (int g = 0; g < kRunGroup; g++) {
+                        if (!found && lo[g] < page_len[g]) {
+                            const uint4* e = reinterpret_cast<const uint4*>(tree.run[r0 + g].entries + page[g] + lo[g]);
+                            if (compare_key(q, e[0], [&] { return e[1]; }) == 0) {
+                                found = true;
+                                const uint4 meta = e[2], val = e[3];  // seqno | type + pad, vptr | vlen + pad
+                                if ((meta.z & 0xFF) == LSM_PUT) {
+                                    live = true;
+                                    h = make_uint4(val.x, val.y, val.z, r0 + g);
+                                }
+                            }
+                        }
                     }
                 }
+                const uint64_t dead = __ballot(!live);
+                if (dead) {
+                    const uint32_t first = (uint32_t)__ffsll((unsigned long long)dead) - 1;
+                    result = c0 + first;
+                    done = true;
+                    if ((uint32_t)lane >= first) h = make_uint4(0, 0, 0, 0);
+                }
             }
-            uint64_t dead = __ballot(!live);
-            if (dead) {
-                uint32_t first = (uint32_t)__ffsll((unsigned long long)dead) - 1;
-                result = c0 + first;
-                done = true;
-                if ((uint32_t)lane >= first) h = make_uint4(0, 0, 0, 0);
-            }
+            if (j < max_blocks) hrow[j] = h;
         }
-        if (j < max_blocks) hrow[j] = h;
+        if (lane == 0) hit_len[req] = result;
     }
-    if (lane == 0) hit_len[req] = result;
 }
 
 }  // namespace lsm
@@ -116,16 +260,23 @@ extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, c
         if (tr.run.n > 0) {
             if (tr.run.entries == nullptr || tr.fence.keys == nullptr) return LSM_ERR_NULL;
             if (tr.fence.stride == 0 || tr.fence.n != (tr.run.n + tr.fence.stride - 1) / tr.fence.stride) return LSM_ERR_BAD_ARG;
+            if (tr.fence.n >= (1ull << 31)) return LSM_ERR_BAD_ARG;
             if ((reinterpret_cast<uintptr_t>(tr.run.entries) & 63) != 0 || (reinterpret_cast<uintptr_t>(tr.fence.keys) & 15) != 0)
                 return LSM_ERR_BAD_ARG;
         } else {
             d.n_fences = 0;  // an empty run is never searched
+            d.stride = 1;
         }
     }
     tt.n_runs = tree->n_runs;
     for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, 0, 1, 0};
+    int device = 0, cus = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
+        return LSM_ERR_HIP;
     const uint32_t per_block = kProbeThreads / kWave;
     uint32_t blocks = (queries->n_req + per_block - 1) / per_block;
+    if (blocks > (uint32_t)cus * 4) blocks = (uint32_t)cus * 4;
     hipLaunchKernelGGL(probe_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
                        queries->n_blocks, queries->n_req, queries->max_blocks, out_hits->hit_len, out_hits->hits);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
