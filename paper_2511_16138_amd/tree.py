@@ -1,0 +1,175 @@
+"""Host driver of the LSM key index: level bookkeeping and the adaptive controller.
+
+This sequences the library calls for a mixed workload (paper section 3.3 and appendix C):
+flushed runs enter level 1, a level that holds more than K runs is compacted, a level that
+outgrows its capacity M * T**level is moved down, and a sliding window of operation counts
+re-tunes K through the cost model.  All index work (merging, fence building, lookups, the
+cost model itself) is done by the backend = the GPU library; nothing here touches entries.
+
+Readings of the paper used here (it gives no constants):
+  * window = `window_ops` operations; a write operation is one inserted sequence, a read one
+    probe request; reads that find nothing are "empty probes" (z), the others are split evenly
+    between range reads (s) and point reads (r), as both "derive from successful reads";
+  * the (T, K) search is re-run when the L1 distance between the window's mix and the mix at
+    the last search exceeds `shift_threshold`;
+  * lazy transition: a level adopts the current K the next time a run arrives at it.  A larger
+    K leaves resident runs as they are (the newcomer is placed beside them); a smaller K merges
+    all runs of the level at that next arrival.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Any, List, Optional, Sequence, Tuple
+
+LSM_BOTTOMMOST = 1
+
+
+@dataclass
+class LevelRun:
+    run: Any      # backend handle of the entries (has .shape[0] = number of entries)
+    fences: Any   # backend handle of its fence index
+
+    @property
+    def n(self) -> int:
+        return int(self.run.shape[0])
+
+
+class GpuBackend:
+    """The library calls the driver needs, on torch CUDA tensors."""
+
+    def __init__(self, fence_stride: int = 64):
+        from . import binding
+        self._b = binding
+        self.fence_stride = fence_stride
+
+    def compact(self, runs: Sequence[Any], flags: int) -> Any:
+        out, n_out = self._b.lsm_compact(list(runs), flags)
+        n = int(n_out.item())
+        if n < 0 or n > out.shape[0]:
+            raise RuntimeError("lsm_compact reported a device-side failure")
+        return out[:n]
+
+    def build_fences(self, run: Any) -> Any:
+        return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
+
+    def probe(self, qkeys: Any, n_blocks: Any, tree: Sequence[LevelRun]) -> Tuple[Any, Any]:
+        tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i) for i, t in enumerate(tree)]
+        return self._b.lsm_probe(qkeys, n_blocks, tr)
+
+    def hit_len_to_host(self, hit_len: Any) -> List[int]:
+        return hit_len.cpu().tolist()
+
+    def policy_choose(self, w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d) -> Tuple[int, int]:
+        return self._b.lsm_policy_choose(w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d)
+
+
+@dataclass
+class AdaptiveLsmTree:
+    backend: Any
+    buffer_entries: int                 # M
+    size_ratio: int = 10                # T
+    runs_per_level: int = 1             # K currently asked for by the controller
+    window_ops: int = 4096
+    shift_threshold: float = 0.2
+    t_grid: Tuple[int, int] = (10, 10)
+    page_entries: float = 64.0          # B
+    filter_fpr: float = 1.0             # p (no Bloom filters)
+    levels: List[List[LevelRun]] = field(default_factory=list)   # levels[0] = level 1; runs newest first
+    level_k: List[int] = field(default_factory=list)             # K each level is currently run with
+    trace: List[tuple] = field(default_factory=list)
+    _win: List[float] = field(default_factory=lambda: [0, 0, 0, 0.0])  # writes, hits, empties, blocks hit
+    _last_mix: Optional[Tuple[float, float, float, float]] = None
+
+    # ------------------------------------------------------------------ structure
+    def load_level(self, level: int, runs_newest_first: Sequence[Any]) -> None:
+        while len(self.levels) <= level:
+            self.levels.append([])
+            self.level_k.append(self.runs_per_level)
+        self.levels[level] = [LevelRun(r, self.backend.build_fences(r)) for r in runs_newest_first]
+
+    def capacity(self, level: int) -> int:
+        return self.buffer_entries * self.size_ratio ** (level + 1)
+
+    def total_entries(self) -> int:
+        return sum(r.n for lv in self.levels for r in lv)
+
+    def tree_runs(self) -> List[LevelRun]:
+        return [r for lv in self.levels for r in lv]
+
+    def flush(self, run: Any) -> None:
+        """A sorted run from the write buffer enters level 1."""
+        self._arrive(0, LevelRun(run, self.backend.build_fences(run)))
+
+    def _arrive(self, level: int, newcomer: LevelRun) -> None:
+        while len(self.levels) <= level:
+            self.levels.append([])
+            self.level_k.append(self.runs_per_level)
+        self.level_k[level] = self.runs_per_level  # lazy transition: K is adopted when a run arrives
+        lv = self.levels[level]
+        lv.insert(0, newcomer)
+        if len(lv) <= self.level_k[level]:
+            return
+        deeper_empty = all(len(x) == 0 for x in self.levels[level + 1:])
+        flags = LSM_BOTTOMMOST if deeper_empty else 0
+        n_in = sum(r.n for r in lv)
+        merged = self.backend.compact([r.run for r in lv], flags)
+        self.trace.append(("compact", level + 1, len(lv), n_in, int(merged.shape[0]), flags))
+        self.levels[level] = []
+        merged_run = LevelRun(merged, None)
+        if merged_run.n > self.capacity(level):
+            self.trace.append(("move", level + 1, level + 2, merged_run.n))
+            merged_run.fences = self.backend.build_fences(merged)
+            self._arrive(level + 1, merged_run)
+        elif merged_run.n > 0:
+            merged_run.fences = self.backend.build_fences(merged)
+            self.levels[level] = [merged_run]
+
+    # ------------------------------------------------------------------ operations and controller
+    def note_writes(self, n_ops: int) -> None:
+        self._win[0] += n_ops
+        self._maybe_retune()
+
+    def probe(self, qkeys: Any, n_blocks: Any) -> Tuple[Any, Any]:
+        hit_len, hits = self.backend.probe(qkeys, n_blocks, self.tree_runs())
+        lens = self.backend.hit_len_to_host(hit_len)
+        hit = [x for x in lens if x > 0]
+        self._win[1] += len(hit)
+        self._win[2] += len(lens) - len(hit)
+        self._win[3] += float(sum(hit))
+        self.trace.append(("probe", len(lens), len(hit), int(sum(hit))))
+        self._maybe_retune()
+        return hit_len, hits
+
+    def _maybe_retune(self) -> None:
+        writes, hits, empties, blocks = self._win
+        total = writes + hits + empties
+        if total < self.window_ops:
+            return
+        mix = (writes / total, hits / total / 2, hits / total / 2, empties / total)  # w, s, r, z
+        d = blocks / hits if hits else 0.0
+        self._win = [0, 0, 0, 0.0]
+        if self._last_mix is not None and sum(abs(a - b) for a, b in zip(mix, self._last_mix)) <= self.shift_threshold:
+            return
+        self._last_mix = mix
+        T, K = self.backend.policy_choose(mix[0], mix[1], mix[2], mix[3], max(1, self.total_entries()), self.buffer_entries,
+                                          self.t_grid[0], self.t_grid[1], self.page_entries, self.filter_fpr, d)
+        self.trace.append(("policy", T, K, tuple(round(x, 6) for x in mix), round(d, 6)))
+        self.size_ratio, self.runs_per_level = T, K
+
+
+def run_mixed_trace(tree: AdaptiveLsmTree, trace, on_probe=None, on_compaction=None) -> None:
+    """Replay a workloads.lsm.MixedTrace: flushes and probe batches in time order."""
+    for (kind, i, _phase), n_writes in zip(trace.events, trace.write_ops_between):
+        if n_writes:
+            tree.note_writes(n_writes)
+        if kind == "flush":
+            before = len(tree.trace)
+            tree.flush(trace.flush_runs[i])
+            if on_compaction is not None:
+                for ev in tree.trace[before:]:
+                    on_compaction(ev)
+        else:
+            q, nb = trace.probe_batch(i)
+            out = tree.probe(q, nb)
+            if on_probe is not None:
+                on_probe(i, q, nb, out)

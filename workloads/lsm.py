@@ -173,9 +173,12 @@ def make_universe(seed: int, n_entries: int, n_pool: int, zipf_a: Optional[float
 # --------------------------------------------------------------------------------------
 # entries and runs
 # --------------------------------------------------------------------------------------
-def _assemble(U: Universe, idx: torch.Tensor, seqno: torch.Tensor, typ: torch.Tensor) -> torch.Tensor:
-    """[n, 8] int64 entries for universe indices `idx`, sorted ascending by key."""
-    order = torch.argsort(U.rank[idx])
+def _assemble(U: Universe, idx: torch.Tensor, seqno: torch.Tensor, typ: torch.Tensor,
+              group: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """[n, 8] int64 entries for universe indices `idx`, sorted ascending by key (within each
+    `group` number, groups in ascending order, if given)."""
+    sort_key = U.rank[idx] if group is None else group * (1 << 40) + U.rank[idx]
+    order = torch.argsort(sort_key)
     idx, seqno, typ = idx[order], seqno[order], typ[order]
     e = torch.empty((idx.numel(), 8), dtype=torch.int64, device=idx.device)
     e[:, 0:4] = K.key_bytes_words(U.keys[idx])
@@ -211,7 +214,13 @@ def _tomb_eligible(U: Universe, owner: torch.Tensor) -> torch.Tensor:
 
 
 def epoch_runs(U: Universe, sizes_old_to_new: List[int], ow_frac: float, tb_frac: float) -> List[torch.Tensor]:
-    """Cut one operation stream into runs (epochs).  Returns runs NEWEST FIRST.
+    """Cut one operation stream into runs (epochs).  Returns runs NEWEST FIRST (see epoch_runs_state)."""
+    return epoch_runs_state(U, sizes_old_to_new, ow_frac, tb_frac)[0]
+
+
+def epoch_runs_state(U: Universe, sizes_old_to_new: List[int], ow_frac: float, tb_frac: float):
+    """Cut one operation stream into runs (epochs).  Returns (runs NEWEST FIRST, number of universe
+    entries consumed as fresh inserts, next unused seqno).
 
     Epoch 0 (oldest) holds fresh inserts only.  Every later epoch of n entries holds
     round(n*ow_frac) overwrites (a new PUT, newer seqno and pointer, for a key inserted in
@@ -266,7 +275,7 @@ def epoch_runs(U: Universe, sizes_old_to_new: List[int], ow_frac: float, tb_frac
         runs.append(_assemble(U, idx, seqno, typ))
         fp += n_fresh
         base += n_e
-    return runs[::-1]
+    return runs[::-1], fp, base
 
 
 def fresh_needed(sizes_old_to_new: List[int], ow_frac: float, tb_frac: float) -> int:
@@ -439,3 +448,117 @@ def queries_config1(w: Workload, n_req: int = 4096, stream: int = 0):
 def queries_config4(w: Workload, n_req: int = 4096, stream: int = 0):
     """Zipf(0.99) over the prefix pool, 30 % misses, 16..256 blocks per request."""
     return make_queries(w.universe, n_req, 16, 256, 0.70, 0.0, 0.99, stream, row_blocks=256)
+
+
+# --------------------------------------------------------------------------------------
+# configuration 5: mixed, shifting workload on a leveled tree
+# --------------------------------------------------------------------------------------
+@dataclass
+class MixedTrace:
+    """Starting tree plus a time-ordered trace of flushes (sorted runs of `buffer_entries`
+    entries from the write buffer) and probe batches."""
+    workload: Workload                 # starting tree, runs newest first, one per level
+    buffer_entries: int                # M: entries per flushed run
+    size_ratio: int                    # T of the starting tree
+    flush_runs: torch.Tensor           # [n_flushes, M, 8]
+    events: List[Tuple[str, int, int]]  # ("flush", f, phase) / ("probe", b, phase) in time order
+    batch_requests: int
+    write_ops_between: List[int]       # write operations (sequences) that happened before each event since the last one
+
+    def probe_batch(self, b: int):
+        return make_queries(self.workload.universe, self.batch_requests, 16, 256, 0.70, 0.0, 0.99, stream=1000 + b,
+                            row_blocks=256)
+
+
+_S_OP_KIND, _S_FLUSH_TB, _S_FLUSH_CUT = 50, 51, 52
+
+
+def config5(device="cpu", seed: int = rng.SEED, tree_total: int = 400_000_000, buffer_entries: int = 3600,
+            ops_per_phase: int = 1 << 18, batch_requests: int = 4096, tb_frac: float = 0.05,
+            read_shares=(0.9, 0.5, 0.1)) -> MixedTrace:
+    """Mixed workload: a leveled tree (size ratio 10, level i holds M * 10**(i-1) entries, the last
+    level the remainder) and three phases of `ops_per_phase` operations with read shares
+    90 %, 50 %, 10 %.  A read is one probe request (batches of `batch_requests`); a write inserts
+    the not-yet-present blocks of the next sequence into the write buffer, which is flushed as a
+    sorted run every `buffer_entries` entries, `tb_frac` of them tombstones for tails of
+    sequences of the starting tree."""
+    T = 10
+    n_levels = 1
+    while buffer_entries * T ** n_levels < tree_total:
+        n_levels += 1
+    sizes = tree_sizes(tree_total, n_levels, T)
+    old_to_new = sizes[::-1]
+    n_ops = 3 * ops_per_phase
+    n_write_est = int(sum((1 - r) * ops_per_phase for r in read_shares))
+    n_pool = max(16, min(4096, tree_total // 100_000))
+    U = make_universe(seed + 5, fresh_needed(old_to_new, 0.08, tb_frac) + 45 * n_write_est + 4096, n_pool, 0.9, device)
+    runs, fp, next_seq = epoch_runs_state(U, old_to_new, 0.08, tb_frac)
+    w = Workload(f"cfg5_tree{n_levels}_{tree_total}", U, runs, list(range(1, n_levels + 1)), False)
+    dev = U.keys.device
+
+    # operations: write or read, by phase
+    op = torch.arange(n_ops, device=dev, dtype=torch.int64)
+    phase = op // ops_per_phase
+    thr = torch.tensor([int((1 - r) * (1 << 31)) for r in read_shares], device=dev, dtype=torch.int64)
+    is_write = rng.lsr(rng.u64(seed, _S_OP_KIND, op), 33) < thr[phase]
+    n_writes_before = torch.cumsum(is_write.to(torch.int64), 0)   # inclusive
+    n_reads_before = torch.cumsum((~is_write).to(torch.int64), 0)
+    # write k inserts the private blocks of the k-th sequence after the ones the tree used up
+    seq_end = U.seq_first + U.seq_ulen
+    s0 = int(torch.searchsorted(seq_end, torch.tensor([fp], device=dev), right=True).item())  # first sequence with blocks >= fp
+    n_seq_avail = U.seq_ulen.numel() - s0
+    seq_of_write = s0 + torch.arange(min(int(n_writes_before[-1].item()), n_seq_avail), device=dev)
+    ends = torch.clamp(seq_end[seq_of_write], min=fp) - fp        # fresh entries written after each write op
+    m_tb = int(round(buffer_entries * tb_frac))
+    m_fresh = buffer_entries - m_tb
+    n_flushes = int(ends[-1].item()) // m_fresh if ends.numel() else 0
+    # event times: flush f right after the write that fills the buffer, probe batch b after its last read
+    write_pos = torch.nonzero(is_write).squeeze(1)[: ends.numel()]
+    fl_targets = (torch.arange(n_flushes, device=dev, dtype=torch.int64) + 1) * m_fresh
+    fl_write = torch.searchsorted(ends, fl_targets)               # index of the write op that reaches the target
+    fl_op = write_pos[fl_write]
+    n_batches = int(n_reads_before[-1].item()) // batch_requests
+    pb_targets = (torch.arange(n_batches, device=dev, dtype=torch.int64) + 1) * batch_requests
+    pb_op = torch.searchsorted(n_reads_before, pb_targets)
+    ev = [("flush", f, int(o)) for f, o in enumerate(fl_op.tolist())] + [("probe", b, int(o)) for b, o in enumerate(pb_op.tolist())]
+    ev.sort(key=lambda e: (e[2], 0 if e[0] == "flush" else 1))
+    events, writes_between, last_w = [], [], 0
+    nwb = n_writes_before.cpu()
+    for kind, i, o in ev:
+        events.append((kind, i, o // ops_per_phase))
+        wb = int(nwb[o])
+        writes_between.append(wb - last_w)
+        last_w = wb
+
+    # flushed runs: fresh slice + tombstones for tails of tree sequences, sorted per flush
+    if n_flushes:
+        fresh_idx = fp + torch.arange(n_flushes * m_fresh, device=dev, dtype=torch.int64)
+        fresh_flush = torch.arange(n_flushes * m_fresh, device=dev, dtype=torch.int64) // m_fresh
+        seq_owner = U.pool.n + torch.arange(U.seq_ulen.numel(), device=dev, dtype=torch.int64)
+        vict = torch.nonzero(_tomb_eligible(U, seq_owner) & (U.seq_ulen > 0) & (seq_end <= fp)).squeeze(1)
+        vict = _pick_smallest_hash(seed, _S_FLUSH_TB, vict, vict.numel())
+        cut = rng.lsr(rng.u64(seed, _S_FLUSH_CUT, vict), 33) % U.seq_ulen[vict]
+        tail = U.seq_ulen[vict] - cut
+        need_tb = n_flushes * m_tb
+        csum = torch.cumsum(tail, 0)
+        assert vict.numel() and int(csum[-1].item()) >= need_tb, "not enough evictable tails for the trace"
+        nv = int(torch.searchsorted(csum, torch.tensor([need_tb], device=dev)).item()) + 1
+        vict, tail, cut = vict[:nv], tail[:nv].clone(), cut[:nv].clone()
+        over = int(csum[nv - 1].item()) - need_tb
+        tail[-1] -= over
+        cut[-1] += over
+        rep_ = torch.repeat_interleave(torch.arange(nv, device=dev), tail)
+        within = torch.arange(need_tb, device=dev) - (torch.cumsum(tail, 0) - tail)[rep_]
+        tb_idx = (U.seq_first[vict] + cut)[rep_] + within
+        tb_flush = torch.arange(need_tb, device=dev, dtype=torch.int64) // max(m_tb, 1)
+        idx = torch.cat([fresh_idx, tb_idx])
+        flush_id = torch.cat([fresh_flush, tb_flush])
+        within_flush = torch.cat([torch.arange(n_flushes * m_fresh, device=dev) % m_fresh,
+                                  m_fresh + torch.arange(need_tb, device=dev) % max(m_tb, 1)])
+        seqno = next_seq + flush_id * buffer_entries + within_flush
+        typ = torch.cat([torch.zeros(n_flushes * m_fresh, dtype=torch.int64, device=dev),
+                         torch.ones(need_tb, dtype=torch.int64, device=dev)])
+        flush_runs = _assemble(U, idx, seqno, typ, group=flush_id).view(n_flushes, buffer_entries, 8)
+    else:
+        flush_runs = torch.empty((0, buffer_entries, 8), dtype=torch.int64, device=dev)
+    return MixedTrace(w, buffer_entries, T, flush_runs, events, batch_requests, writes_between)
