@@ -25,12 +25,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 
 
-def cpu_baseline(runs_gpu, sample_per_run: int):
+def cpu_baseline(sample_runs):
     """The CPU checker (single thread, as it stands) on a bounded sample of the same workload:
-    the first `sample_per_run` entries of every run."""
+    the first entries of every run (host copies made by the caller)."""
     from oracle import lsm_oracle
     lsm_oracle.build()
-    sample = [lsm_oracle.as_run(r[:sample_per_run].cpu()) for r in runs_gpu]
+    sample = [lsm_oracle.as_run(r) for r in sample_runs]
+    sample_per_run = sample[0].shape[0]
     n_in = sum(r.shape[0] for r in sample)
     t0 = time.perf_counter()
     out = lsm_oracle.compact(sample, lsm_oracle.FLAG_BOTTOMMOST)
@@ -40,6 +41,71 @@ def cpu_baseline(runs_gpu, sample_per_run: int):
                       f"({n_in} in, {out.shape[0]} out, {dt:.1f} s)"}
 
 
+def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
+    """Lookup-heavy configuration: batches of 4,096 longest-prefix requests (Zipf(0.99) prefixes, 30 % misses,
+    up to 256 block keys each) against the 5-level, 100M-entry tree.  Returns probes/s and key lookups/s."""
+    w = lsm.config4(device=dev, scale=scale)
+    tree = [g.TreeRun(r, g.lsm_build_fences(r, 64), 64, i + 1) for i, r in enumerate(w.runs)]
+    batches = [lsm.queries_config4(w, 4096, stream=b) for b in range(n_batches)]
+    hit_len = torch.empty(4096, dtype=torch.int32, device=dev)
+    hits = torch.empty((4096, 256, 2), dtype=torch.int64, device=dev)
+    for q, nb in batches[:2]:
+        g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    live = 0
+    for q, nb in batches:
+        g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / n_batches
+    keys = sum(int(nb.sum().item()) for _, nb in batches) / n_batches
+    return {"workload": "configs[3]: 5-level tree of %d entries, batches of 4096 requests" % sum(int(r.shape[0]) for r in w.runs),
+            "batches_timed": n_batches, "ms_per_batch": ms, "probes_per_s": 4096 / (ms * 1e-3),
+            "requested_keys_per_s": keys / (ms * 1e-3), "mean_hit_len_last_batch": float(hit_len.float().mean().item())}
+
+
+def mixed_config5(g, lsm, torch, dev, scale: int):
+    """Mixed shifting workload on the 6-level, 400M-entry tree: flushes, compactions chosen by the
+    adaptive controller and probe batches, replayed by the host driver.  Probe batches are generated
+    before the clock starts."""
+    from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
+    tr = lsm.config5(device=dev, tree_total=400_000_000 // scale, buffer_entries=max(36, 3600 // scale),
+                     ops_per_phase=(1 << 18) // scale)
+    tree = AdaptiveLsmTree(GpuBackend(), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests)
+    for level, r in enumerate(tr.workload.runs):
+        tree.load_level(level, [r])
+    batches = {i: tr.probe_batch(i) for kind, i, _ in tr.events if kind == "probe"}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    t_probe = 0.0
+    for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
+        if n_writes:
+            tree.note_writes(n_writes)
+        if kind == "flush":
+            tree.flush(tr.flush_runs[i])
+        else:
+            torch.cuda.synchronize()
+            tp = time.perf_counter()
+            tree.probe(*batches[i])
+            torch.cuda.synchronize()
+            t_probe += time.perf_counter() - tp
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    comp = [e for e in tree.trace if e[0] == "compact"]
+    merged = sum(e[3] for e in comp)
+    n_probe = sum(e[1] for e in tree.trace if e[0] == "probe")
+    return {"workload": "configs[4]: %d-level tree of %d entries, %d flushes of %d entries, %d probe batches"
+                        % (len(tr.workload.runs), sum(int(r.shape[0]) for r in tr.workload.runs), tr.flush_runs.shape[0],
+                           tr.buffer_entries, len(batches)),
+            "seconds": dt, "compactions": len(comp), "entries_merged": merged,
+            "merged_entries_per_s_incl_host": merged / max(dt - t_probe, 1e-9),
+            "probes": n_probe, "probes_per_s_incl_host": n_probe / max(t_probe, 1e-9),
+            "policy_trace_T_K": [e[1:3] for e in tree.trace if e[0] == "policy"],
+            "final_level_sizes": [[r.n for r in lv] for lv in tree.levels]}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +113,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scale", type=int, default=1, help="divide the workload size (1 = the full configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe-config", action="store_true", help="skip the extra probe measurement on the 100M-entry tree")
+    ap.add_argument("--mixed", action="store_true", help="also replay the mixed workload of the 400M-entry tree (about a minute)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the index shards by key range without any exchange, "
@@ -149,8 +217,17 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "merge_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes": algo_bytes},
     }
+    cpu_sample = None if args.no_cpu_baseline else [r[: max(1, (1 << 21) // args.scale)].cpu() for r in runs]
+    del runs, out, fences, q, hits, w
+    torch.cuda.empty_cache()
+    if not args.no_probe_config:
+        result["probe_config"] = probe_config4(g, lsm, torch, dev, 16, args.scale)
+        torch.cuda.empty_cache()
+    if args.mixed:
+        result["mixed_config"] = mixed_config5(g, lsm, torch, dev, args.scale)
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(runs, max(1, (1 << 21) // args.scale))
+        result["cpu_baseline"] = cpu_baseline(cpu_sample)
     print(json.dumps(result))
     return 0
 

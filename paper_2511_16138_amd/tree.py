@@ -7,11 +7,12 @@ re-tunes K through the cost model.  All index work (merging, fence building, loo
 cost model itself) is done by the backend = the GPU library; nothing here touches entries.
 
 Readings of the paper used here (it gives no constants):
-  * window = `window_ops` operations; a write operation is one inserted sequence, a read one
-    probe request; reads that find nothing are "empty probes" (z), the others are split evenly
-    between range reads (s) and point reads (r), as both "derive from successful reads";
-  * the (T, K) search is re-run when the L1 distance between the window's mix and the mix at
-    the last search exceeds `shift_threshold`;
+  * a sliding window over the last `window_ops` operations; a write operation is one inserted
+    sequence, a read one probe request; reads that find nothing are "empty probes" (z), the
+    others are split evenly between range reads (s) and point reads (r), as both "derive from
+    successful reads";
+  * once the window is full, the (T, K) search is re-run whenever the L1 distance between the
+    window's mix and the mix at the last search exceeds `shift_threshold`;
   * lazy transition: a level adopts the current K the next time a run arrives at it.  A larger
     K leaves resident runs as they are (the newcomer is placed beside them); a smaller K merges
     all runs of the level at that next arrival.
@@ -77,7 +78,8 @@ class AdaptiveLsmTree:
     levels: List[List[LevelRun]] = field(default_factory=list)   # levels[0] = level 1; runs newest first
     level_k: List[int] = field(default_factory=list)             # K each level is currently run with
     trace: List[tuple] = field(default_factory=list)
-    _win: List[float] = field(default_factory=lambda: [0, 0, 0, 0.0])  # writes, hits, empties, blocks hit
+    _events: Any = field(default_factory=lambda: __import__("collections").deque())  # (writes, hits, empties, blocks hit)
+    _win: List[float] = field(default_factory=lambda: [0, 0, 0, 0.0])  # sums over _events
     _last_mix: Optional[Tuple[float, float, float, float]] = None
 
     # ------------------------------------------------------------------ structure
@@ -125,19 +127,29 @@ class AdaptiveLsmTree:
             self.levels[level] = [merged_run]
 
     # ------------------------------------------------------------------ operations and controller
-    def note_writes(self, n_ops: int) -> None:
-        self._win[0] += n_ops
+    def _count(self, writes: int, hits: int, empties: int, blocks: float) -> None:
+        self._events.append((writes, hits, empties, blocks))
+        for i, v in enumerate((writes, hits, empties, blocks)):
+            self._win[i] += v
+        # slide: drop the oldest events while the rest still covers window_ops operations
+        while len(self._events) > 1:
+            w0, h0, e0, b0 = self._events[0]
+            if self._win[0] + self._win[1] + self._win[2] - (w0 + h0 + e0) < self.window_ops:
+                break
+            self._events.popleft()
+            for i, v in enumerate((w0, h0, e0, b0)):
+                self._win[i] -= v
         self._maybe_retune()
+
+    def note_writes(self, n_ops: int) -> None:
+        self._count(n_ops, 0, 0, 0.0)
 
     def probe(self, qkeys: Any, n_blocks: Any) -> Tuple[Any, Any]:
         hit_len, hits = self.backend.probe(qkeys, n_blocks, self.tree_runs())
         lens = self.backend.hit_len_to_host(hit_len)
         hit = [x for x in lens if x > 0]
-        self._win[1] += len(hit)
-        self._win[2] += len(lens) - len(hit)
-        self._win[3] += float(sum(hit))
         self.trace.append(("probe", len(lens), len(hit), int(sum(hit))))
-        self._maybe_retune()
+        self._count(0, len(hit), len(lens) - len(hit), float(sum(hit)))
         return hit_len, hits
 
     def _maybe_retune(self) -> None:
@@ -147,7 +159,6 @@ class AdaptiveLsmTree:
             return
         mix = (writes / total, hits / total / 2, hits / total / 2, empties / total)  # w, s, r, z
         d = blocks / hits if hits else 0.0
-        self._win = [0, 0, 0, 0.0]
         if self._last_mix is not None and sum(abs(a - b) for a, b in zip(mix, self._last_mix)) <= self.shift_threshold:
             return
         self._last_mix = mix

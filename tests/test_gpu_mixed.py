@@ -40,12 +40,13 @@ def _replay(backend, trace, runs, keep_probes):
     return tree
 
 
-@pytest.mark.parametrize("tree_total,buffer_entries,ops", [(400_000, 360, 4096), (2_000_000, 900, 8192)])
-def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops):
+@pytest.mark.parametrize("tree_total,buffer_entries,ops,shares", [(400_000, 360, 4096, (0.9, 0.5, 0.1)),
+                                                                  (2_000_000, 900, 8192, (0.9, 0.5, 0.02))])
+def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops, shares):
     from paper_2511_16138_amd.tree import GpuBackend
     from workloads import lsm
     print("mixed trace", tree_total, buffer_entries, ops, flush=True)
-    tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=512)
+    tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=512, read_shares=shares)
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
 
     gpu_probes, cpu_probes = [], []
@@ -60,7 +61,10 @@ def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops)
     kinds = {e[0] for e in gpu_tree.trace}
     assert {"compact", "probe", "policy"} <= kinds
     ks = [e[2] for e in gpu_tree.trace if e[0] == "policy"]
-    assert min(ks) == 1 and max(ks) > 1, ks  # leveling in the read-heavy phase, more runs per level when writes dominate
+    assert ks[0] == 1, ks  # leveling in the read-heavy phase
+    if shares[2] < 0.05:   # with p = 1 and B = 64 the model leaves leveling only above ~93 % writes
+        assert max(ks) > 1, ks
+        assert any(e[0] == "compact" and e[2] > 2 for e in gpu_tree.trace)  # several runs per level were merged at once
     assert len(gpu_probes) == len(cpu_probes) > 0
     for (ghl, ghits), (chl, chits) in zip(gpu_probes, cpu_probes):
         assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl)
