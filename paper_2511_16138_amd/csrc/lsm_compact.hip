@@ -27,6 +27,7 @@ namespace lsm {
 constexpr int kMergeThreads = 512;
 constexpr int kMergeItems = 4;
 constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
+constexpr int kRoundItems = 4;                         // outputs per thread in a merge round
 constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
 constexpr uint64_t kCoarseStride = 32;                 // every 32nd boundary is searched over whole runs first
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
@@ -211,7 +212,7 @@ __device__ __forceinline__ void sur_store(uint4* p, const Sur& v) {
 }
 // key part of a <= key part of b (the index bits never decide)
 __device__ __forceinline__ bool sur_le(const Sur& a, const Sur& b) {
-    return a.hi < b.hi || (a.hi == b.hi && (a.lo >> 16) <= (b.lo >> 16));
+    return a.hi < b.hi || (a.hi == b.hi && (a.lo & ~0xFFFFull) <= (b.lo | 0xFFFFull));
 }
 __device__ __forceinline__ bool sur_same_key(const Sur& a, const Sur& b) { return a.hi == b.hi && ((a.lo ^ b.lo) >> 16) == 0; }
 
@@ -287,37 +288,52 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     const uint32_t k = rt.k;
     const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
-    // ---- tile number (ticket order = output order) and its k pieces
-    if (tid == 0) s.tile = atomicAdd(&ws.hdr->ticket, 1u);
+    // ---- tile number (ticket order = output order) and its k pieces, all by wave 0.  Tickets are
+    //      almost always handed out in workgroup order, so the split rows of tile blockIdx.x are
+    //      requested together with the ticket and only re-read if the ticket says otherwise.
+    if (wave == 0) {
+        uint32_t ticket = 0;
+        if (lane == 0) ticket = atomicAdd(&ws.hdr->ticket, 1u);
+        uint64_t t = blockIdx.x, a = 0, b = 0;
+        const bool mine = lane < (int)k;
+        if (mine) {
+            a = ws.splits[t * k + lane];
+            b = ws.splits[(t + 1) * k + lane];
+            s.run[lane] = rt.ptr[lane];
+        }
+        ticket = __shfl(ticket, 0, kWave);
+        if (ticket != t && ticket < n_tiles) {
+            t = ticket;
+            if (mine) {
+                a = ws.splits[t * k + lane];
+                b = ws.splits[(t + 1) * k + lane];
+            }
+        }
+        // piece lengths -> offsets (inclusive scan over the lanes); split rows never exceed the run
+        // lengths, and only inputs that break the precondition can make a row pair inconsistent
+        const bool bad = mine && (b < a || b - a > (uint64_t)kTileCap);
+        uint32_t incl = (mine && !bad) ? (uint32_t)(b - a) : 0;
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t v = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += v;
+        }
+        const uint32_t total = __shfl(incl, kWave - 1, kWave);
+        const bool ok = __ballot(bad) == 0 && total <= (uint32_t)kTileCap;
+        if (mine) {
+            s.lo[lane] = a;
+            s.seg[lane + 1] = ok ? incl : 0;
+        }
+        if (lane == 0) {
+            s.seg[0] = 0;
+            s.tile = ticket;
+            s.n = ok ? total : 0;
+            s.failed = ok ? 0 : 1;
+            s.inexact = 0;
+        }
+    }
     __syncthreads();
     const uint64_t tile = s.tile;
     if (tile >= n_tiles) return;  // cannot happen: the grid has exactly n_tiles workgroups
-    if (tid < (int)k) {
-        uint64_t a = ws.splits[tile * k + tid], b = ws.splits[(tile + 1) * k + tid];
-        s.lo[tid] = a;
-        s.run[tid] = rt.ptr[tid];
-        s.seg[tid + 1] = (uint32_t)(b >= a && b - a <= (uint64_t)kTileCap ? b - a : kTileCap + 1);
-    }
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t acc = 0;
-        s.seg[0] = 0;
-        bool ok = true;
-        for (uint32_t j = 0; j < k; j++) {
-            uint32_t len = s.seg[j + 1];
-            if (len > (uint32_t)kTileCap || s.lo[j] + len > rt.n[j]) {  // only inputs that break the precondition
-                ok = false;
-                len = 0;
-            }
-            acc += len;
-            s.seg[j + 1] = acc;
-        }
-        if (acc > (uint32_t)kTileCap) ok = false;
-        s.n = ok ? acc : 0;
-        s.failed = ok ? 0 : 1;
-        s.inexact = 0;
-    }
-    __syncthreads();
     const uint32_t n = s.n;
 
     // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
@@ -366,8 +382,10 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     for (uint32_t width = 1; width < k; width <<= 1) {
         const uint4* in = s.buf[cur];
         uint4* dst = s.buf[cur ^ 1];
-        uint32_t o = tid * kMergeItems;
-        const uint32_t o_end = min(o + (uint32_t)kMergeItems, n);
+        // thread t produces outputs [t * kRoundItems, (t + 1) * kRoundItems): longer serial merges on
+        // fewer threads keep the co-rank searches (most of the LDS reads of a round) a smaller share
+        uint32_t o = tid * kRoundItems;
+        const uint32_t o_end = min(o + (uint32_t)kRoundItems, n);
         while (o < o_end) {
             // the pair of lists whose output range contains position o
             const uint32_t j = piece_of(s.seg, k, top_step, o);
