@@ -115,6 +115,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe-config", action="store_true", help="skip the extra probe measurement on the 100M-entry tree")
     ap.add_argument("--mixed", action="store_true", help="also replay the mixed workload of the 400M-entry tree (about a minute)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="before the steps, run a plain streaming kernel (dst = src + 1 over 1 GiB of int64, 5 launches) "
+                         "whose HBM bytes are known; it scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the index shards by key range without any exchange, "
@@ -151,6 +154,15 @@ def main() -> int:
     torch.cuda.empty_cache()
 
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        src = torch.arange(1 << 27, dtype=torch.int64, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)  # reads 2^30 bytes, writes 2^30 bytes per launch
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     def mk_events(n):
         evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]

@@ -166,7 +166,8 @@ typedef struct {
 int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                       size_t workspace_bytes, void* stream, const lsm_compact_events_t* ev);
 
-/* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments. */
+/* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments.
+ * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per 1984 entries. */
 size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
 
 /*

@@ -44,27 +44,59 @@ __device__ __forceinline__ bool key_equal(const Key& a, const Key& b) {
 
 __device__ __forceinline__ bool key_less_equal(const Key& a, const Key& b) { return !key_less(b, a); }
 
-// key of entry e < k, reading the second half of e's key only when the first 16 bytes tie
-__device__ __forceinline__ bool entry_key_less(const lsm_entry_t* e, const Key& k) {
-    const uint4* q = reinterpret_cast<const uint4*>(e);
-    const uint4 lo = q[0];
-    const uint64_t w0 = __builtin_bswap64(((uint64_t)lo.y << 32) | lo.x);
-    const uint64_t w1 = __builtin_bswap64(((uint64_t)lo.w << 32) | lo.z);
+// key < k for a key kept as two separate halves (bytes 0..15 at lo, bytes 16..31 at hi); the second
+// half is read only when the first 16 bytes tie.
+__device__ __forceinline__ bool entry_key_less(const uint4* lo, const uint4* hi, const Key& k) {
+    const uint4 a = *lo;
+    const uint64_t w0 = __builtin_bswap64(((uint64_t)a.y << 32) | a.x);
+    const uint64_t w1 = __builtin_bswap64(((uint64_t)a.w << 32) | a.z);
     if (w0 != k.w[0]) return w0 < k.w[0];
     if (w1 != k.w[1]) return w1 < k.w[1];
-    const uint4 hi = q[1];
-    const uint64_t w2 = __builtin_bswap64(((uint64_t)hi.y << 32) | hi.x);
-    const uint64_t w3 = __builtin_bswap64(((uint64_t)hi.w << 32) | hi.z);
+    const uint4 b = *hi;
+    const uint64_t w2 = __builtin_bswap64(((uint64_t)b.y << 32) | b.x);
+    const uint64_t w3 = __builtin_bswap64(((uint64_t)b.w << 32) | b.z);
     if (w2 != k.w[2]) return w2 < k.w[2];
     return w3 < k.w[3];
 }
 
-// Number of entries of run[lo, hi) whose key is < k, plus lo.  Global memory.
-__device__ __forceinline__ uint64_t lower_bound_run(const lsm_entry_t* run, uint64_t lo, uint64_t hi, const Key& k) {
+// Three-way compare of a record's key with k (-1, 0, +1) given the record's first 16 key bytes;
+// the second half is read only when those tie.
+template <typename E>
+__device__ __forceinline__ int entry_key_cmp(const E* e, const uint4 lo, const Key& k) {
+    const uint64_t w0 = __builtin_bswap64(((uint64_t)lo.y << 32) | lo.x);
+    const uint64_t w1 = __builtin_bswap64(((uint64_t)lo.w << 32) | lo.z);
+    if (w0 != k.w[0]) return w0 < k.w[0] ? -1 : 1;
+    if (w1 != k.w[1]) return w1 < k.w[1] ? -1 : 1;
+    const uint4 hi = reinterpret_cast<const uint4*>(e)[1];
+    const uint64_t w2 = __builtin_bswap64(((uint64_t)hi.y << 32) | hi.x);
+    const uint64_t w3 = __builtin_bswap64(((uint64_t)hi.w << 32) | hi.z);
+    if (w2 != k.w[2]) return w2 < k.w[2] ? -1 : 1;
+    if (w3 != k.w[3]) return w3 < k.w[3] ? -1 : 1;
+    return 0;
+}
+
+// The probe position of a search step in [lo, hi), lo < hi: the index with the most trailing zero
+// bits.  Positions then form one fixed search tree over the whole array whatever range a search
+// starts from, so searches for nearby keys - and repeated searches in a shrinking range - read the
+// same few records (the ancestors of the answer) instead of a fresh set of midpoints each time.
+__device__ __forceinline__ uint64_t tree_mid(uint64_t lo, uint64_t hi) {
+    const uint64_t last = hi - 1, diff = lo ^ last;
+    if (diff == 0) return lo;
+    const int top = 63 - __builtin_clzll(diff);  // highest bit in which lo and last differ: set in last, clear in lo
+    return last & ~((1ull << top) - 1);
+}
+
+// Number of records of run[lo, hi) whose key is < k, plus lo (global memory), by bisection along
+// the fixed tree.  eq tells whether the record at the result lies inside
+// [lo, hi) and has exactly the key k.
+template <typename E>
+__device__ __forceinline__ uint64_t lower_bound_eq(const E* run, uint64_t lo, uint64_t hi, const Key& k, bool& eq) {
+    eq = false;  // always describes the record at the current hi
     while (lo < hi) {
-        uint64_t mid = lo + ((hi - lo) >> 1);
-        if (entry_key_less(run + mid, k)) lo = mid + 1;
-        else hi = mid;
+        const uint64_t mid = tree_mid(lo, hi);
+        const int c = entry_key_cmp(run + mid, *reinterpret_cast<const uint4*>(run + mid), k);
+        if (c < 0) lo = mid + 1;
+        else hi = mid, eq = c == 0;
     }
     return lo;
 }

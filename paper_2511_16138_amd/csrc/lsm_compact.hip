@@ -29,7 +29,9 @@ constexpr int kMergeItems = 4;
 constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
 constexpr int kRoundItems = 4;                         // outputs per thread in a merge round
 constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
-constexpr uint64_t kCoarseStride = 32;                 // every 32nd boundary is searched over whole runs first
+constexpr uint64_t kCoarseStride = 32;                 // every 32nd boundary is searched over whole sequences first
+constexpr uint64_t kSampleStride = 32;                 // one key in 32 is copied for the sampled partition
+constexpr uint64_t kSampledMinTiles = 65;              // inputs of fewer tiles search the runs directly
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
 
 // Tile status word: top two bits = state, low 62 bits = value.
@@ -44,15 +46,28 @@ struct Header {  // first 256 bytes of the workspace
 };
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
+// A bare 32-byte key: one sample of a run.
+struct SampleKey {
+    uint4 q[2];
+};
+
+struct SampleTable {
+    SampleKey* ptr[LSM_MAX_RUNS];
+    uint64_t m[LSM_MAX_RUNS];  // samples of run j = ceil(n[j] / kSampleStride)
+};
+
 struct Workspace {
     Header* hdr;
-    uint64_t* status;  // [n_tiles]
-    uint64_t* splits;  // [(n_tiles + 1) * k]
+    uint64_t* status;   // [n_tiles]
+    uint64_t* splits;   // [(n_tiles + 1) * k]
+    uint64_t* ycoarse;  // [(n_coarse + 2) * k]   sample-space splits of every kCoarseStride-th boundary
+    uint64_t* ywin;     // [2 * (n_tiles - 1) * k] sample-space brackets of every boundary
+    SampleTable st;
 };
 
 __host__ __device__ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-__global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_t* n_out) {
+__global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_t n_coarse, uint64_t* n_out) {
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     if (i == 0) {
@@ -64,17 +79,25 @@ __global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_
     if (i < rt.k) {
         ws.splits[i] = 0;
         ws.splits[n_tiles * rt.k + i] = rt.n[i];
+        ws.ycoarse[i] = 0;
+        ws.ycoarse[(n_coarse + 1) * rt.k + i] = ws.st.m[i];
     }
 }
 
 // ---------------------------------------------------------------------------------------
-// Partition: a group of G lanes (G = smallest power of two >= k) works on one boundary, lane
-// j of the group owns run j, and a wave handles 64/G boundaries at once.  Candidates for x are
-// the entries still inside [lo_j, hi_j) of every run; each step takes the middle entry of the
-// widest range as pivot, every lane finds the pivot's lower bound in its own range, and the
-// sum over the group decides which side of the pivot survives.  The pivot always leaves its
-// range and the widest range at least halves, so the loop ends after at most
-// k * log2(longest run) steps whatever the input.
+// Partition: a group of G lanes (G = smallest power of two >= k) works on one selection
+// problem, lane j of the group owns sequence j, and a wave handles 64/G problems at once.
+// For a target rank r the problem is: among the records still inside [lo_j, hi_j) of every
+// sequence, find the key x with the largest L(x) = sum_j |{e in sequence j : e.key < x}| that
+// is still <= r, and return the k lower bounds of x.  Each step takes a record of the widest
+// range as pivot, every lane finds the pivot's lower bound in its own range, and the sum over
+// the group decides which side of the pivot survives.  The pivot always leaves its range and
+// the widest range at least halves every third step, so the loop ends after at most
+// 3 * k * log2(longest sequence) steps whatever the input.
+//
+// The ranges need not be cuts of one key: it is enough that lo_j <= (the answer's lower bound
+// in j) <= hi_j and that the answer itself lies inside its own sequence's range.  Lower bounds
+// are then clamped into the ranges, which never changes on which side of r a sum falls.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ uint64_t group_sum_u64(uint64_t v, int group) {
     for (int off = group >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
@@ -88,43 +111,43 @@ __device__ __forceinline__ uint64_t group_max_u64(uint64_t v, int group) {
     return v;
 }
 
-// The kernel runs twice: first for the boundaries that are multiples of `coarse` (search over
-// whole runs), then for the others, whose search starts from the enclosing coarse boundaries
-// (splits are monotone in the boundary number, so those are valid bounds).
-__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group,
-                                                         uint64_t coarse, int fine_pass) {
-    const int lane = threadIdx.x & (kWave - 1);
-    const int member = lane & (group - 1);   // run owned by this lane
-    const int group_base = lane - member;
-    const uint64_t wave_id = (uint64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    const uint64_t slot = wave_id * (uint64_t)(kWave / group) + (uint64_t)(lane / group);
-    // coarse pass: b = coarse, 2*coarse, ...; fine pass: every b in 1..n_tiles-1 that is not a multiple of coarse
-    const uint64_t b = fine_pass ? slot + slot / (coarse - 1) + 1 : (slot + 1) * coarse;
-    const bool valid = b < n_tiles;
-    const uint64_t r = b * (uint64_t)kTileNominal;
-    const bool own = valid && member < (int)rt.k;
-    const lsm_entry_t* run = own ? rt.ptr[member] : nullptr;
-    uint64_t lo = 0, hi = own ? rt.n[member] : 0, best = 0;
-    if (fine_pass && own) {
-        const uint64_t below = b - b % coarse, above = below + coarse < n_tiles ? below + coarse : n_tiles;
-        lo = best = ws.splits[below * rt.k + member];
-        hi = ws.splits[above * rt.k + member];
-        if (hi > rt.n[member]) hi = rt.n[member];  // only inputs that break the precondition
-        if (lo > hi) lo = best = hi;
+constexpr int kTailKeys = 4;  // ranges this short are finished from registers
+
+// One step's bookkeeping once every lane has its lower bound lb (and whether the record there equals the pivot).
+__device__ __forceinline__ void select_update(uint64_t& lo, uint64_t& hi, uint64_t& best, const uint64_t lb, const bool eq,
+                                              const uint64_t mid, const bool is_src, const bool active, const bool own,
+                                              const uint64_t r, const int group) {
+    const uint64_t total = group_sum_u64(own ? lb : 0, group);
+    if (!active) return;
+    // on sorted input the pivot's own lane has lb == mid; the clamps only matter for inputs that
+    // break the precondition, where they still shrink the widest range
+    const uint64_t ub = lb + (eq ? 1 : 0);
+    if (total <= r) {
+        best = lb;
+        lo = (is_src && ub < mid + 1) ? mid + 1 : ub;
+    } else {
+        hi = (is_src && lb > mid) ? mid : lb;
     }
+}
+
+template <typename E>
+__device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint64_t hi, const uint64_t r, const bool own,
+                                                 const int member, const int group, const int group_base) {
+    uint64_t best = lo;
+    // phase 1: pivots and lower bounds from memory, until every range of the group is at most kTailKeys long
     for (uint32_t iter = 0;; iter++) {
         const uint64_t width = hi - lo;
         const uint64_t widest = group_max_u64((width << 6) | (uint64_t)member, group);
-        const bool active = (widest >> 6) != 0;
+        const bool active = (widest >> 6) > (uint64_t)kTailKeys;
         if (__ballot(active) == 0) break;
         const int src = (int)(widest & 63);
-        uint64_t mid = lo + (width >> 1);
+        uint64_t mid = width ? tree_mid(lo, hi) : lo;
         if (iter % 3 != 2) {
             // interpolation steps: the candidates are the merged ranks [sum lo, sum hi); aim the pivot at
             // the same fraction of the widest range as a target rank is of that interval.  The target
             // is r minus, then r plus, about two standard deviations of the estimate (2 * sqrt of the
-            // interval), so that two steps bracket x from both sides.  Every third step stays at the
-            // middle of the widest range, which keeps the worst case logarithmic.
+            // interval), so that two steps bracket x from both sides.  Every third step takes the
+            // widest range's node of the fixed search tree, which keeps the worst case logarithmic.
             const uint64_t rank_lo = group_sum_u64(own ? lo : 0, group), rank_hi = group_sum_u64(own ? hi : 0, group);
             uint64_t span = rank_hi - rank_lo, ahead = r > rank_lo ? r - rank_lo : 0;
             const uint64_t margin = span ? 2ull << ((64 - __builtin_clzll(span)) >> 1) : 0;
@@ -139,30 +162,169 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
             if (rank_hi - rank_lo >= 256 && width > 0 && width <= 0xFFFFFFFFull) {  // few candidates left: plain bisection
                 mid = lo + ((width * frac) >> 32);
                 if (mid >= hi) mid = hi - 1;
+                // the roundest position within 1/16 of the range around the aim: likely read before, or again later
+                const uint64_t slack = width >> 4;
+                mid = tree_mid(mid - lo > slack ? mid - slack : lo, hi - mid > slack + 1 ? mid + slack + 1 : hi);
             }
         }
         Key pivot = {{0, 0, 0, 0}};
         if (active && member == src) pivot = load_key(run + mid);
         for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], group_base + src, kWave);
-        uint64_t lb = lo, ub = lo;
-        if (own && active) {
-            lb = lower_bound_run(run, lo, hi, pivot);
-            ub = lb;
-            if (lb < hi && key_equal(load_key(run + lb), pivot)) ub = lb + 1;
-        }
-        const uint64_t total = group_sum_u64(own ? lb : 0, group);
-        if (active) {
-            // on sorted input the pivot's own lane has lb == mid; the clamps only matter for
-            // inputs that break the precondition, where they still halve the widest range
-            if (total <= r) {
-                best = lb;
-                lo = (member == src && ub < mid + 1) ? mid + 1 : ub;
-            } else {
-                hi = (member == src && lb > mid) ? mid : lb;
-            }
-        }
+        uint64_t lb = lo;
+        bool eq = false;
+        if (own && active) lb = lower_bound_eq(run, lo, hi, pivot, eq);
+        select_update(lo, hi, best, lb, eq, mid, member == src, active, own, r, group);
     }
-    if (own) ws.splits[b * rt.k + member] = best;
+    // phase 2: the same steps on the at most kTailKeys keys per range that are left, held in registers
+    const uint64_t base = lo;
+    const int cnt = (int)(hi - lo);  // <= kTailKeys
+    Key kk[kTailKeys];
+    for (int i = 0; i < kTailKeys; i++) kk[i] = i < cnt ? load_key(run + base + i) : Key{{0, 0, 0, 0}};
+    for (;;) {
+        const uint64_t width = hi - lo;
+        const uint64_t widest = group_max_u64((width << 6) | (uint64_t)member, group);
+        const bool active = (widest >> 6) != 0;
+        if (__ballot(active) == 0) break;
+        const int src = (int)(widest & 63);
+        const uint64_t mid = lo + (width >> 1);
+        const int at = (int)(mid - base);
+        Key pivot = kk[0];
+        for (int i = 1; i < kTailKeys; i++)
+            if (at == i) pivot = kk[i];
+        for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], group_base + src, kWave);
+        uint64_t lb = base;
+        for (int i = 0; i < kTailKeys; i++) lb += (i < cnt && key_less(kk[i], pivot)) ? 1 : 0;
+        lb = lb < lo ? lo : (lb > hi ? hi : lb);
+        bool eq = false;
+        for (int i = 0; i < kTailKeys; i++) eq = eq || (lb < hi && lb == base + i && key_equal(kk[i], pivot));
+        select_update(lo, hi, best, lb, eq, mid, member == src, active, own, r, group);
+    }
+    return best;
+}
+
+// Lane bookkeeping shared by the partition kernels: which problem and which sequence a lane has.
+struct GroupLane {
+    int member, group_base;
+    uint64_t slot;
+};
+__device__ __forceinline__ GroupLane group_lane(int group) {
+    const int lane = threadIdx.x & (kWave - 1);
+    GroupLane g;
+    g.member = lane & (group - 1);
+    g.group_base = lane - g.member;
+    const uint64_t wave_id = (uint64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    g.slot = wave_id * (uint64_t)(kWave / group) + (uint64_t)(lane / group);
+    return g;
+}
+
+// Direct search over the runs, for inputs of a few tiles.  The kernel runs twice: first for the
+// boundaries that are multiples of `coarse` (search over whole runs), then for the others, whose
+// search starts from the enclosing coarse boundaries (splits are monotone in the boundary number,
+// so those are valid bounds).
+__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group,
+                                                         uint64_t coarse, int fine_pass) {
+    const GroupLane g = group_lane(group);
+    // coarse pass: b = coarse, 2*coarse, ...; fine pass: every b in 1..n_tiles-1 that is not a multiple of coarse
+    const uint64_t b = fine_pass ? g.slot + g.slot / (coarse - 1) + 1 : (g.slot + 1) * coarse;
+    const bool valid = b < n_tiles;
+    const uint64_t r = b * (uint64_t)kTileNominal;
+    const bool own = valid && g.member < (int)rt.k;
+    const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
+    uint64_t lo = 0, hi = own ? rt.n[g.member] : 0;
+    if (fine_pass && own) {
+        const uint64_t below = b - b % coarse, above = below + coarse < n_tiles ? below + coarse : n_tiles;
+        lo = ws.splits[below * rt.k + g.member];
+        hi = ws.splits[above * rt.k + g.member];
+        if (hi > rt.n[g.member]) hi = rt.n[g.member];  // only inputs that break the precondition
+        if (lo > hi) lo = hi;
+    }
+    const uint64_t best = select_split(run, lo, hi, r, own, g.member, group, g.group_base);
+    if (own) ws.splits[b * rt.k + g.member] = best;
+}
+
+// ---------------------------------------------------------------------------------------
+// Sampled partition, for large inputs.  Searching the runs directly costs tens of scattered
+// 64-byte reads per boundary and run, which is HBM traffic of the order of the merge itself.
+// Instead every kSampleStride-th key of each run is copied into a compact array (1/64 of the
+// input bytes: it stays in the last-level cache), the selection is done on the samples, and the
+// runs themselves are only searched inside the few dozen entries the samples leave open.
+//
+// With s = kSampleStride, a key P that has y_j samples below it in run j has x_j entries below
+// it with s * (y_j - 1) < x_j <= s * y_j, so for Y = sum y_j:  s * (Y - k) < L(P) <= s * Y.
+//   lower bracket: the sample key with the largest Y <= floor(r / s) has L <= r, so it is <= x;
+//   upper bracket: the sample key with the largest Y <= ceil(r / s) + 2k - 1 has, if a larger sample
+//                  exists at all, Y >= ceil(r / s) + k and therefore L > r: it is > x.
+// The answer's lower bound in run j then lies in [s * (ylo_j - 1) + 1, s * yhi_j] (clamped to the run).
+// The sample-space problems are themselves solved coarse first: every kCoarseStride-th boundary
+// over whole sample arrays, the rest between the coarse rows that enclose their targets.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) sample_kernel(RunTable rt, SampleTable st) {
+    const uint32_t j = blockIdx.y;
+    const uint4* src = reinterpret_cast<const uint4*>(rt.ptr[j]);
+    uint4* dst = reinterpret_cast<uint4*>(st.ptr[j]);
+    const uint64_t n16 = st.m[j] * 2, stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[(i >> 1) * (kSampleStride * 4) + (i & 1)];  // 4 uint4 per entry; two lanes copy one key
+}
+
+__device__ __forceinline__ uint64_t sample_target(uint64_t b, int side, uint32_t k) {
+    const uint64_t r = b * (uint64_t)kTileNominal;
+    return side ? (r + kSampleStride - 1) / kSampleStride + 2ull * k - 1 : r / kSampleStride;
+}
+
+// coarse rows: row c (1 <= c <= n_coarse) = lower bracket of boundary c * kCoarseStride over whole sample arrays
+__global__ void __launch_bounds__(256) sample_coarse_kernel(Workspace ws, uint32_t k, uint64_t n_coarse, int group) {
+    const GroupLane g = group_lane(group);
+    const uint64_t c = g.slot + 1;
+    const bool own = c <= n_coarse && g.member < (int)k;
+    const SampleKey* run = own ? ws.st.ptr[g.member] : nullptr;
+    const uint64_t best = select_split(run, 0, own ? ws.st.m[g.member] : 0, sample_target(c * kCoarseStride, 0, k), own,
+                                       g.member, group, g.group_base);
+    if (own) ws.ycoarse[c * k + g.member] = best;
+}
+
+// problem p = 2 * (b - 1) + side for boundary b; targets of boundaries [c * stride, (c + 1) * stride) lie
+// between those of coarse rows c and c + 2 (the upper bracket overshoots by 2k - 1 <= one coarse step)
+__global__ void __launch_bounds__(256) sample_fine_kernel(Workspace ws, uint32_t k, uint64_t n_tiles, uint64_t n_coarse, int group) {
+    const GroupLane g = group_lane(group);
+    const uint64_t b = g.slot / 2 + 1;
+    const int side = (int)(g.slot & 1);
+    const bool own = b < n_tiles && g.member < (int)k;
+    const SampleKey* run = own ? ws.st.ptr[g.member] : nullptr;
+    uint64_t lo = 0, hi = 0;
+    if (own) {
+        const uint64_t c = b / kCoarseStride, above = c + 2 < n_coarse + 1 ? c + 2 : n_coarse + 1;
+        lo = ws.ycoarse[c * k + g.member];
+        hi = ws.ycoarse[above * k + g.member];
+        if (hi > ws.st.m[g.member]) hi = ws.st.m[g.member];  // only inputs that break the precondition
+        if (lo > hi) lo = hi;
+    }
+    const uint64_t best = select_split(run, lo, hi, sample_target(b, side, k), own, g.member, group, g.group_base);
+    if (own) ws.ywin[g.slot * k + g.member] = best;
+}
+
+// the boundary itself, searched inside the brackets
+__global__ void __launch_bounds__(256) bracket_partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group) {
+    const GroupLane g = group_lane(group);
+    const uint64_t b = g.slot + 1;
+    const bool own = b < n_tiles && g.member < (int)rt.k;
+    const uint64_t r = b * (uint64_t)kTileNominal;
+    const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
+    uint64_t lo = 0, hi = 0, yhi = 0;
+    if (own) {
+        const uint64_t n = rt.n[g.member];
+        const uint64_t ylo = ws.ywin[(2 * (b - 1)) * rt.k + g.member];
+        yhi = ws.ywin[(2 * (b - 1) + 1) * rt.k + g.member];
+        lo = ylo ? (ylo - 1) * kSampleStride + 1 : 0;
+        hi = yhi * kSampleStride;
+        if (hi > n) hi = n;
+    }
+    // no sample above the upper target: the upper bracket proves nothing, search to the end of the runs
+    const uint64_t y_total = group_sum_u64(own ? yhi : 0, group);
+    if (own && y_total < (r + kSampleStride - 1) / kSampleStride + rt.k) hi = rt.n[g.member];
+    if (lo > hi) lo = hi;  // only inputs that break the precondition
+    const uint64_t best = select_split(run, lo, hi, r, own, g.member, group, g.group_base);
+    if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -492,8 +654,20 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         }
     } else {
         // ---- exact path: merged position and winner of every entry by binary search over the
-        //      tile's pieces in global memory, full 32-byte compares, order (key, run index)
+        //      tile's other pieces with full 32-byte compares, order (key, run index).  The keys
+        //      are staged in LDS in entry order (the info arrays are not needed any more), so only
+        //      the seqno of an equal key in another piece is read from global memory.
         __syncthreads();
+        uint4* klo = s.buf[0];  // key bytes 0..15 of entry e
+        uint4* khi = s.buf[1];  // key bytes 16..31
+#pragma unroll
+        for (int i = 0; i < kMergeItems; i++) {
+            const uint32_t e = tid + i * kMergeThreads;
+            if (e < n) {
+                klo[e] = ent[i][0];
+                khi[e] = ent[i][1];
+            }
+        }
         for (uint32_t o = tid; o <= n; o += kMergeThreads) s.flag[o] = 0;
         __syncthreads();
 #pragma unroll
@@ -507,12 +681,16 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
                 bool win = true;
                 for (uint32_t j2 = 0; j2 < k; j2++) {
                     if (j2 == j) continue;
-                    const lsm_entry_t* run = s.run[j2];
-                    const uint64_t first = s.lo[j2], last = first + (s.seg[j2 + 1] - s.seg[j2]);
-                    const uint64_t lb = lower_bound_run(run, first, last, x);
-                    p += (uint32_t)(lb - first);
-                    if (lb < last && key_equal(load_key(run + lb), x)) {
-                        const uint64_t other = run[lb].seqno;
+                    const uint32_t first = s.seg[j2], last = s.seg[j2 + 1];
+                    uint32_t lb = first, ub = last;
+                    while (lb < ub) {
+                        const uint32_t mid = (lb + ub) >> 1;
+                        if (entry_key_less(&klo[mid], &khi[mid], x)) lb = mid + 1;
+                        else ub = mid;
+                    }
+                    p += lb - first;
+                    if (lb < last && key_equal(key_from_raw(klo[lb], khi[lb]), x)) {
+                        const uint64_t other = s.run[j2][s.lo[j2] + (lb - first)].seqno;
                         if (other > seq || (other == seq && j2 < j)) win = false;
                         if (j2 < j) p++;
                     }
@@ -604,27 +782,40 @@ __global__ void validate_kernel(RunTable rt, Workspace ws) {
     if (bad) atomicOr(&ws.hdr->validate_status, bad);
 }
 
-static Workspace carve(void* base, uint64_t n_tiles, uint32_t k) {
-    char* p = static_cast<char*>(base);
-    Workspace ws;
-    ws.hdr = reinterpret_cast<Header*>(p);
-    ws.status = reinterpret_cast<uint64_t*>(p + sizeof(Header));
-    ws.splits = reinterpret_cast<uint64_t*>(p + sizeof(Header) + align256(n_tiles * sizeof(uint64_t)));
-    (void)k;
-    return ws;
-}
-
 static uint64_t tiles_for(uint64_t total) { return (total + kTileNominal - 1) / kTileNominal; }
+static uint64_t coarse_rows(uint64_t n_tiles) { return n_tiles > 1 ? (n_tiles - 1) / kCoarseStride : 0; }
+
+// Lays the workspace out; with base == nullptr it only measures.  Returns the bytes used.
+static size_t carve(void* base, const uint64_t* run_lens, uint32_t k, Workspace* ws) {
+    uint64_t total = 0;
+    for (uint32_t j = 0; j < k; j++) total += run_lens[j];
+    const uint64_t n_tiles = tiles_for(total), n_coarse = coarse_rows(n_tiles);
+    char* p = static_cast<char*>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* at = p ? p + off : nullptr;
+        off += align256(bytes);
+        return at;
+    };
+    Workspace w;
+    w.hdr = reinterpret_cast<Header*>(take(sizeof(Header)));
+    w.status = reinterpret_cast<uint64_t*>(take(n_tiles * sizeof(uint64_t)));
+    w.splits = reinterpret_cast<uint64_t*>(take((n_tiles + 1) * (uint64_t)k * sizeof(uint64_t)));
+    w.ycoarse = reinterpret_cast<uint64_t*>(take((n_coarse + 2) * (uint64_t)k * sizeof(uint64_t)));
+    w.ywin = reinterpret_cast<uint64_t*>(take(2 * (n_tiles ? n_tiles - 1 : 0) * (uint64_t)k * sizeof(uint64_t)));
+    for (uint32_t j = 0; j < LSM_MAX_RUNS; j++) {
+        w.st.m[j] = j < k ? (run_lens[j] + kSampleStride - 1) / kSampleStride : 0;
+        w.st.ptr[j] = j < k ? reinterpret_cast<SampleKey*>(take(w.st.m[j] * sizeof(SampleKey))) : nullptr;
+    }
+    if (ws) *ws = w;
+    return off;
+}
 
 }  // namespace lsm
 
 extern "C" size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs) {
     if (run_lens == nullptr || n_runs == 0 || n_runs > LSM_MAX_RUNS) return 0;
-    uint64_t total = 0;
-    for (uint32_t j = 0; j < n_runs; j++) total += run_lens[j];
-    uint64_t n_tiles = lsm::tiles_for(total);
-    return sizeof(lsm::Header) + lsm::align256(n_tiles * sizeof(uint64_t)) +
-           lsm::align256((n_tiles + 1) * (uint64_t)n_runs * sizeof(uint64_t));
+    return lsm::carve(nullptr, run_lens, n_runs, nullptr);
 }
 
 extern "C" int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
@@ -662,12 +853,14 @@ extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_
     const uint64_t n_tiles = tiles_for(total);
     if (n_tiles >= (1ull << 31)) return LSM_ERR_BAD_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    Workspace ws = carve(workspace, n_tiles, n_runs);
+    Workspace ws;
+    carve(workspace, lens, n_runs, &ws);
+    const uint64_t n_coarse = coarse_rows(n_tiles);  // boundaries kCoarseStride, 2 * kCoarseStride, ... < n_tiles
 
     uint32_t init_blocks = (uint32_t)((n_tiles + 255) / 256);
     if (init_blocks == 0) init_blocks = 1;
     if (init_blocks > 1024) init_blocks = 1024;
-    hipLaunchKernelGGL(init_kernel, dim3(init_blocks), dim3(256), 0, stream, rt, ws, n_tiles, out->n_out);
+    hipLaunchKernelGGL(init_kernel, dim3(init_blocks), dim3(256), 0, stream, rt, ws, n_tiles, n_coarse, out->n_out);
 
     if (flags & LSM_VALIDATE) {
         hipLaunchKernelGGL(validate_kernel, dim3(256, n_runs), dim3(256), 0, stream, rt, ws);
@@ -683,16 +876,24 @@ extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_
     if (n_tiles > 1) {
         int group = 1;
         while (group < (int)n_runs) group <<= 1;
-        const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);  // boundaries per workgroup
-        const uint64_t coarse = kCoarseStride;
-        const uint64_t n_coarse = (n_tiles - 1) / coarse;  // boundaries coarse, 2*coarse, ... < n_tiles
-        const uint64_t n_fine = (n_tiles - 1) - n_coarse;
-        if (n_coarse > 0)
-            hipLaunchKernelGGL(partition_kernel, dim3((uint32_t)((n_coarse + per_block - 1) / per_block)), dim3(256), 0, stream,
-                               rt, ws, n_tiles, group, coarse, 0);
-        if (n_fine > 0)
-            hipLaunchKernelGGL(partition_kernel, dim3((uint32_t)((n_fine + per_block - 1) / per_block)), dim3(256), 0, stream,
-                               rt, ws, n_tiles, group, coarse, 1);
+        const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);  // selection problems per workgroup
+        auto blocks = [&](uint64_t problems) { return dim3((uint32_t)((problems + per_block - 1) / per_block)); };
+        if (n_tiles < kSampledMinTiles) {
+            const uint64_t n_fine = (n_tiles - 1) - n_coarse;
+            if (n_coarse > 0)
+                hipLaunchKernelGGL(partition_kernel, blocks(n_coarse), dim3(256), 0, stream, rt, ws, n_tiles, group, kCoarseStride, 0);
+            if (n_fine > 0)
+                hipLaunchKernelGGL(partition_kernel, blocks(n_fine), dim3(256), 0, stream, rt, ws, n_tiles, group, kCoarseStride, 1);
+        } else {
+            uint64_t m_max = 0;
+            for (uint32_t j = 0; j < n_runs; j++) m_max = ws.st.m[j] > m_max ? ws.st.m[j] : m_max;
+            uint64_t sample_blocks = (2 * m_max + 255) / 256;
+            if (sample_blocks > 4096) sample_blocks = 4096;
+            hipLaunchKernelGGL(sample_kernel, dim3((uint32_t)sample_blocks, n_runs), dim3(256), 0, stream, rt, ws.st);
+            hipLaunchKernelGGL(sample_coarse_kernel, blocks(n_coarse), dim3(256), 0, stream, ws, n_runs, n_coarse, group);
+            hipLaunchKernelGGL(sample_fine_kernel, blocks(2 * (n_tiles - 1)), dim3(256), 0, stream, ws, n_runs, n_tiles, n_coarse, group);
+            hipLaunchKernelGGL(bracket_partition_kernel, blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
+        }
     }
     if (ev && ev->before_merge && hipEventRecord(static_cast<hipEvent_t>(ev->before_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
