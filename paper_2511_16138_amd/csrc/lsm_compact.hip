@@ -336,11 +336,13 @@ __global__ void __launch_bounds__(256) bracket_partition_kernel(RunTable rt, Wor
 // the entry's tile-local index in the low 16 bits.  Surrogates are merged with stable
 // two-way merge-path merges (the left list = lower run indices wins ties).  Afterwards each
 // merged position gets the rest of its key (bytes 14..31), its seqno and its type, so that
-// neighbours can be compared exactly: equal surrogates with different key tails mean the
-// 14-byte order was not enough, and the tile is redone by the exact path below (ranks by
-// binary search over the tile's pieces in global memory with full 32-byte compares).
+// neighbours can be compared exactly.  Equal surrogates with different key tails mean the
+// 14-byte order was not enough: a short group of such positions is put in key order in place
+// (one thread, insertion sort by the tail), and a tile with a longer group is redone by the
+// exact path below (ranks by binary search over the tile's pieces with full 32-byte compares).
 // ---------------------------------------------------------------------------------------
 enum : uint8_t { kFlagEq = 1, kFlagFullEq = 2, kFlagSurvive = 4 };
+constexpr int kRepairMax = 32;                // longest prefix-tie group one thread puts in key order
 constexpr int kStageEntries = kTileCap / 2;  // output staging: 64 bytes per survivor, two passes at most
 
 struct MergeShared {
@@ -439,6 +441,15 @@ __device__ uint64_t lookback(uint64_t* status, uint64_t tile, uint64_t count, bo
     uint64_t word = bad ? (kStFailed << kStShift) : ((kStPrefix << kStShift) | (base + count));
     if (lane == 0) __hip_atomic_store(&status[tile], word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return base;
+}
+
+// order of two entries with the same 14-byte key prefix by the rest of the key, from their info words
+__device__ __forceinline__ bool tail_less(const uint4 a0, const uint4 a1, const uint4 b0, const uint4 b1) {
+    const uint32_t ta = ((a0.z >> 8) & 0xFF) << 8 | ((a0.z >> 16) & 0xFF), tb = ((b0.z >> 8) & 0xFF) << 8 | ((b0.z >> 16) & 0xFF);
+    if (ta != tb) return ta < tb;  // key bytes 14, 15
+    const uint64_t a2 = __builtin_bswap64(((uint64_t)a1.y << 32) | a1.x), b2 = __builtin_bswap64(((uint64_t)b1.y << 32) | b1.x);
+    if (a2 != b2) return a2 < b2;  // key bytes 16..23
+    return __builtin_bswap64(((uint64_t)a1.w << 32) | a1.z) < __builtin_bswap64(((uint64_t)b1.w << 32) | b1.z);
 }
 
 __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
@@ -603,7 +614,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     __syncthreads();
 
     // ---- every owner posts key bytes 14..31, seqno and type of its entries at their merged positions
-    uint4* info0 = s.buf[0];  // {seqno lo, seqno hi, type | key bytes 14..15 << 8, 0} of the entry at a position
+    uint4* info0 = s.buf[0];  // {seqno lo, seqno hi, type | key bytes 14..15 << 8, entry index} of the entry at a position
     uint4* info1 = s.buf[1];  // its key bytes 16..31
 #pragma unroll
     for (int i = 0; i < kMergeItems; i++) {
@@ -611,7 +622,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
         if (e < n) {
             const uint32_t p = s.rank[e];
             pos[i] = p;
-            info0[p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, 0);
+            info0[p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, e);
             info1[p] = ent[i][1];
         }
     }
@@ -633,7 +644,50 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Works
     }
     __syncthreads();
 
-    if (s.inexact == 0) {
+    if (s.inexact != 0) {
+        // ---- repair: positions that share the 14-byte prefix but not the whole key stand in run order, not in
+        //      key order.  The thread whose share holds the first position of such a group sorts the group by the
+        //      rest of the key (stable, so equal keys keep their run order); a group too long for one thread
+        //      sends the whole tile to the exact path instead.
+        const uint32_t o0 = tid * kMergeItems;
+        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
+            if ((s.flag[o] & kFlagEq) != 0 || (s.flag[o + 1] & kFlagEq) == 0) continue;  // flag[n] is 0
+            uint32_t end = o + 1;
+            bool broken = false;
+            for (; s.flag[end] & kFlagEq; end++) broken = broken || (s.flag[end] & kFlagFullEq) == 0;
+            if (!broken) continue;
+            if (end - o > (uint32_t)kRepairMax) {
+                s.inexact = 2;
+                continue;
+            }
+            for (uint32_t a = o + 1; a < end; a++) {
+                const uint4 x0 = info0[a], x1 = info1[a];
+                uint32_t b = a;
+                for (; b > o && tail_less(x0, x1, info0[b - 1], info1[b - 1]); b--) {
+                    info0[b] = info0[b - 1];
+                    info1[b] = info1[b - 1];
+                }
+                info0[b] = x0;
+                info1[b] = x1;
+            }
+            s.rank[info0[o].w] = (uint16_t)o;
+            for (uint32_t a = o + 1; a < end; a++) {
+                const bool same = !tail_less(info0[a - 1], info1[a - 1], info0[a], info1[a]);  // sorted: not less = equal
+                s.flag[a] = same ? (kFlagEq | kFlagFullEq) : kFlagEq;
+                s.rank[info0[a].w] = (uint16_t)a;
+            }
+        }
+        __syncthreads();
+        if (s.inexact == 1) {
+#pragma unroll
+            for (int i = 0; i < kMergeItems; i++) {
+                const uint32_t e = tid + i * kMergeThreads;
+                if (e < n) pos[i] = s.rank[e];
+            }
+        }
+    }
+
+    if (s.inexact != 2) {
         // ---- survivors: newest version of each key (largest seqno, ties to the earlier = lower run),
         //      minus winning tombstones when the output is the last level
         const uint32_t o0 = tid * kMergeItems;

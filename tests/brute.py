@@ -112,3 +112,28 @@ def random_runs(rs: np.random.RandomState, n_runs: int, max_len: int, alphabet: 
                                   int(rs.randint(0, 1 << 31))))
         runs.append(run)
     return runs
+
+
+def tie_group_runs(rs: np.random.RandomState, n_runs: int, n_heads: int, long_groups: int = 0) -> List[List[bytes]]:
+    """Runs whose keys fall into groups that share their first 14 bytes and differ somewhere in
+    bytes 14..31 (each of the later byte ranges decides for some pair).  Most groups have one to
+    eight members; `long_groups` of them have forty.  Every key is in a random subset of the runs
+    with random seqnos, so groups interleave runs and versions."""
+    heads = sorted(set(bytes(rs.randint(0, 256, size=14).astype(np.uint8)) for _ in range(n_heads)))
+    spots = [14, 15, 16, 20, 23, 24, 31]  # byte that tells two tails of a group apart
+    runs: List[List[bytes]] = [[] for _ in range(n_runs)]
+    for h, head in enumerate(heads):
+        size = 40 if h < long_groups else int(rs.choice([1, 1, 1, 2, 3, 5, 8]))
+        tails = set()
+        while len(tails) < size:
+            t = bytearray(18)
+            for _ in range(int(rs.randint(1, 3))):
+                t[spots[int(rs.randint(len(spots)))] - 14] = int(rs.randint(0, 4))
+            tails.add(bytes(t))
+        for tail in tails:
+            for j in range(n_runs):
+                if rs.rand() < 0.5:
+                    typ = TOMBSTONE if rs.rand() < 0.2 else PUT
+                    runs[j].append(pack_entry(head + tail, int(rs.randint(0, 1 << 40)), typ, int(rs.randint(0, 1 << 62)),
+                                              j, bytes([j] * 7), h & 0x7FFFFFFF))
+    return [sorted(r, key=lambda raw: raw[:32]) for r in runs]

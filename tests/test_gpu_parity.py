@@ -134,6 +134,17 @@ def test_adversarial_keys_long_common_prefixes(g, oracle):
         _check_compact(g, oracle, runs, flags)
 
 
+@pytest.mark.parametrize("n_runs,n_heads,long_groups", [(5, 3000, 0), (16, 1500, 0), (4, 2500, 6)])
+def test_keys_that_tie_in_their_first_14_bytes(g, oracle, n_runs, n_heads, long_groups):
+    """Small groups of keys equal in the bytes the merge orders by and different after them; with
+    long_groups some groups are longer than the in-place repair handles."""
+    print("prefix-tie groups", n_runs, n_heads, long_groups, flush=True)
+    rs = np.random.RandomState(1000 + n_runs)
+    runs = [to_dev(brute.run_from_raw(r)) for r in brute.tie_group_runs(rs, n_runs, n_heads, long_groups)]
+    for flags in (0, 1):
+        _check_compact(g, oracle, runs, flags)
+
+
 def test_results_do_not_depend_on_repetition(g, cfg1):
     print("determinism", flush=True)
     first = compact_gpu(g, cfg1.runs, 1).clone()
