@@ -90,8 +90,9 @@ __device__ __forceinline__ uint64_t tree_mid(uint64_t lo, uint64_t hi) {
 // the fixed tree.  eq tells whether the record at the result lies inside
 // [lo, hi) and has exactly the key k.
 template <typename E>
-__device__ __forceinline__ uint64_t lower_bound_eq(const E* run, uint64_t lo, uint64_t hi, const Key& k, bool& eq) {
-    eq = false;  // always describes the record at the current hi
+__device__ __forceinline__ uint64_t lower_bound_eq(const E* run, uint64_t lo, uint64_t hi, const Key& k, bool& eq,
+                                                   const bool fresh = true) {
+    if (fresh) eq = false;  // always describes the record at the current hi
     while (lo < hi) {
         const uint64_t mid = tree_mid(lo, hi);
         const int c = entry_key_cmp(run + mid, *reinterpret_cast<const uint4*>(run + mid), k);
@@ -99,6 +100,32 @@ __device__ __forceinline__ uint64_t lower_bound_eq(const E* run, uint64_t lo, ui
         else hi = mid, eq = c == 0;
     }
     return lo;
+}
+
+// The same result by four-way steps at the quartiles of the range (three records read together per
+// step): half the dependent round trips for half as many reads again.  For arrays that stay in cache,
+// where the round trips are what costs.
+template <typename E>
+__device__ __forceinline__ uint64_t lower_bound_eq4(const E* run, uint64_t lo, uint64_t hi, const Key& k, bool& eq) {
+    eq = false;  // always describes the record at the current hi
+    while (hi - lo >= 3) {
+        const uint64_t w = hi - lo;
+        const uint64_t m1 = lo + (w >> 2), m2 = lo + (w >> 1), m3 = lo + ((3 * w) >> 2);  // lo <= m1 < m2 < m3 < hi
+        const uint4 a1 = *reinterpret_cast<const uint4*>(run + m1);
+        const uint4 a2 = *reinterpret_cast<const uint4*>(run + m2);
+        const uint4 a3 = *reinterpret_cast<const uint4*>(run + m3);
+        const int c1 = entry_key_cmp(run + m1, a1, k), c2 = entry_key_cmp(run + m2, a2, k), c3 = entry_key_cmp(run + m3, a3, k);
+        if (c3 < 0) {
+            lo = m3 + 1;
+        } else if (c2 < 0) {
+            lo = m2 + 1, hi = m3, eq = c3 == 0;
+        } else if (c1 < 0) {
+            lo = m1 + 1, hi = m2, eq = c2 == 0;
+        } else {
+            hi = m1, eq = c1 == 0;
+        }
+    }
+    return lower_bound_eq(run, lo, hi, k, eq, false);  // at most two records left; eq carries over
 }
 
 // Sum / max over the 64 lanes of a wave; every lane must call.

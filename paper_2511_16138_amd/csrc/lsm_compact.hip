@@ -130,7 +130,7 @@ __device__ __forceinline__ void select_update(uint64_t& lo, uint64_t& hi, uint64
     }
 }
 
-template <typename E>
+template <bool kCached, typename E>
 __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint64_t hi, const uint64_t r, const bool own,
                                                  const int member, const int group, const int group_base) {
     uint64_t best = lo;
@@ -141,7 +141,10 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
         const bool active = (widest >> 6) > (uint64_t)kTailKeys;
         if (__ballot(active) == 0) break;
         const int src = (int)(widest & 63);
-        uint64_t mid = width ? tree_mid(lo, hi) : lo;
+        // bisection steps take the roundest position of the middle quarter when the records are in HBM
+        // (a position other searches read too), the plain middle when they are cached
+        uint64_t mid = lo + (width >> 1);
+        if (!kCached && width) mid = tree_mid(lo + ((3 * width) >> 3), lo + ((5 * width) >> 3) + 1);
         if (iter % 3 != 2) {
             // interpolation steps: the candidates are the merged ranks [sum lo, sum hi); aim the pivot at
             // the same fraction of the widest range as a target rank is of that interval.  The target
@@ -164,7 +167,7 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
                 if (mid >= hi) mid = hi - 1;
                 // the roundest position within 1/16 of the range around the aim: likely read before, or again later
                 const uint64_t slack = width >> 4;
-                mid = tree_mid(mid - lo > slack ? mid - slack : lo, hi - mid > slack + 1 ? mid + slack + 1 : hi);
+                if (!kCached) mid = tree_mid(mid - lo > slack ? mid - slack : lo, hi - mid > slack + 1 ? mid + slack + 1 : hi);
             }
         }
         Key pivot = {{0, 0, 0, 0}};
@@ -172,7 +175,7 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
         for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], group_base + src, kWave);
         uint64_t lb = lo;
         bool eq = false;
-        if (own && active) lb = lower_bound_eq(run, lo, hi, pivot, eq);
+        if (own && active) lb = kCached ? lower_bound_eq4(run, lo, hi, pivot, eq) : lower_bound_eq(run, lo, hi, pivot, eq);
         select_update(lo, hi, best, lb, eq, mid, member == src, active, own, r, group);
     }
     // phase 2: the same steps on the at most kTailKeys keys per range that are left, held in registers
@@ -238,7 +241,7 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
         if (hi > rt.n[g.member]) hi = rt.n[g.member];  // only inputs that break the precondition
         if (lo > hi) lo = hi;
     }
-    const uint64_t best = select_split(run, lo, hi, r, own, g.member, group, g.group_base);
+    const uint64_t best = select_split<false>(run, lo, hi, r, own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
@@ -278,7 +281,7 @@ __global__ void __launch_bounds__(256) sample_coarse_kernel(Workspace ws, uint32
     const uint64_t c = g.slot + 1;
     const bool own = c <= n_coarse && g.member < (int)k;
     const SampleKey* run = own ? ws.st.ptr[g.member] : nullptr;
-    const uint64_t best = select_split(run, 0, own ? ws.st.m[g.member] : 0, sample_target(c * kCoarseStride, 0, k), own,
+    const uint64_t best = select_split<true>(run, 0, own ? ws.st.m[g.member] : 0, sample_target(c * kCoarseStride, 0, k), own,
                                        g.member, group, g.group_base);
     if (own) ws.ycoarse[c * k + g.member] = best;
 }
@@ -299,7 +302,7 @@ __global__ void __launch_bounds__(256) sample_fine_kernel(Workspace ws, uint32_t
         if (hi > ws.st.m[g.member]) hi = ws.st.m[g.member];  // only inputs that break the precondition
         if (lo > hi) lo = hi;
     }
-    const uint64_t best = select_split(run, lo, hi, sample_target(b, side, k), own, g.member, group, g.group_base);
+    const uint64_t best = select_split<true>(run, lo, hi, sample_target(b, side, k), own, g.member, group, g.group_base);
     if (own) ws.ywin[g.slot * k + g.member] = best;
 }
 
@@ -323,7 +326,7 @@ __global__ void __launch_bounds__(256) bracket_partition_kernel(RunTable rt, Wor
     const uint64_t y_total = group_sum_u64(own ? yhi : 0, group);
     if (own && y_total < (r + kSampleStride - 1) / kSampleStride + rt.k) hi = rt.n[g.member];
     if (lo > hi) lo = hi;  // only inputs that break the precondition
-    const uint64_t best = select_split(run, lo, hi, r, own, g.member, group, g.group_base);
+    const uint64_t best = select_split<false>(run, lo, hi, r, own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
@@ -452,7 +455,8 @@ __device__ __forceinline__ bool tail_less(const uint4 a0, const uint4 a1, const 
     return __builtin_bswap64(((uint64_t)a1.w << 32) | a1.z) < __builtin_bswap64(((uint64_t)b1.w << 32) | b1.z);
 }
 
-__global__ void __launch_bounds__(kMergeThreads) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
+// two workgroups per compute unit = four waves per SIMD: at most 128 vector registers
+__global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
                                                                lsm_entry_t* out, uint64_t* n_out) {
     __shared__ MergeShared s;
     const int tid = threadIdx.x;
