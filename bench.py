@@ -23,6 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
+# HBM bytes of one merge_kernel launch on the full configuration, from the FETCH_SIZE and WRITE_SIZE counters of
+# rocprofv3 scaled by a streaming kernel of known size (profiles/compaction_cfg3_tiered16_hbm_traffic.md)
+MERGE_KERNEL_TRAFFIC_BYTES = 4.343e9 + 2.934e9
 
 
 def cpu_baseline(sample_runs):
@@ -227,8 +230,24 @@ def main() -> int:
         "ms": {"partition_kernels": ms_partition, "merge_kernel": ms_merge, "compact_total": ms_compact,
                "fence_build": ms_fence, "probe_batch": ms_probe, "generate_inputs_s": gen_s},
         "roofline": {"bound": "hbm", "kernel": "merge_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None, "algorithmic_bytes": algo_bytes},
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MERGE_KERNEL_TRAFFIC_BYTES if args.scale == 1 else None,
+                     "algorithmic_bytes": algo_bytes},
     }
+    # second denominator: a plain device-to-device copy that moves the same number of bytes (half read, half written)
+    half = algo_bytes // 2 // 8
+    src = torch.empty(half, dtype=torch.int64, device=dev).random_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * half * 8 / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
+    result["copy_ceiling_gbps"] = copy_gbps
+    result["compact_frac_of_copy_ceiling"] = result["compact_hbm_gbps"] / copy_gbps
+    del src, dst
     cpu_sample = None if args.no_cpu_baseline else [r[: max(1, (1 << 21) // args.scale)].cpu() for r in runs]
     del runs, out, fences, q, hits, w
     torch.cuda.empty_cache()
