@@ -137,3 +137,22 @@ def tie_group_runs(rs: np.random.RandomState, n_runs: int, n_heads: int, long_gr
                     runs[j].append(pack_entry(head + tail, int(rs.randint(0, 1 << 40)), typ, int(rs.randint(0, 1 << 62)),
                                               j, bytes([j] * 7), h & 0x7FFFFFFF))
     return [sorted(r, key=lambda raw: raw[:32]) for r in runs]
+
+
+def close_first_words_runs(rs: np.random.RandomState, n_runs: int, per_run: int, separate: bool) -> List[List[bytes]]:
+    """Keys whose first 8 bytes take three values: two that differ only in their last bit and one far away, so
+    that any fixed-width scaling of the first word maps the close pair to one value.  With `separate` the two
+    close values never occur in the same run (run j holds only one of them), otherwise every run mixes them."""
+    a = bytes([0x10] + [0] * 7)
+    b = bytes([0x10] + [0] * 6 + [1])
+    far = bytes([0xF0] + [0] * 7)
+    runs = []
+    for j in range(n_runs):
+        firsts = [a if j % 2 == 0 else b, far] if separate else [a, b, far]
+        keys = set()
+        while len(keys) < per_run:
+            keys.add(firsts[int(rs.randint(len(firsts)))] + bytes(rs.randint(0, 256, size=3).astype(np.uint8)) + bytes(21))
+        run = [pack_entry(key, int(rs.randint(0, 1 << 40)), TOMBSTONE if rs.rand() < 0.2 else PUT, int(rs.randint(0, 1 << 62)), j,
+                          bytes([j] * 7), j) for key in sorted(keys)]
+        runs.append(run)
+    return runs

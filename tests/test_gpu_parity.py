@@ -145,6 +145,18 @@ def test_keys_that_tie_in_their_first_14_bytes(g, oracle, n_runs, n_heads, long_
         _check_compact(g, oracle, runs, flags)
 
 
+@pytest.mark.parametrize("separate", [False, True])
+def test_first_key_words_that_differ_in_one_bit(g, oracle, separate):
+    """Two first key words that differ in their last bit next to one far away (any scaled or
+    shortened form of the first word confuses the close pair), mixed inside every run or
+    kept in separate runs; the rest of the key is random."""
+    print("close first words, separate =", separate, flush=True)
+    rs = np.random.RandomState(31 + separate)
+    runs = [to_dev(brute.run_from_raw(r)) for r in brute.close_first_words_runs(rs, 6, 1500, separate)]
+    for flags in (0, 1):
+        _check_compact(g, oracle, runs, flags)
+
+
 def test_results_do_not_depend_on_repetition(g, cfg1):
     print("determinism", flush=True)
     first = compact_gpu(g, cfg1.runs, 1).clone()
