@@ -1,7 +1,7 @@
 // lsm_compact: single-pass k-way merge of sorted runs (paper section 2.2, compaction).
 //
 // Three kernels on one stream:
-//   init_kernel       clears the per-call scratch (ticket, tile status words) and writes the
+//   init_kernel       clears the per-call scratch (tile status words) and writes the
 //                     first and last partition rows.
 //   partition_kernel  one group of lanes per interior tile boundary: multi-sequence selection
 //                     over the k runs.  For target rank r it finds the key x with the largest
@@ -40,7 +40,7 @@ constexpr int kStShift = 62;
 constexpr uint64_t kStValueMask = (1ull << kStShift) - 1;
 
 struct Header {  // first 256 bytes of the workspace
-    uint32_t ticket;
+    uint32_t unused;
     uint32_t validate_status;
     uint64_t reserved[31];
 };
@@ -71,7 +71,6 @@ __global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_
     uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     if (i == 0) {
-        ws.hdr->ticket = 0;
         ws.hdr->validate_status = 0;
         if (n_tiles == 0) *n_out = 0;
     }
@@ -396,9 +395,9 @@ __device__ __forceinline__ uint32_t piece_of(const uint32_t* seg, uint32_t k, ui
 }
 
 // Publish this tile's survivor count and return the number of survivors in all earlier tiles
-// (decoupled look-back).  Called by wave 0 only, all 64 lanes.  Tiles take their numbers from
-// an atomic ticket, so every earlier tile has already started and will publish; the wait is
-// bounded anyway, and a tile that gives up publishes kStFailed, which propagates forward.
+// (decoupled look-back).  Called by wave 0 only, all 64 lanes.  Earlier tiles are earlier
+// workgroups, which have started (or finished) by the time this one runs, and will publish; the
+// wait is bounded anyway, and a tile that gives up publishes kStFailed, which propagates forward.
 __device__ uint64_t lookback(uint64_t* status, uint64_t tile, uint64_t count, bool self_failed, bool* failed) {
     const int lane = threadIdx.x & (kWave - 1);
     *failed = self_failed;
@@ -465,26 +464,20 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     const uint32_t k = rt.k;
     const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
-    // ---- tile number (ticket order = output order) and its k pieces, all by wave 0.  Tickets are
-    //      almost always handed out in workgroup order, so the split rows of tile blockIdx.x are
-    //      requested together with the ticket and only re-read if the ticket says otherwise.
+    // ---- the tile's k pieces, by wave 0.  Tile number = workgroup number: the look-back below waits only for
+    //      tiles with smaller numbers, and workgroups are handed to the compute units in ascending order, so the
+    //      tiles waited for are resident or done.  (A ticket taken with an atomic would make that independent
+    //      of the dispatch order, but it costs a second dependent memory round trip before the first load: the
+    //      tickets come back in a different order than the workgroup numbers for 99 % of the tiles.)  The waits
+    //      are bounded in any case.
     if (wave == 0) {
-        uint32_t ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&ws.hdr->ticket, 1u);
-        uint64_t t = blockIdx.x, a = 0, b = 0;
+        const uint64_t t = blockIdx.x;
+        uint64_t a = 0, b = 0;
         const bool mine = lane < (int)k;
         if (mine) {
             a = ws.splits[t * k + lane];
             b = ws.splits[(t + 1) * k + lane];
             s.run[lane] = rt.ptr[lane];
-        }
-        ticket = __shfl(ticket, 0, kWave);
-        if (ticket != t && ticket < n_tiles) {
-            t = ticket;
-            if (mine) {
-                a = ws.splits[t * k + lane];
-                b = ws.splits[(t + 1) * k + lane];
-            }
         }
         // piece lengths -> offsets (inclusive scan over the lanes); split rows never exceed the run
         // lengths, and only inputs that break the precondition can make a row pair inconsistent
@@ -502,7 +495,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         }
         if (lane == 0) {
             s.seg[0] = 0;
-            s.tile = ticket;
+            s.tile = (uint32_t)t;
             s.n = ok ? total : 0;
             s.failed = ok ? 0 : 1;
             s.inexact = 0;
