@@ -779,7 +779,9 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         }
     }
 
-    // ---- output offset of this tile
+    __syncthreads();  // prefix[] complete, last reads of info[] done: the staging area is free
+
+    // ---- output offset of this tile: wave 0 looks back while the other waves already stage their survivors
     if (wave == 0) {
         bool failed;
         uint64_t base = lookback(ws.status, tile, total, s.failed != 0, &failed);
@@ -788,16 +790,13 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             if (failed) s.failed = 1;
         }
     }
-    __syncthreads();  // also orders prefix[] and the last reads of info[] before the staging writes below
-    const bool failed = s.failed != 0;
-    const uint64_t base = s.base;
-    if (tile == n_tiles - 1 && tid == 0) *n_out = failed ? ~0ull : base + total;
-    if (failed) return;
 
     // ---- survivors leave through an LDS stage so that the global stores are contiguous; the four
     //      16-byte parts of a slot are rotated by the slot number to spread them over the banks
     uint4* stage = &s.buf[0][0];
-    for (uint32_t first = 0; first < total; first += kStageEntries) {
+    uint64_t base = 0;
+    uint32_t first = 0;
+    do {
 #pragma unroll
         for (int i = 0; i < kMergeItems; i++) {
             const uint32_t e = tid + i * kMergeThreads;
@@ -810,11 +809,18 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             }
         }
         __syncthreads();
+        if (first == 0) {
+            const bool failed = s.failed != 0;
+            base = s.base;
+            if (tile == n_tiles - 1 && tid == 0) *n_out = failed ? ~0ull : base + total;
+            if (failed) return;
+        }
         const uint32_t count = min(total - first, (uint32_t)kStageEntries);
         uint4* dst = reinterpret_cast<uint4*>(out + base + first);
         for (uint32_t c = tid; c < count * 4; c += kMergeThreads) dst[(c & ~3u) | ((c ^ (c >> 2)) & 3)] = stage[c];
-        __syncthreads();
-    }
+        first += kStageEntries;
+        if (first < total) __syncthreads();  // the stage is reused
+    } while (first < total);
 }
 
 // ---------------------------------------------------------------------------------------
