@@ -44,6 +44,7 @@ struct Header {  // first 256 bytes of the workspace
     uint32_t validate_status;
     uint64_t reserved[31];
 };
+static_assert(kRoundItems == 4, "the register merge network is written for four outputs");
 static_assert(sizeof(Header) == 256, "header is 256 bytes");
 
 // A bare 32-byte key: one sample of a run.
@@ -376,9 +377,16 @@ __device__ __forceinline__ Sur sur_load(const uint4* p) {
 __device__ __forceinline__ void sur_store(uint4* p, const Sur& v) {
     *p = make_uint4((uint32_t)v.hi, (uint32_t)(v.hi >> 32), (uint32_t)v.lo, (uint32_t)(v.lo >> 32));
 }
-// key part of a <= key part of b (the index bits never decide)
-__device__ __forceinline__ bool sur_le(const Sur& a, const Sur& b) {
-    return a.hi < b.hi || (a.hi == b.hi && (a.lo & ~0xFFFFull) <= (b.lo | 0xFFFFull));
+// a < b as 128-bit numbers (key bits, then index)
+__device__ __forceinline__ bool sur_less(const Sur& a, const Sur& b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
+// afterwards a < b
+__device__ __forceinline__ void sur_order(Sur& a, Sur& b) {
+    const bool swap = sur_less(b, a);
+    const Sur t = a;
+    a.hi = swap ? b.hi : a.hi;
+    a.lo = swap ? b.lo : a.lo;
+    b.hi = swap ? t.hi : b.hi;
+    b.lo = swap ? t.lo : b.lo;
 }
 __device__ __forceinline__ bool sur_same_key(const Sur& a, const Sur& b) { return a.hi == b.hi && ((a.lo ^ b.lo) >> 16) == 0; }
 
@@ -547,18 +555,21 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     if (tid == 0) s.flag[n] = 0;
     __syncthreads();
 
-    // ---- merge rounds: lists of `width` runs each are merged pairwise, stable (left list first)
+    // ---- merge rounds: lists of `width` runs each are merged pairwise.  Surrogates are compared as whole
+    //      128-bit numbers: the index in the low bits grows with the run number, so the order is the stable one
+    //      (equal keys: lower run first) and all values are distinct.  Thread t produces outputs
+    //      [4t, 4t + 4): a co-rank search finds where they start in the two lists, then the next four of each
+    //      list are read at once and merged in registers (half-cleaner + two exchange stages), so the only
+    //      dependent LDS reads of a round are those of the search.
+    const uint32_t j_first = piece_of(s.seg, k, top_step, min((uint32_t)(tid * kRoundItems), n ? n - 1 : 0));
     int cur = 0;
     for (uint32_t width = 1; width < k; width <<= 1) {
         const uint4* in = s.buf[cur];
         uint4* dst = s.buf[cur ^ 1];
-        // thread t produces outputs [t * kRoundItems, (t + 1) * kRoundItems): longer serial merges on
-        // fewer threads keep the co-rank searches (most of the LDS reads of a round) a smaller share
-        uint32_t o = tid * kRoundItems;
+        uint32_t o = tid * kRoundItems, j = j_first;
         const uint32_t o_end = min(o + (uint32_t)kRoundItems, n);
         while (o < o_end) {
-            // the pair of lists whose output range contains position o
-            const uint32_t j = piece_of(s.seg, k, top_step, o);
+            // the pair of lists whose output range contains position o (o lies in piece j)
             const uint32_t ra = (j / (2 * width)) * 2 * width, rb = min(ra + width, k), rc = min(ra + 2 * width, k);
             const uint32_t sa = s.seg[ra], sb = s.seg[rb], sc = s.seg[rc];
             const uint32_t len_a = sb - sa, len_b = sc - sb;
@@ -568,27 +579,31 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             uint32_t lo = d > len_b ? d - len_b : 0, hi = min(d, len_a);
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (sur_le(sur_load(&in[sa + mid]), sur_load(&in[sb + (d - 1 - mid)]))) lo = mid + 1;
+                if (sur_less(sur_load(&in[sa + mid]), sur_load(&in[sb + (d - 1 - mid)]))) lo = mid + 1;
                 else hi = mid;
             }
-            // serial merge, written without branches: one dependent LDS read per output
-            uint32_t a = lo, b = d - lo;
-            Sur va = sur_load(&in[a < len_a ? sa + a : sa]), vb = sur_load(&in[b < len_b ? sb + b : sa]);
-            for (; o < stop; o++) {
-                const bool take_a = (b >= len_b) | ((a < len_a) & sur_le(va, vb));
-                Sur w;
-                w.hi = take_a ? va.hi : vb.hi;
-                w.lo = take_a ? va.lo : vb.lo;
-                sur_store(&dst[o], w);
-                a += take_a ? 1 : 0;
-                b += take_a ? 0 : 1;
-                const uint32_t ia = a < len_a ? sa + a : sa, ib = b < len_b ? sb + b : sa;
-                const Sur nv = sur_load(&in[take_a ? ia : ib]);
-                va.hi = take_a ? nv.hi : va.hi;
-                va.lo = take_a ? nv.lo : va.lo;
-                vb.hi = take_a ? vb.hi : nv.hi;
-                vb.lo = take_a ? vb.lo : nv.lo;
+            const uint32_t a = lo, b = d - lo;
+            Sur x[kRoundItems], y[kRoundItems];
+#pragma unroll
+            for (int i = 0; i < kRoundItems; i++) {
+                x[i] = sur_load(&in[min(sa + a + i, (uint32_t)kTileCap - 1)]);
+                y[i] = sur_load(&in[min(sb + b + i, (uint32_t)kTileCap - 1)]);
+                if (a + i >= len_a) x[i].hi = x[i].lo = ~0ull;  // past the end of a list: larger than any surrogate
+                if (b + i >= len_b) y[i].hi = y[i].lo = ~0ull;
             }
+            // the four smallest of x[0..3], y[0..3] in order
+            Sur c[kRoundItems];
+#pragma unroll
+            for (int i = 0; i < kRoundItems; i++) c[i] = sur_less(x[i], y[kRoundItems - 1 - i]) ? x[i] : y[kRoundItems - 1 - i];
+            sur_order(c[0], c[2]);
+            sur_order(c[1], c[3]);
+            sur_order(c[0], c[1]);
+            sur_order(c[2], c[3]);
+#pragma unroll
+            for (int i = 0; i < kRoundItems; i++)
+                if (o + i < stop) sur_store(&dst[o + i], c[i]);
+            o = stop;
+            for (j = rc; j + 1 < k && s.seg[j + 1] <= o; j++) {}  // piece of the next position (skips empty pieces)
         }
         __syncthreads();
         cur ^= 1;
