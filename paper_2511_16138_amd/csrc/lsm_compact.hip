@@ -352,7 +352,7 @@ struct MergeShared {
     uint4 buf[2][kTileCap];          // surrogate ping-pong; then 2 x uint4 of key tail/seqno/type per position; then output staging
     uint16_t rank[kTileCap];         // tile-local entry index -> merged position
     uint16_t prefix[kTileCap];       // survivors before this merged position
-    uint8_t flag[kTileCap + 8];      // per merged position: kFlagEq | kFlagFullEq | kFlagSurvive
+    alignas(4) uint8_t flag[kTileCap + 8];  // per merged position: kFlagEq | kFlagFullEq | kFlagSurvive
     uint32_t seg[LSM_MAX_RUNS + 1];  // start of each run's piece in tile-local index space
     uint64_t lo[LSM_MAX_RUNS];       // first entry of each run's piece
     const lsm_entry_t* run[LSM_MAX_RUNS];  // copy of the run pointers (indexed per lane)
@@ -640,19 +640,43 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     }
     __syncthreads();
 
-    // ---- exact equality with the previous position; a differing tail under an equal prefix makes the tile inexact
+    // ---- exact equality with the previous position; a differing tail under an equal prefix makes the tile inexact.
+    //      A thread's four positions are neighbours, so the words of positions o0-1 .. o0+3 that some comparison
+    //      needs are all requested before the first compare.
     {
         const uint32_t o0 = tid * kMergeItems;
-        bool inexact = false;
-        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
-            if (s.flag[o] & kFlagEq) {
-                const uint4 a0 = info0[o], a1 = info1[o], b0 = info0[o - 1], b1 = info1[o - 1];
-                bool same = ((a0.z ^ b0.z) >> 8) == 0 && a1.x == b1.x && a1.y == b1.y && a1.z == b1.z && a1.w == b1.w;
-                if (same) s.flag[o] = kFlagEq | kFlagFullEq;
-                else inexact = true;
+        if (o0 < n) {
+            const uint32_t f = *reinterpret_cast<const uint32_t*>(&s.flag[o0]);
+            bool eq[kMergeItems + 1];
+#pragma unroll
+            for (int i = 0; i < kMergeItems; i++) eq[i] = o0 + i < n && ((f >> (8 * i)) & kFlagEq) != 0;
+            eq[kMergeItems] = false;
+            uint32_t z[kMergeItems + 1];
+            uint4 t[kMergeItems + 1];  // [i] = position o0 + i - 1
+#pragma unroll
+            for (int i = 0; i <= kMergeItems; i++) {
+                const bool need = (i > 0 && eq[i - 1]) || eq[i];  // compared as a position or as a predecessor
+                z[i] = 0;
+                t[i] = make_uint4(0, 0, 0, 0);
+                if (need) {
+                    z[i] = info0[o0 + i - 1].z;
+                    t[i] = info1[o0 + i - 1];
+                }
             }
+            uint32_t g = f;
+            bool inexact = false;
+#pragma unroll
+            for (int i = 0; i < kMergeItems; i++) {
+                if (eq[i]) {
+                    const bool same = ((z[i + 1] ^ z[i]) >> 8) == 0 && t[i + 1].x == t[i].x && t[i + 1].y == t[i].y &&
+                                      t[i + 1].z == t[i].z && t[i + 1].w == t[i].w;
+                    g |= same ? (uint32_t)kFlagFullEq << (8 * i) : 0;
+                    inexact = inexact || !same;
+                }
+            }
+            if (g != f) *reinterpret_cast<uint32_t*>(&s.flag[o0]) = g;
+            if (inexact) s.inexact = 1;
         }
-        if (inexact) s.inexact = 1;
     }
     __syncthreads();
 
@@ -701,22 +725,53 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
 
     if (s.inexact != 2) {
         // ---- survivors: newest version of each key (largest seqno, ties to the earlier = lower run),
-        //      minus winning tombstones when the output is the last level
+        //      minus winning tombstones when the output is the last level.  Groups of equal keys are short and
+        //      mostly lie inside a thread's four positions: those are settled from registers, and only a
+        //      group that crosses into a neighbour's share is followed through LDS.
         const uint32_t o0 = tid * kMergeItems;
-        for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
-            const uint4 me = info0[o];
-            const uint64_t seq = ((uint64_t)me.y << 32) | me.x;
-            bool win = true;
-            for (uint32_t p = o; s.flag[p] & kFlagFullEq; p--) {  // earlier members of the group (flag[0] has no Eq bit)
-                const uint4 v = info0[p - 1];
-                if ((((uint64_t)v.y << 32) | v.x) >= seq) win = false;
+        if (o0 < n) {
+            const uint32_t f = *reinterpret_cast<const uint32_t*>(&s.flag[o0]);
+            const bool more = o0 + kMergeItems < n && (s.flag[o0 + kMergeItems] & kFlagFullEq) != 0;  // the group goes on to the right
+            bool fe[kMergeItems];
+            uint64_t seq[kMergeItems];
+            uint32_t type[kMergeItems];
+#pragma unroll
+            for (int i = 0; i < kMergeItems; i++) {
+                const bool valid = o0 + i < n;
+                const uint4 me = info0[valid ? o0 + i : o0];
+                fe[i] = valid && ((f >> (8 * i)) & kFlagFullEq) != 0;
+                seq[i] = ((uint64_t)me.y << 32) | me.x;
+                type[i] = me.z & 0xFF;
             }
-            for (uint32_t p = o + 1; s.flag[p] & kFlagFullEq; p++) {  // later members (flag[n] is 0)
-                const uint4 v = info0[p];
-                if ((((uint64_t)v.y << 32) | v.x) > seq) win = false;
+            uint32_t g = f;
+#pragma unroll
+            for (int i = 0; i < kMergeItems; i++) {
+                bool win = true, chain = true;
+#pragma unroll
+                for (int q = i; q >= 1; q--) {  // earlier members of the group
+                    chain = chain && fe[q];
+                    if (chain && seq[q - 1] >= seq[i]) win = false;
+                }
+                if (chain && fe[0])
+                    for (uint32_t p = o0; s.flag[p] & kFlagFullEq; p--) {  // flag[0] never has the bit
+                        const uint4 v = info0[p - 1];
+                        if ((((uint64_t)v.y << 32) | v.x) >= seq[i]) win = false;
+                    }
+                chain = true;
+#pragma unroll
+                for (int q = i + 1; q < kMergeItems; q++) {  // later members
+                    chain = chain && fe[q];
+                    if (chain && seq[q] > seq[i]) win = false;
+                }
+                if (chain && more)
+                    for (uint32_t p = o0 + kMergeItems; s.flag[p] & kFlagFullEq; p++) {  // flag[n] is 0
+                        const uint4 v = info0[p];
+                        if ((((uint64_t)v.y << 32) | v.x) > seq[i]) win = false;
+                    }
+                if (win && (flags & LSM_BOTTOMMOST) && type[i] == LSM_TOMBSTONE) win = false;
+                if (win && o0 + i < n) g |= (uint32_t)kFlagSurvive << (8 * i);
             }
-            if (win && (flags & LSM_BOTTOMMOST) && (me.z & 0xFF) == LSM_TOMBSTONE) win = false;
-            if (win) s.flag[o] |= kFlagSurvive;
+            if (g != f) *reinterpret_cast<uint32_t*>(&s.flag[o0]) = g;
         }
     } else {
         // ---- exact path: merged position and winner of every entry by binary search over the
