@@ -377,6 +377,11 @@ __device__ __forceinline__ Sur sur_load(const uint4* p) {
 __device__ __forceinline__ void sur_store(uint4* p, const Sur& v) {
     *p = make_uint4((uint32_t)v.hi, (uint32_t)(v.hi >> 32), (uint32_t)v.lo, (uint32_t)(v.lo >> 32));
 }
+// Where the record of position p sits in the 16-byte-per-position LDS arrays.  Threads own four consecutive
+// positions, so lane t of a wave reads or writes position 4t + i: without this every second lane would
+// fall on the same banks (64-byte stride).  The swap inside each group of four spreads eight lanes over all banks.
+__device__ __forceinline__ uint32_t sw(uint32_t p) { return p ^ ((p >> 3) & 3); }
+
 // a < b as 128-bit numbers (key bits, then index)
 __device__ __forceinline__ bool sur_less(const Sur& a, const Sur& b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
 // afterwards a < b
@@ -549,7 +554,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             Sur v;
             v.hi = kk.w[0];
             v.lo = (kk.w[1] & ~0xFFFFull) | e;
-            sur_store(&s.buf[0][e], v);
+            sur_store(&s.buf[0][sw(e)], v);
         }
     }
     if (tid == 0) s.flag[n] = 0;
@@ -579,15 +584,15 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             uint32_t lo = d > len_b ? d - len_b : 0, hi = min(d, len_a);
             while (lo < hi) {
                 const uint32_t mid = (lo + hi) >> 1;
-                if (sur_less(sur_load(&in[sa + mid]), sur_load(&in[sb + (d - 1 - mid)]))) lo = mid + 1;
+                if (sur_less(sur_load(&in[sw(sa + mid)]), sur_load(&in[sw(sb + (d - 1 - mid))]))) lo = mid + 1;
                 else hi = mid;
             }
             const uint32_t a = lo, b = d - lo;
             Sur x[kRoundItems], y[kRoundItems];
 #pragma unroll
             for (int i = 0; i < kRoundItems; i++) {
-                x[i] = sur_load(&in[min(sa + a + i, (uint32_t)kTileCap - 1)]);
-                y[i] = sur_load(&in[min(sb + b + i, (uint32_t)kTileCap - 1)]);
+                x[i] = sur_load(&in[sw(min(sa + a + i, (uint32_t)kTileCap - 1))]);
+                y[i] = sur_load(&in[sw(min(sb + b + i, (uint32_t)kTileCap - 1))]);
                 if (a + i >= len_a) x[i].hi = x[i].lo = ~0ull;  // past the end of a list: larger than any surrogate
                 if (b + i >= len_b) y[i].hi = y[i].lo = ~0ull;
             }
@@ -601,7 +606,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             sur_order(c[2], c[3]);
 #pragma unroll
             for (int i = 0; i < kRoundItems; i++)
-                if (o + i < stop) sur_store(&dst[o + i], c[i]);
+                if (o + i < stop) sur_store(&dst[sw(o + i)], c[i]);
             o = stop;
             for (j = rc; j + 1 < k && s.seg[j + 1] <= o; j++) {}  // piece of the next position (skips empty pieces)
         }
@@ -614,9 +619,9 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         const uint4* fin = s.buf[cur];
         const uint32_t o0 = tid * kMergeItems;
         if (o0 < n) {
-            Sur prev = sur_load(&fin[o0 > 0 ? o0 - 1 : 0]);
+            Sur prev = sur_load(&fin[sw(o0 > 0 ? o0 - 1 : 0)]);
             for (uint32_t o = o0; o < min(o0 + (uint32_t)kMergeItems, n); o++) {
-                Sur v = sur_load(&fin[o]);
+                Sur v = sur_load(&fin[sw(o)]);
                 s.flag[o] = (o > 0 && sur_same_key(prev, v)) ? kFlagEq : 0;
                 s.rank[v.lo & 0xFFFF] = (uint16_t)o;
                 prev = v;
@@ -634,8 +639,8 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         if (e < n) {
             const uint32_t p = s.rank[e];
             pos[i] = p;
-            info0[p] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, e);
-            info1[p] = ent[i][1];
+            info0[sw(p)] = make_uint4(ent[i][2].x, ent[i][2].y, (ent[i][2].z & 0xFF) | (ent[i][0].w & 0xFFFF0000u) >> 8, e);
+            info1[sw(p)] = ent[i][1];
         }
     }
     __syncthreads();
@@ -659,8 +664,8 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 z[i] = 0;
                 t[i] = make_uint4(0, 0, 0, 0);
                 if (need) {
-                    z[i] = info0[o0 + i - 1].z;
-                    t[i] = info1[o0 + i - 1];
+                    z[i] = info0[sw(o0 + i - 1)].z;
+                    t[i] = info1[sw(o0 + i - 1)];
                 }
             }
             uint32_t g = f;
@@ -697,20 +702,20 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 continue;
             }
             for (uint32_t a = o + 1; a < end; a++) {
-                const uint4 x0 = info0[a], x1 = info1[a];
+                const uint4 x0 = info0[sw(a)], x1 = info1[sw(a)];
                 uint32_t b = a;
-                for (; b > o && tail_less(x0, x1, info0[b - 1], info1[b - 1]); b--) {
-                    info0[b] = info0[b - 1];
-                    info1[b] = info1[b - 1];
+                for (; b > o && tail_less(x0, x1, info0[sw(b - 1)], info1[sw(b - 1)]); b--) {
+                    info0[sw(b)] = info0[sw(b - 1)];
+                    info1[sw(b)] = info1[sw(b - 1)];
                 }
-                info0[b] = x0;
-                info1[b] = x1;
+                info0[sw(b)] = x0;
+                info1[sw(b)] = x1;
             }
-            s.rank[info0[o].w] = (uint16_t)o;
+            s.rank[info0[sw(o)].w] = (uint16_t)o;
             for (uint32_t a = o + 1; a < end; a++) {
-                const bool same = !tail_less(info0[a - 1], info1[a - 1], info0[a], info1[a]);  // sorted: not less = equal
+                const bool same = !tail_less(info0[sw(a - 1)], info1[sw(a - 1)], info0[sw(a)], info1[sw(a)]);  // sorted: not less = equal
                 s.flag[a] = same ? (kFlagEq | kFlagFullEq) : kFlagEq;
-                s.rank[info0[a].w] = (uint16_t)a;
+                s.rank[info0[sw(a)].w] = (uint16_t)a;
             }
         }
         __syncthreads();
@@ -738,7 +743,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
 #pragma unroll
             for (int i = 0; i < kMergeItems; i++) {
                 const bool valid = o0 + i < n;
-                const uint4 me = info0[valid ? o0 + i : o0];
+                const uint4 me = info0[sw(valid ? o0 + i : o0)];
                 fe[i] = valid && ((f >> (8 * i)) & kFlagFullEq) != 0;
                 seq[i] = ((uint64_t)me.y << 32) | me.x;
                 type[i] = me.z & 0xFF;
@@ -754,7 +759,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 }
                 if (chain && fe[0])
                     for (uint32_t p = o0; s.flag[p] & kFlagFullEq; p--) {  // flag[0] never has the bit
-                        const uint4 v = info0[p - 1];
+                        const uint4 v = info0[sw(p - 1)];
                         if ((((uint64_t)v.y << 32) | v.x) >= seq[i]) win = false;
                     }
                 chain = true;
@@ -765,7 +770,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 }
                 if (chain && more)
                     for (uint32_t p = o0 + kMergeItems; s.flag[p] & kFlagFullEq; p++) {  // flag[n] is 0
-                        const uint4 v = info0[p];
+                        const uint4 v = info0[sw(p)];
                         if ((((uint64_t)v.y << 32) | v.x) > seq[i]) win = false;
                     }
                 if (win && (flags & LSM_BOTTOMMOST) && type[i] == LSM_TOMBSTONE) win = false;
