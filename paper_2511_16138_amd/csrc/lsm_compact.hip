@@ -1,14 +1,17 @@
 // lsm_compact: single-pass k-way merge of sorted runs (paper section 2.2, compaction).
 //
-// Three kernels on one stream:
+// Kernels, on one stream:
 //   init_kernel       clears the per-call scratch (tile status words) and writes the
 //                     first and last partition rows.
-//   partition_kernel  one group of lanes per interior tile boundary: multi-sequence selection
+//   partition         one group of lanes per interior tile boundary: multi-sequence selection
 //                     over the k runs.  For target rank r it finds the key x with the largest
 //                     L(x) = sum_j |{e in run j : e.key < x}| that is still <= r, and stores
 //                     the k lower bounds.  Boundaries are therefore key-aligned (all versions
 //                     of a key fall into the same tile) and tile sizes are within k of the
-//                     nominal size.
+//                     nominal size.  Small inputs search the runs directly (partition_kernel);
+//                     large ones first bracket every boundary on a copy of every 32nd key
+//                     (sample_kernel, sample_coarse_kernel, sample_fine_kernel) and search the
+//                     runs only inside the brackets (bracket_partition_kernel).
 //   merge_kernel      one workgroup per tile: every thread loads its share of the tile's entries
 //                     into registers, 16-byte surrogates (14 key bytes + index) are merged in LDS
 //                     by ceil(log2 k) rounds of stable two-way merge-path merges, the newest
