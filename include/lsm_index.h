@@ -9,6 +9,7 @@
  *
  *   lsm_compact       merge sorted runs into one run (section 2.2, compaction)
  *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
+ *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes)
  *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
  *                     section 2.2, "Point Lookups")
  *   lsm_policy_*      the adaptive controller's cost model (section 2.2 costs, section 3.3)
@@ -94,10 +95,28 @@ typedef struct {
     uint32_t stride;
 } lsm_fence_t;
 
+/*
+ * Bloom filter of a run (section 2.2: lookups go through Bloom filters and fence pointers; the
+ * false-positive rate is the p of the lookup costs).  The paper does not fix a filter format; this one is a
+ * blocked filter with 128-bit blocks, so that a lookup reads one 16-byte word:
+ *   k_i   = key bytes 8i .. 8i+7 read as a big-endian 64-bit number, i = 0..3
+ *   mix(x): x ^= x >> 30; x *= 0xBF58476D1CE4E5B9; x ^= x >> 27; x *= 0x94D049BB133111EB; x ^= x >> 31
+ *           (64-bit arithmetic; the output function of the splitmix64 generator)
+ *   h = 0x5EED251116138; for i = 0..3: h = mix(h ^ k_i);   g = mix(h ^ 0x9E3779B97F4A7C15)
+ *   block = ((h >> 32) * n_blocks) >> 32;   bit_j = (g >> (7 j)) & 127 for j = 0..5
+ * A key is in the filter when the six bits are set in its block; bit b of a block is bit (b & 31) of the
+ * block's little-endian 32-bit word b >> 5.  No false negatives; about 1 % false positives at 16 bits per key.
+ */
+typedef struct {
+    const void* blocks; /* DEVICE, n_blocks x 16 bytes, 16-byte aligned; NULL = the run has no filter */
+    uint64_t n_blocks;  /* < 2^32 */
+} lsm_bloom_t;
+
 typedef struct {
     lsm_run_t run;
     lsm_fence_t fence;
-    uint32_t level; /* informational */
+    lsm_bloom_t bloom; /* optional: lsm_probe skips the run for keys the filter excludes */
+    uint32_t level;    /* informational */
 } lsm_tree_run_t;
 
 /* A tree = its runs ordered NEWEST -> OLDEST (shallow level first; within a level, the most
@@ -177,6 +196,16 @@ size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
  * fence_keys_out: DEVICE, ceil(n/stride) x 32 bytes.  Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (stride == 0).
  */
 int lsm_build_fences(const lsm_run_t* run, uint32_t stride, uint8_t* fence_keys_out, void* stream);
+
+/*
+ * lsm_build_bloom -- Bloom filter of a run in the format described at lsm_bloom_t.
+ * lsm_bloom_blocks(n, bits_per_key) = max(1, ceil(n * bits_per_key / 128)) blocks of 16 bytes (0 if that is
+ * 2^32 or more, or bits_per_key is 0).  filter_out: DEVICE, 16-byte aligned, n_blocks x 16 bytes, overwritten
+ * (cleared, then every key of the run inserted).  The result does not depend on the order of insertion.
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (n_blocks == 0 or >= 2^32, misaligned pointers), LSM_ERR_HIP.
+ */
+uint64_t lsm_bloom_blocks(uint64_t n, uint32_t bits_per_key);
+int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t n_blocks, void* stream);
 
 /*
  * lsm_probe -- batched longest-cached-prefix lookup (appendix B "Probe": find the longest

@@ -165,6 +165,64 @@ void oracle_build_fences(const entry_t* run, uint64_t n, uint32_t stride, uint8_
 }
 
 /* ------------------------------------------------------------------------------------
+ * Bloom filter of a run (section 2.2: lookups use Bloom filters and fence pointers).  The
+ * paper fixes no format; the one checked here is the library's documented one, written out
+ * bit by bit: blocks of 128 bits, six bits per key inside one block.
+ *   k_i = key bytes 8i..8i+7 as a big-endian number; mix = output function of splitmix64
+ *   h = 0x5EED251116138; h = mix(h ^ k_i) for i = 0..3; g = mix(h ^ 0x9E3779B97F4A7C15)
+ *   block = ((h >> 32) * n_blocks) >> 32; bits (g >> 7j) & 127, j = 0..5
+ * A filter is stored as bytes: bit b of a block lives in byte b / 8, bit b % 8 (that is the
+ * little-endian 32-bit-word layout of the library).
+ * ------------------------------------------------------------------------------------ */
+static uint64_t splitmix_out(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ULL;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBULL;
+    x ^= x >> 31;
+    return x;
+}
+
+static void bloom_place(const uint8_t* key, uint64_t n_blocks, uint64_t* block, unsigned bits[6]) {
+    uint64_t h = 0x5EED251116138ULL;
+    for (int i = 0; i < 4; i++) {
+        uint64_t k = 0;
+        for (int b = 0; b < 8; b++) k = (k << 8) | key[8 * i + b];
+        h = splitmix_out(h ^ k);
+    }
+    uint64_t g = splitmix_out(h ^ 0x9E3779B97F4A7C15ULL);
+    *block = ((h >> 32) * n_blocks) >> 32;
+    for (int j = 0; j < 6; j++) bits[j] = (unsigned)((g >> (7 * j)) & 127);
+}
+
+uint64_t oracle_bloom_blocks(uint64_t n, uint32_t bits_per_key) {
+    if (bits_per_key == 0) return 0;
+    unsigned __int128 bits = (unsigned __int128)n * bits_per_key;
+    unsigned __int128 blocks = bits == 0 ? 1 : (bits + 127) / 128;
+    return blocks >= ((unsigned __int128)1 << 32) ? 0 : (uint64_t)blocks;
+}
+
+void oracle_build_bloom(const entry_t* run, uint64_t n, uint8_t* filter, uint64_t n_blocks) {
+    memset(filter, 0, 16 * n_blocks);
+    for (uint64_t e = 0; e < n; e++) {
+        uint64_t block;
+        unsigned bits[6];
+        bloom_place(run[e].key, n_blocks, &block, bits);
+        for (int j = 0; j < 6; j++) filter[16 * block + bits[j] / 8] |= (uint8_t)(1u << (bits[j] % 8));
+    }
+}
+
+/* 1 if the filter may contain the key, 0 if it certainly does not */
+int oracle_bloom_may_contain(const uint8_t* filter, uint64_t n_blocks, const uint8_t* key) {
+    uint64_t block;
+    unsigned bits[6];
+    bloom_place(key, n_blocks, &block, bits);
+    for (int j = 0; j < 6; j++)
+        if (!(filter[16 * block + bits[j] / 8] & (1u << (bits[j] % 8)))) return 0;
+    return 1;
+}
+
+/* ------------------------------------------------------------------------------------
  * Cost model of the adaptive controller.
  *   levels   L = smallest integer >= 1 with M * T^L >= N   (L = log_T(N*e/M), in entries)
  *   update   W = T*L / (B*K)

@@ -48,6 +48,12 @@ def lib() -> C.CDLL:
                                    C.c_uint32, C.c_void_p, C.c_void_p]
         L.oracle_build_fences.restype = None
         L.oracle_build_fences.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]
+        L.oracle_bloom_blocks.restype = C.c_uint64
+        L.oracle_bloom_blocks.argtypes = [C.c_uint64, C.c_uint32]
+        L.oracle_build_bloom.restype = None
+        L.oracle_build_bloom.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
+        L.oracle_bloom_may_contain.restype = C.c_int
+        L.oracle_bloom_may_contain.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
         L.oracle_levels.restype = C.c_uint32
         L.oracle_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
         L.oracle_cost.restype = C.c_double
@@ -116,6 +122,24 @@ def build_fences(run, stride: int) -> np.ndarray:
     out = np.zeros(((n + stride - 1) // stride, 32), dtype=np.uint8)
     lib().oracle_build_fences(run.ctypes.data, n, stride, out.ctypes.data)
     return out
+
+
+def bloom_blocks(n: int, bits_per_key: int) -> int:
+    return int(lib().oracle_bloom_blocks(n, bits_per_key))
+
+
+def build_bloom(run, n_blocks: int) -> np.ndarray:
+    """Filter bytes [n_blocks, 16] (section 2.2, Bloom filters; format in the C source)."""
+    run = as_run(run)
+    out = np.zeros((n_blocks, 16), dtype=np.uint8)
+    lib().oracle_build_bloom(run.ctypes.data, run.shape[0], out.ctypes.data, n_blocks)
+    return out
+
+
+def bloom_may_contain(filt: np.ndarray, key: bytes) -> bool:
+    filt = np.ascontiguousarray(filt, dtype=np.uint8)
+    kb = (C.c_uint8 * 32).from_buffer_copy(key)
+    return bool(lib().oracle_bloom_may_contain(filt.ctypes.data, filt.shape[0], kb))
 
 
 def levels(n_entries: int, buffer_entries: int, T: int) -> int:

@@ -47,8 +47,12 @@ class _Fence(C.Structure):
     _fields_ = [("keys", C.c_void_p), ("n", C.c_uint64), ("stride", C.c_uint32)]
 
 
+class _Bloom(C.Structure):
+    _fields_ = [("blocks", C.c_void_p), ("n_blocks", C.c_uint64)]
+
+
 class _TreeRun(C.Structure):
-    _fields_ = [("run", _Run), ("fence", _Fence), ("level", C.c_uint32)]
+    _fields_ = [("run", _Run), ("fence", _Fence), ("bloom", _Bloom), ("level", C.c_uint32)]
 
 
 class _Tree(C.Structure):
@@ -91,6 +95,10 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_compact_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), C.c_uint32]
     L.lsm_build_fences.restype = C.c_int
     L.lsm_build_fences.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_void_p, C.c_void_p]
+    L.lsm_bloom_blocks.restype = C.c_uint64
+    L.lsm_bloom_blocks.argtypes = [C.c_uint64, C.c_uint32]
+    L.lsm_build_bloom.restype = C.c_int
+    L.lsm_build_bloom.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_uint64, C.c_void_p]
     L.lsm_probe.restype = C.c_int
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
     L.lsm_policy_levels.restype = C.c_uint32
@@ -172,12 +180,30 @@ def lsm_build_fences(run: torch.Tensor, stride: int = 64, out: Optional[torch.Te
     return out
 
 
+def lsm_bloom_blocks(n: int, bits_per_key: int = 16) -> int:
+    return int(_load().lsm_bloom_blocks(n, bits_per_key))
+
+
+def lsm_build_bloom(run: torch.Tensor, bits_per_key: int = 16, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Bloom filter of a run; returns int32 [n_blocks, 4] (one 16-byte block per row)."""
+    L = _load()
+    n = int(_dev(run, "run").shape[0])
+    if out is None:
+        out = torch.empty((lsm_bloom_blocks(n, bits_per_key), 4), dtype=torch.int32, device=run.device)
+    rd = _Run(run.data_ptr(), n)
+    rc = L.lsm_build_bloom(C.byref(rd), _dev(out, "bloom filter").data_ptr(), int(out.shape[0]), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_build_bloom")
+    return out
+
+
 @dataclass
 class TreeRun:
     run: torch.Tensor      # int64 [n, 8]
     fences: torch.Tensor   # int64 [ceil(n/stride), 4]
     stride: int = 64
     level: int = 0
+    bloom: Optional[torch.Tensor] = None  # int32 [n_blocks, 4] from lsm_build_bloom, or None
 
 
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],
@@ -195,6 +221,8 @@ def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRu
     for i, t in enumerate(tree):
         tr[i].run = _Run(_dev(t.run, "tree run").data_ptr(), int(t.run.shape[0]))
         tr[i].fence = _Fence(_dev(t.fences, "fences").data_ptr(), int(t.fences.shape[0]), t.stride)
+        if t.bloom is not None:
+            tr[i].bloom = _Bloom(_dev(t.bloom, "bloom filter").data_ptr(), int(t.bloom.shape[0]))
         tr[i].level = t.level
     td = _Tree(tr, len(tree))
     qd = _Queries(qkeys.data_ptr(), _dev(n_blocks, "n_blocks").data_ptr(), n_req, max_blocks)

@@ -1,0 +1,55 @@
+// lsm_build_bloom: blocked Bloom filter of a run (paper section 2.2 names Bloom filters as the structure that
+// lets a lookup skip a run; appendix B uses point lookups in "Probe").  One thread per entry: hash the key,
+// OR its six bits into the 16-byte block.  Bits only ever get set, so the result is the same for any order.
+#include <hip/hip_runtime.h>
+
+#include "lsm_common.h"
+
+namespace lsm {
+
+__global__ void bloom_clear_kernel(uint4* blocks, uint64_t n_blocks) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_blocks; i += stride) blocks[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void bloom_insert_kernel(const lsm_entry_t* entries, uint64_t n, uint32_t* words, uint32_t n_blocks) {
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint4 mask;
+        const uint32_t block = bloom_address(load_key(entries + i), n_blocks, mask);
+        uint32_t* w = words + (uint64_t)block * 4;
+        if (mask.x) atomicOr(w + 0, mask.x);
+        if (mask.y) atomicOr(w + 1, mask.y);
+        if (mask.z) atomicOr(w + 2, mask.z);
+        if (mask.w) atomicOr(w + 3, mask.w);
+    }
+}
+
+}  // namespace lsm
+
+extern "C" uint64_t lsm_bloom_blocks(uint64_t n, uint32_t bits_per_key) {
+    if (bits_per_key == 0) return 0;
+    const unsigned __int128 bits = (unsigned __int128)n * bits_per_key;
+    const unsigned __int128 blocks = bits == 0 ? 1 : (bits + 127) / 128;
+    return blocks >= ((unsigned __int128)1 << 32) ? 0 : (uint64_t)blocks;
+}
+
+extern "C" int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t n_blocks, void* stream_v) {
+    using namespace lsm;
+    if (run == nullptr || filter_out == nullptr) return LSM_ERR_NULL;
+    if (run->n > 0 && run->entries == nullptr) return LSM_ERR_NULL;
+    if (n_blocks == 0 || n_blocks >= (1ull << 32)) return LSM_ERR_BAD_ARG;
+    if ((reinterpret_cast<uintptr_t>(filter_out) & 15) != 0 || (reinterpret_cast<uintptr_t>(run->entries) & 63) != 0)
+        return LSM_ERR_BAD_ARG;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint64_t clear_blocks = (n_blocks + 255) / 256;
+    if (clear_blocks > 4096) clear_blocks = 4096;
+    hipLaunchKernelGGL(bloom_clear_kernel, dim3((uint32_t)clear_blocks), dim3(256), 0, stream, static_cast<uint4*>(filter_out), n_blocks);
+    if (run->n > 0) {
+        uint64_t blocks = (run->n + 255) / 256;
+        if (blocks > 16384) blocks = 16384;
+        hipLaunchKernelGGL(bloom_insert_kernel, dim3((uint32_t)blocks), dim3(256), 0, stream, run->entries, run->n,
+                           static_cast<uint32_t*>(filter_out), (uint32_t)n_blocks);
+    }
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+}

@@ -145,6 +145,30 @@ __device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
 // table, so the compiler cannot tell): a global instead of a flat load.
 __device__ __forceinline__ uint4 load_global_u4(const uint4* p) { typedef uint32_t v4 __attribute__((ext_vector_type(4))); const v4 v = *(const __attribute__((address_space(1))) v4*)p; return make_uint4(v.x, v.y, v.z, v.w); }
 
+// Bloom filter addressing: the block of a key and the six bits it sets or tests there, as four 32-bit masks.
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 30;
+    x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27;
+    x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+__device__ __forceinline__ uint32_t bloom_address(const Key& k, uint32_t n_blocks, uint4& mask) {
+    uint64_t h = 0x5EED251116138ull;
+    for (int i = 0; i < 4; i++) h = mix64(h ^ k.w[i]);
+    const uint64_t g = mix64(h ^ 0x9E3779B97F4A7C15ull);
+    uint32_t m[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int j = 0; j < 6; j++) {
+        const uint32_t b = (uint32_t)(g >> (7 * j)) & 127;
+#pragma unroll
+        for (int w = 0; w < 4; w++) m[w] |= (b >> 5) == (uint32_t)w ? 1u << (b & 31) : 0u;
+    }
+    mask = make_uint4(m[0], m[1], m[2], m[3]);
+    return (uint32_t)(((h >> 32) * (uint64_t)n_blocks) >> 32);
+}
+
 // Run descriptors passed to kernels by value.
 struct RunTable {
     const lsm_entry_t* ptr[LSM_MAX_RUNS];

@@ -21,7 +21,8 @@ struct TreeRun {
     uint64_t n;
     uint64_t n_fences;
     uint32_t stride;
-    uint32_t pad;
+    uint32_t bloom_blocks;  // 0 = no filter
+    const uint4* bloom;
 };
 
 struct TreeTable {
@@ -110,6 +111,12 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
                         const uint32_t r = r0 + g;
                         lo[g] = 0;
                         hi[g] = (!found && r < n_runs) ? s.n_top[r] : 0;
+                        // (0) the run's Bloom filter, if it has one: one 16-byte read decides whether the run is searched
+                        if (hi[g] != 0 && tree.run[r].bloom_blocks != 0) {
+                            uint4 mask;
+                            const uint4 w = tree.run[r].bloom[bloom_address(q, tree.run[r].bloom_blocks, mask)];
+                            if (((w.x & mask.x) ^ mask.x) | ((w.y & mask.y) ^ mask.y) | ((w.z & mask.z) ^ mask.z) | ((w.w & mask.w) ^ mask.w)) hi[g] = 0;
+                        }
                     }
                     for (;;) {
                         bool any = false;
@@ -256,7 +263,11 @@ extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, c
         d.fences = tr.fence.keys;
         d.n_fences = tr.fence.n;
         d.stride = tr.fence.stride;
-        d.pad = 0;
+        d.bloom = static_cast<const uint4*>(tr.bloom.blocks);
+        d.bloom_blocks = tr.bloom.blocks ? (uint32_t)tr.bloom.n_blocks : 0;
+        if (tr.bloom.blocks != nullptr &&
+            (tr.bloom.n_blocks == 0 || tr.bloom.n_blocks >= (1ull << 32) || (reinterpret_cast<uintptr_t>(tr.bloom.blocks) & 15) != 0))
+            return LSM_ERR_BAD_ARG;
         if (tr.run.n > 0) {
             if (tr.run.entries == nullptr || tr.fence.keys == nullptr) return LSM_ERR_NULL;
             if (tr.fence.stride == 0 || tr.fence.n != (tr.run.n + tr.fence.stride - 1) / tr.fence.stride) return LSM_ERR_BAD_ARG;
@@ -269,7 +280,7 @@ extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, c
         }
     }
     tt.n_runs = tree->n_runs;
-    for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, 0, 1, 0};
+    for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, 0, 1, 0, nullptr};
     int device = 0, cus = 0;
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)

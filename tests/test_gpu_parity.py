@@ -281,3 +281,39 @@ def test_probe_empty_tree_and_empty_runs(g, oracle, cfg1):
     tree = build_tree(g, [empty, cfg1.runs[3], empty])
     want = oracle.probe(q, nb, [empty.cpu(), cfg1.runs[3].cpu(), empty.cpu()])
     assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)
+
+
+# ------------------------------------------------------------------ Bloom filters
+@pytest.mark.parametrize("bits_per_key", [8, 16])
+def test_bloom_filter_bytes_equal_the_checker(g, oracle, cfg1, bits_per_key):
+    print("bloom filter", bits_per_key, flush=True)
+    for run in list(cfg1.runs) + [cfg1.runs[0][:0], cfg1.runs[1][:1], cfg1.runs[2][:1000]]:
+        n_blocks = g.lsm_bloom_blocks(int(run.shape[0]), bits_per_key)
+        assert n_blocks == oracle.bloom_blocks(int(run.shape[0]), bits_per_key)
+        got = g.lsm_build_bloom(run.contiguous(), bits_per_key)
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(got).reshape(-1, 16), oracle.build_bloom(run.cpu(), n_blocks))
+        # building again into the same buffer clears it first
+        again = g.lsm_build_bloom(run.contiguous(), bits_per_key, out=got.fill_(-1))
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(again).reshape(-1, 16), oracle.build_bloom(run.cpu(), n_blocks))
+
+
+def test_probe_with_bloom_filters_gives_the_same_answers(g, oracle, cfg1):
+    """Filters only let the probe skip runs that cannot hold a key: results equal the checker's (which
+    has no filters) with filters on every run, on some runs, and with a deliberately tiny filter."""
+    from workloads import lsm
+    print("probe with bloom filters", flush=True)
+    q, nb = lsm.queries_config1(cfg1, 2048)
+    want = oracle.probe(q, nb, [r.cpu() for r in cfg1.runs])
+    plain = build_tree(g, cfg1.runs)
+    for choice in ("all", "some", "tiny"):
+        tree = []
+        for i, t in enumerate(plain):
+            bloom = None
+            if choice == "all" or (choice == "some" and i % 2 == 0):
+                bloom = g.lsm_build_bloom(t.run, 16)
+            elif choice == "tiny":
+                bloom = g.lsm_build_bloom(t.run, 16, out=torch.empty((3, 4), dtype=torch.int32, device=dev()))  # nearly all ones
+            tree.append(g.TreeRun(t.run, t.fences, t.stride, t.level, bloom))
+        assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)

@@ -37,7 +37,7 @@ def test_every_declared_entry_point_is_exported(lib):
 def test_struct_sizes_match_the_header():
     import paper_2511_16138_amd.binding as B
     assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 24 and C.sizeof(B._Fence) == 24
-    assert C.sizeof(B._TreeRun) == 48 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
+    assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 64 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
     assert C.sizeof(B._PolicyInput) == 72
 
 
