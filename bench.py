@@ -48,25 +48,39 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     """Lookup-heavy configuration: batches of 4,096 longest-prefix requests (Zipf(0.99) prefixes, 30 % misses,
     up to 256 block keys each) against the 5-level, 100M-entry tree.  Returns probes/s and key lookups/s."""
     w = lsm.config4(device=dev, scale=scale)
-    tree = [g.TreeRun(r, g.lsm_build_fences(r, 64), 64, i + 1) for i, r in enumerate(w.runs)]
+    plain = [g.TreeRun(r, g.lsm_build_fences(r, 64), 64, i + 1) for i, r in enumerate(w.runs)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    filtered = [g.TreeRun(t.run, t.fences, 64, t.level, g.lsm_build_bloom(t.run, 16)) for t in plain]
+    torch.cuda.synchronize()
+    bloom_build_ms = (time.perf_counter() - t0) * 1e3
     batches = [lsm.queries_config4(w, 4096, stream=b) for b in range(n_batches)]
     hit_len = torch.empty(4096, dtype=torch.int32, device=dev)
     hits = torch.empty((4096, 256, 2), dtype=torch.int64, device=dev)
-    for q, nb in batches[:2]:
-        g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    live = 0
-    for q, nb in batches:
-        g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / n_batches
+
+    def timed(tree):
+        for q, nb in batches[:2]:
+            g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for q, nb in batches:
+            g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_batches
+
+    ms_plain = timed(plain)
+    plain_len = hit_len.clone()
+    ms = timed(filtered)
+    assert bool((plain_len == hit_len).all()), "filters changed a probe result"
     keys = sum(int(nb.sum().item()) for _, nb in batches) / n_batches
-    return {"workload": "configs[3]: 5-level tree of %d entries, batches of 4096 requests" % sum(int(r.shape[0]) for r in w.runs),
+    return {"workload": "configs[3]: 5-level tree of %d entries, batches of 4096 requests, Bloom filters of 16 bits per key on every run"
+                        % sum(int(r.shape[0]) for r in w.runs),
             "batches_timed": n_batches, "ms_per_batch": ms, "probes_per_s": 4096 / (ms * 1e-3),
-            "requested_keys_per_s": keys / (ms * 1e-3), "mean_hit_len_last_batch": float(hit_len.float().mean().item())}
+            "requested_keys_per_s": keys / (ms * 1e-3), "mean_hit_len_last_batch": float(hit_len.float().mean().item()),
+            "without_filters": {"ms_per_batch": ms_plain, "probes_per_s": 4096 / (ms_plain * 1e-3)},
+            "bloom_build_ms_all_runs": bloom_build_ms}
 
 
 def mixed_config5(g, lsm, torch, dev, scale: int):
