@@ -16,7 +16,7 @@ __global__ void bloom_insert_kernel(const lsm_entry_t* entries, uint64_t n, uint
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         uint4 mask;
-        const uint32_t block = bloom_address(load_key(entries + i), n_blocks, mask);
+        const uint32_t block = bloom_block(bloom_hash(load_key(entries + i), mask), n_blocks);
         uint32_t* w = words + (uint64_t)block * 4;
         if (mask.x) atomicOr(w + 0, mask.x);
         if (mask.y) atomicOr(w + 1, mask.y);

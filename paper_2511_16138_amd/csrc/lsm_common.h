@@ -154,7 +154,8 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
     x ^= x >> 31;
     return x;
 }
-__device__ __forceinline__ uint32_t bloom_address(const Key& k, uint32_t n_blocks, uint4& mask) {
+// the hash h of a key (its top half picks the block) and the six bits as four 32-bit masks
+__device__ __forceinline__ uint64_t bloom_hash(const Key& k, uint4& mask) {
     uint64_t h = 0x5EED251116138ull;
     for (int i = 0; i < 4; i++) h = mix64(h ^ k.w[i]);
     const uint64_t g = mix64(h ^ 0x9E3779B97F4A7C15ull);
@@ -166,7 +167,11 @@ __device__ __forceinline__ uint32_t bloom_address(const Key& k, uint32_t n_block
         for (int w = 0; w < 4; w++) m[w] |= (b >> 5) == (uint32_t)w ? 1u << (b & 31) : 0u;
     }
     mask = make_uint4(m[0], m[1], m[2], m[3]);
-    return (uint32_t)(((h >> 32) * (uint64_t)n_blocks) >> 32);
+    return h;
+}
+__device__ __forceinline__ uint32_t bloom_block(uint64_t h, uint32_t n_blocks) { return (uint32_t)(((h >> 32) * (uint64_t)n_blocks) >> 32); }
+__device__ __forceinline__ bool bloom_excludes(const uint4 w, const uint4 mask) {
+    return (((w.x & mask.x) ^ mask.x) | ((w.y & mask.y) ^ mask.y) | ((w.z & mask.z) ^ mask.z) | ((w.w & mask.w) ^ mask.w)) != 0;
 }
 
 // Run descriptors passed to kernels by value.

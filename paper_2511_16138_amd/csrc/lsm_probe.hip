@@ -85,6 +85,8 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
     }
     __syncthreads();
 
+    bool any_bloom = false;
+    for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
     const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
     for (uint32_t req = blockIdx.x * (kProbeThreads / kWave) + tid / kWave; req < n_req; req += waves) {
         uint32_t nb = n_blocks[req];
@@ -102,6 +104,26 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
                 bool found = !mine;
                 Key q = {{0, 0, 0, 0}};
                 if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
+                // (0) Bloom filters of the runs that have one: one 16-byte read per run, all runs of a group of
+                //     eight requested together, decides which runs this key is searched in
+                uint64_t maybe = ~0ull;
+                if (mine && any_bloom) {
+                    uint4 mask;
+                    const uint64_t bh = bloom_hash(q, mask);
+                    for (uint32_t rb = 0; rb < n_runs; rb += 8) {
+                        uint4 w[8];
+#pragma unroll
+                        for (int g = 0; g < 8; g++) {
+                            const uint32_t r = rb + g;
+                            const uint32_t blocks = r < n_runs ? tree.run[r].bloom_blocks : 0;
+                            w[g] = make_uint4(~0u, ~0u, ~0u, ~0u);
+                            if (blocks) w[g] = tree.run[r].bloom[bloom_block(bh, blocks)];
+                        }
+#pragma unroll
+                        for (int g = 0; g < 8; g++)
+                            if (bloom_excludes(w[g], mask)) maybe &= ~(1ull << (rb + g));
+                    }
+                }
                 for (uint32_t r0 = 0; r0 < n_runs && __ballot(!found) != 0; r0 += kRunGroup) {
                     // searches in runs r0 .. r0 + kRunGroup - 1 proceed in lockstep; lo/hi are fence numbers, then entry offsets in the page
                     uint32_t lo[kRunGroup], hi[kRunGroup];
@@ -111,12 +133,13 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
                         const uint32_t r = r0 + g;
                         lo[g] = 0;
                         hi[g] = (!found && r < n_runs) ? s.n_top[r] : 0;
-                        // (0) the run's Bloom filter, if it has one: one 16-byte read decides whether the run is searched
-                        if (hi[g] != 0 && tree.run[r].bloom_blocks != 0) {
-                            uint4 mask;
-                            const uint4 w = tree.run[r].bloom[bloom_address(q, tree.run[r].bloom_blocks, mask)];
-                            if (((w.x & mask.x) ^ mask.x) | ((w.y & mask.y) ^ mask.y) | ((w.z & mask.z) ^ mask.z) | ((w.w & mask.w) ^ mask.w)) hi[g] = 0;
-                        }
+                        if (!((maybe >> r) & 1)) hi[g] = 0;  // excluded by the run's Bloom filter
+                    }
+                    {
+                        bool some = false;
+#pragma unroll
+                        for (int g = 0; g < kRunGroup; g++) some = some || hi[g] != 0;
+                        if (__ballot(some) == 0) continue;  // no key of the chunk needs these runs
                     }
                     for (;;) {
                         bool any = false;
