@@ -4,11 +4,12 @@
 // One wave per request, requests taken round-robin by the waves of a fixed-size grid.  Every
 // workgroup first copies a top-level fence table into LDS: for each run of the tree, an evenly
 // spaced subset of its fence keys (all of them for small runs).  A request's block keys are
-// handled 64 at a time, one key per lane.  A lane walks the runs newest -> oldest (kRunGroup at a
-// time) and stops at the first run that holds the key: top-level fences in LDS, then the
-// remaining fence range and the 64-entry page in global memory, reading the first 16 key bytes
-// and the second half only on a tie.  A ballot over the lanes gives the first block that is not live; later chunks of
-// the request are skipped and zero-filled.
+// handled 64 at a time, one key per lane.  A lane first reads the Bloom filters of the runs that have one
+// (all together), then walks the runs they admit, newest -> oldest, each lane its own list, and stops at
+// the first run that holds the key: top-level fences in LDS, then the remaining fence range and the
+// 64-entry page in global memory, reading the first 16 key bytes and the second half only on a tie.
+// A ballot over the lanes gives the first block that is not live; later chunks of the request are
+// skipped and zero-filled.
 #include <hip/hip_runtime.h>
 
 #include "lsm_common.h"
@@ -32,7 +33,6 @@ struct TreeTable {
 
 constexpr int kProbeThreads = 256;
 constexpr int kTopSlots = 1024;  // top-level fence keys held in LDS per workgroup (32 KB)
-constexpr int kRunGroup = 1;     // runs searched together by one lane (more only adds memory traffic: the search is bound by cold lines)
 
 struct ProbeShared {
     uint4 top_lo[kTopSlots];  // first 16 bytes of each top-level fence key
@@ -40,6 +40,12 @@ struct ProbeShared {
     uint32_t first_slot[LSM_MAX_RUNS];  // slots of run r: [first_slot[r], first_slot[r] + n_top[r])
     uint32_t n_top[LSM_MAX_RUNS];
     uint32_t top_stride[LSM_MAX_RUNS];  // top key i of run r = fence i * top_stride[r]
+    // the run descriptors, readable with a per-lane run number
+    const uint8_t* fences[LSM_MAX_RUNS];
+    const lsm_entry_t* entries[LSM_MAX_RUNS];
+    uint64_t n[LSM_MAX_RUNS];
+    uint64_t n_fences[LSM_MAX_RUNS];
+    uint32_t stride[LSM_MAX_RUNS];
 };
 
 // -1 / 0 / +1 for q < / == / > the 32-byte key whose halves are (lo, hi); hi is only fetched on a tie
@@ -73,6 +79,11 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
         s.first_slot[tid] = tid * share;
         s.top_stride[tid] = ts ? ts : 1;
         s.n_top[tid] = ts ? (uint32_t)((nf + ts - 1) / ts) : 0;
+        s.fences[tid] = tree.run[tid].fences;
+        s.entries[tid] = tree.run[tid].entries;
+        s.n[tid] = tree.run[tid].n;
+        s.n_fences[tid] = nf;
+        s.stride[tid] = tree.run[tid].stride;
     }
     __syncthreads();
     for (uint32_t slot = tid; slot < share * n_runs; slot += kProbeThreads) {
@@ -85,6 +96,7 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
     }
     __syncthreads();
 
+    const uint64_t run_mask = n_runs >= 64 ? ~0ull : (1ull << n_runs) - 1;
     bool any_bloom = false;
     for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
     const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
@@ -124,128 +136,72 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
                             if (bloom_excludes(w[g], mask)) maybe &= ~(1ull << (rb + g));
                     }
                 }
-                for (uint32_t r0 = 0; r0 < n_runs && __ballot(!found) != 0; r0 += kRunGroup) {
-                    // searches in runs r0 .. r0 + kRunGroup - 1 proceed in lockstep; lo/hi are fence numbers, then entry offsets in the page
-                    uint32_t lo[kRunGroup], hi[kRunGroup];
+                maybe &= run_mask;
+                // every lane walks its own list of admitted runs, newest first, so lanes that need different
+                // runs search them at the same time; the walk of a lane ends at the first run that holds its key
+                while (__ballot(!found && maybe != 0) != 0) {
+                    const bool act = !found && maybe != 0;
+                    const uint32_t r = act ? (uint32_t)__builtin_ctzll(maybe) : 0;
+                    maybe &= maybe - 1;  // 0 stays 0
                     // (1) top-level fences in LDS: number of top keys <= q
-#pragma unroll
-                    for (int g = 0; g < kRunGroup; g++) {
-                        const uint32_t r = r0 + g;
-                        lo[g] = 0;
-                        hi[g] = (!found && r < n_runs) ? s.n_top[r] : 0;
-                        if (!((maybe >> r) & 1)) hi[g] = 0;  // excluded by the run's Bloom filter
-                    }
-                    {
-                        bool some = false;
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) some = some || hi[g] != 0;
-                        if (__ballot(some) == 0) continue;  // no key of the chunk needs these runs
-                    }
-                    for (;;) {
-                        bool any = false;
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) {
-                            if (lo[g] < hi[g]) {
-                                any = true;
-                                const uint32_t mid = (lo[g] + hi[g]) >> 1, slot = s.first_slot[r0 + g] + mid;
-                                const int c = compare_key(q, s.top_lo[slot], [&] { return s.top_hi[slot]; });
-                                if (c < 0) hi[g] = mid;
-                                else lo[g] = mid + 1;
-                            }
+                    uint32_t lo = 0, hi = act ? s.n_top[r] : 0;
+                    const uint32_t first_slot = s.first_slot[r];
+                    while (__ballot(lo < hi) != 0) {
+                        if (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1, slot = first_slot + mid;
+                            const int c = compare_key(q, s.top_lo[slot], [&] { return s.top_hi[slot]; });
+                            if (c < 0) hi = mid;
+                            else lo = mid + 1;
                         }
-                        if (!any) break;
                     }
                     // (2) the fences between two top keys, in global memory: number of fences <= q
-#pragma unroll
-                    for (int g = 0; g < kRunGroup; g++) {
-                        const uint32_t r = r0 + g;
-                        if (lo[g] > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the run is skipped)
-                            const uint32_t ts = s.top_stride[r];
-                            const uint64_t nf = tree.run[r].n_fences;
-                            const uint64_t end = (uint64_t)lo[g] * ts;
-                            hi[g] = (uint32_t)(end < nf ? end : nf);
-                            lo[g] = (lo[g] - 1) * ts + 1;  // fence (lo-1)*ts is <= q
-                        } else {
-                            hi[g] = 0;
-                        }
+                    const uint8_t* fences = s.fences[r];
+                    if (lo > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the lane is idle)
+                        const uint32_t ts = s.top_stride[r];
+                        const uint64_t nf = s.n_fences[r], end = (uint64_t)lo * ts;
+                        hi = (uint32_t)(end < nf ? end : nf);
+                        lo = (lo - 1) * ts + 1;  // fence (lo-1)*ts is <= q
+                    } else {
+                        hi = 0;
                     }
-                    for (;;) {
-                        bool any = false;
-                        uint4 f[kRunGroup];
-                        uint32_t mid[kRunGroup];
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) {
-                            mid[g] = (lo[g] + hi[g]) >> 1;
-                            if (lo[g] < hi[g]) {
-                                any = true;
-                                f[g] = *reinterpret_cast<const uint4*>(tree.run[r0 + g].fences + (uint64_t)mid[g] * LSM_KEY_BYTES);
-                            }
-                        }
-                        if (!any) break;
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) {
-                            if (lo[g] < hi[g]) {
-                                const uint8_t* fp = tree.run[r0 + g].fences + (uint64_t)mid[g] * LSM_KEY_BYTES;
-                                const int c = compare_key(q, f[g], [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
-                                if (c < 0) hi[g] = mid[g];
-                                else lo[g] = mid[g] + 1;
-                            }
+                    while (__ballot(lo < hi) != 0) {
+                        if (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            const uint8_t* fp = fences + (uint64_t)mid * LSM_KEY_BYTES;
+                            const int c = compare_key(q, *reinterpret_cast<const uint4*>(fp), [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
+                            if (c < 0) hi = mid;
+                            else lo = mid + 1;
                         }
                     }
                     // (3) the page of the last fence <= q: first entry whose key is >= q
-                    uint64_t page[kRunGroup];
-#pragma unroll
-                    for (int g = 0; g < kRunGroup; g++) {
-                        const uint32_t r = r0 + g;
-                        page[g] = 0;
-                        if (lo[g] > 0) {  // lo = fences <= q
-                            const uint32_t stride = tree.run[r].stride;
-                            page[g] = (uint64_t)(lo[g] - 1) * stride;
-                            const uint64_t left = tree.run[r].n - page[g];
-                            hi[g] = (uint32_t)(left < stride ? left : stride);
-                            lo[g] = 0;
-                        } else {
-                            hi[g] = 0;
+                    const lsm_entry_t* page = s.entries[r];
+                    uint32_t page_len = 0;
+                    if (lo > 0) {  // lo = fences <= q
+                        const uint32_t stride = s.stride[r];
+                        const uint64_t start = (uint64_t)(lo - 1) * stride, left = s.n[r] - start;
+                        page += start;
+                        page_len = (uint32_t)(left < stride ? left : stride);
+                    }
+                    lo = 0;
+                    hi = page_len;
+                    while (__ballot(lo < hi) != 0) {
+                        if (lo < hi) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            const uint4* ep = reinterpret_cast<const uint4*>(page + mid);
+                            const int c = compare_key(q, ep[0], [&] { return ep[1]; });
+                            if (c > 0) lo = mid + 1;
+                            else hi = mid;
                         }
                     }
-                    uint32_t page_len[kRunGroup];
-#pragma unroll
-                    for (int g = 0; g < kRunGroup; g++) page_len[g] = hi[g];
-                    for (;;) {
-                        bool any = false;
-                        uint4 f[kRunGroup];
-                        uint32_t mid[kRunGroup];
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) {
-                            mid[g] = (lo[g] + hi[g]) >> 1;
-                            if (lo[g] < hi[g]) {
-                                any = true;
-                                f[g] = *reinterpret_cast<const uint4*>(tree.run[r0 + g].entries + page[g] + mid[g]);
-                            }
-                        }
-                        if (!any) break;
-#pragma unroll
-                        for (int g = 0; g < kRunGroup; g++) {
-                            if (lo[g] < hi[g]) {
-                                const lsm_entry_t* ep = tree.run[r0 + g].entries + page[g] + mid[g];
-                                const int c = compare_key(q, f[g], [&] { return reinterpret_cast<const uint4*>(ep)[1]; });
-                                if (c > 0) lo[g] = mid[g] + 1;
-                                else hi[g] = mid[g];
-                            }
-                        }
-                    }
-                    // (4) newest run of the group that holds the key
-#pragma unroll
-                    for (int g = 0; g < kRunGroup; g++) {
-                        if (!found && lo[g] < page_len[g]) {
-                            const uint4* e = reinterpret_cast<const uint4*>(tree.run[r0 + g].entries + page[g] + lo[g]);
-                            if (compare_key(q, e[0], [&] { return e[1]; }) == 0) {
-                                found = true;
-                                const uint4 meta = e[2], val = e[3];  // seqno | type + pad, vptr | vlen + pad
-                                if ((meta.z & 0xFF) == LSM_PUT) {
-                                    live = true;
-                                    h = make_uint4(val.x, val.y, val.z, r0 + g);
-                                }
+                    // (4) is it there?
+                    if (lo < page_len) {
+                        const uint4* e = reinterpret_cast<const uint4*>(page + lo);
+                        if (compare_key(q, e[0], [&] { return e[1]; }) == 0) {
+                            found = true;
+                            const uint4 meta = e[2], val = e[3];  // seqno | type + pad, vptr | vlen + pad
+                            if ((meta.z & 0xFF) == LSM_PUT) {
+                                live = true;
+                                h = make_uint4(val.x, val.y, val.z, r);
                             }
                         }
                     }
