@@ -29,6 +29,7 @@ LSM_BOTTOMMOST = 1
 class LevelRun:
     run: Any      # backend handle of the entries (has .shape[0] = number of entries)
     fences: Any   # backend handle of its fence index
+    bloom: Any = None  # backend handle of its Bloom filter, if the backend builds them
 
     @property
     def n(self) -> int:
@@ -38,10 +39,11 @@ class LevelRun:
 class GpuBackend:
     """The library calls the driver needs, on torch CUDA tensors."""
 
-    def __init__(self, fence_stride: int = 64):
+    def __init__(self, fence_stride: int = 64, bloom_bits: int = 0):
         from . import binding
         self._b = binding
         self.fence_stride = fence_stride
+        self.bloom_bits = bloom_bits  # bits per key of the per-run Bloom filters; 0 = none
 
     def compact(self, runs: Sequence[Any], flags: int) -> Any:
         out, n_out = self._b.lsm_compact(list(runs), flags)
@@ -53,8 +55,11 @@ class GpuBackend:
     def build_fences(self, run: Any) -> Any:
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
+    def build_bloom(self, run: Any) -> Any:
+        return self._b.lsm_build_bloom(run.contiguous(), self.bloom_bits) if self.bloom_bits else None
+
     def probe(self, qkeys: Any, n_blocks: Any, tree: Sequence[LevelRun]) -> Tuple[Any, Any]:
-        tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i) for i, t in enumerate(tree)]
+        tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i, t.bloom) for i, t in enumerate(tree)]
         return self._b.lsm_probe(qkeys, n_blocks, tr)
 
     def hit_len_to_host(self, hit_len: Any) -> List[int]:
@@ -87,7 +92,12 @@ class AdaptiveLsmTree:
         while len(self.levels) <= level:
             self.levels.append([])
             self.level_k.append(self.runs_per_level)
-        self.levels[level] = [LevelRun(r, self.backend.build_fences(r)) for r in runs_newest_first]
+        self.levels[level] = [self._index(r) for r in runs_newest_first]
+
+    def _index(self, run: Any) -> LevelRun:
+        """A run with the lookup structures the backend builds for it (fence index, optional Bloom filter)."""
+        build_bloom = getattr(self.backend, "build_bloom", None)
+        return LevelRun(run, self.backend.build_fences(run), build_bloom(run) if build_bloom else None)
 
     def capacity(self, level: int) -> int:
         return self.buffer_entries * self.size_ratio ** (level + 1)
@@ -100,7 +110,7 @@ class AdaptiveLsmTree:
 
     def flush(self, run: Any) -> None:
         """A sorted run from the write buffer enters level 1."""
-        self._arrive(0, LevelRun(run, self.backend.build_fences(run)))
+        self._arrive(0, self._index(run))
 
     def _arrive(self, level: int, newcomer: LevelRun) -> None:
         while len(self.levels) <= level:
@@ -117,14 +127,12 @@ class AdaptiveLsmTree:
         merged = self.backend.compact([r.run for r in lv], flags)
         self.trace.append(("compact", level + 1, len(lv), n_in, int(merged.shape[0]), flags))
         self.levels[level] = []
-        merged_run = LevelRun(merged, None)
-        if merged_run.n > self.capacity(level):
-            self.trace.append(("move", level + 1, level + 2, merged_run.n))
-            merged_run.fences = self.backend.build_fences(merged)
-            self._arrive(level + 1, merged_run)
-        elif merged_run.n > 0:
-            merged_run.fences = self.backend.build_fences(merged)
-            self.levels[level] = [merged_run]
+        n_merged = int(merged.shape[0])
+        if n_merged > self.capacity(level):
+            self.trace.append(("move", level + 1, level + 2, n_merged))
+            self._arrive(level + 1, self._index(merged))
+        elif n_merged > 0:
+            self.levels[level] = [self._index(merged)]
 
     # ------------------------------------------------------------------ operations and controller
     def _count(self, writes: int, hits: int, empties: int, blocks: float) -> None:

@@ -40,9 +40,10 @@ def _replay(backend, trace, runs, keep_probes):
     return tree
 
 
-@pytest.mark.parametrize("tree_total,buffer_entries,ops,shares", [(400_000, 360, 4096, (0.9, 0.5, 0.1)),
-                                                                  (2_000_000, 900, 8192, (0.9, 0.5, 0.02))])
-def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops, shares):
+@pytest.mark.parametrize("tree_total,buffer_entries,ops,shares,bloom_bits", [(400_000, 360, 4096, (0.9, 0.5, 0.1), 0),
+                                                                             (2_000_000, 900, 8192, (0.9, 0.5, 0.02), 0),
+                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), 16)])
+def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops, shares, bloom_bits):
     from paper_2511_16138_amd.tree import GpuBackend
     from workloads import lsm
     print("mixed trace", tree_total, buffer_entries, ops, flush=True)
@@ -50,7 +51,7 @@ def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops,
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
 
     gpu_probes, cpu_probes = [], []
-    gpu_tree = _replay(GpuBackend(), tr, tr.workload.runs, gpu_probes)
+    gpu_tree = _replay(GpuBackend(bloom_bits=bloom_bits), tr, tr.workload.runs, gpu_probes)  # the checker has no filters
     torch.cuda.synchronize()
 
     cpu_trace = lsm.MixedTrace(tr.workload, tr.buffer_entries, tr.size_ratio, tr.flush_runs.cpu(), tr.events, tr.batch_requests,
