@@ -1,6 +1,6 @@
 // lsm_build_bloom: blocked Bloom filter of a run (paper section 2.2 names Bloom filters as the structure that
 // lets a lookup skip a run; appendix B uses point lookups in "Probe").  One thread per entry: hash the key,
-// OR its six bits into the 16-byte block.  Bits only ever get set, so the result is the same for any order.
+// OR its six bits into the 16-byte block (two 64-bit atomics at most).  Bits only ever get set, so the result is the same for any order.
 #include <hip/hip_runtime.h>
 
 #include "lsm_common.h"
@@ -17,11 +17,11 @@ __global__ void bloom_insert_kernel(const lsm_entry_t* entries, uint64_t n, uint
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
         uint4 mask;
         const uint32_t block = bloom_block(bloom_hash(load_key(entries + i), mask), n_blocks);
-        uint32_t* w = words + (uint64_t)block * 4;
-        if (mask.x) atomicOr(w + 0, mask.x);
-        if (mask.y) atomicOr(w + 1, mask.y);
-        if (mask.z) atomicOr(w + 2, mask.z);
-        if (mask.w) atomicOr(w + 3, mask.w);
+        // two 64-bit halves (little-endian: word 0 is the low half of the first)
+        unsigned long long* w = reinterpret_cast<unsigned long long*>(words + (uint64_t)block * 4);
+        const unsigned long long lo = ((unsigned long long)mask.y << 32) | mask.x, hi = ((unsigned long long)mask.w << 32) | mask.z;
+        if (lo) atomicOr(w + 0, lo);
+        if (hi) atomicOr(w + 1, hi);
     }
 }
 
