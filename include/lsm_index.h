@@ -7,7 +7,8 @@
  * section 3.1 "disk index layer" / "tensor-log layer", section 3.2).  This library runs the
  * data-parallel part of that index on one AMD MI355X (gfx950):
  *
- *   lsm_compact       merge sorted runs into one run (section 2.2, compaction)
+ *   lsm_compact       merge sorted runs into one run (section 2.2, compaction); lsm_compact_remap also rewrites
+ *                     value pointers for merged tensor files (section 3.4)
  *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
  *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes)
  *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
@@ -184,6 +185,23 @@ typedef struct {
 
 int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                       size_t workspace_bytes, void* stream, const lsm_compact_events_t* ev);
+
+/*
+ * lsm_compact_remap -- lsm_compact that also rewrites the value pointers of the entries it writes (section 3.4,
+ * automatic tensor-file merging: when tensor files are merged "during scheduled compaction cycles", the file id
+ * and offset stored in the index entries are updated).  A value pointer is (file_id << 32) | offset.  For every
+ * surviving PUT whose file_id < n_files:  vptr_out = base[file_id] + offset  (64-bit addition; base[f] is the new
+ * (file_id << 32) | offset of old file f's first byte).  Other entries - tombstones, files outside the table -
+ * are copied unchanged.  base: DEVICE, n_files x uint64.  remap == NULL or n_files == 0 is exactly lsm_compact.
+ * ev may be NULL (see lsm_compact_timed).  Errors as lsm_compact, plus LSM_ERR_NULL for a table without base.
+ */
+typedef struct {
+    const uint64_t* base;
+    uint32_t n_files;
+} lsm_remap_t;
+
+int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                      size_t workspace_bytes, void* stream, const lsm_remap_t* remap, const lsm_compact_events_t* ev);
 
 /* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments.
  * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per 1984 entries. */

@@ -124,6 +124,19 @@ def build_fences(run, stride: int) -> np.ndarray:
     return out
 
 
+def remap_pointers(run, base) -> np.ndarray:
+    """Pointer rewrite for merged tensor files (section 3.4): a value pointer is (file_id << 32) | offset;
+    every PUT whose file_id is inside the table gets base[file_id] + offset, everything else stays."""
+    out = as_run(run).copy()
+    rec = out.view(ENTRY_DTYPE).reshape(-1)
+    base = np.asarray(base, dtype=np.uint64)
+    for i in range(rec.shape[0]):
+        file_id, offset = int(rec["vptr"][i]) >> 32, int(rec["vptr"][i]) & 0xFFFFFFFF
+        if int(rec["type"][i]) == 0 and file_id < base.shape[0]:
+            rec["vptr"][i] = (int(base[file_id]) + offset) & 0xFFFFFFFFFFFFFFFF
+    return out
+
+
 def bloom_blocks(n: int, bits_per_key: int) -> int:
     return int(lib().oracle_bloom_blocks(n, bits_per_key))
 

@@ -71,6 +71,10 @@ class _CompactEvents(C.Structure):
     _fields_ = [("before_partition", C.c_void_p), ("before_merge", C.c_void_p), ("after_merge", C.c_void_p)]
 
 
+class _Remap(C.Structure):
+    _fields_ = [("base", C.c_void_p), ("n_files", C.c_uint32)]
+
+
 class _PolicyInput(C.Structure):
     _fields_ = [("w", C.c_double), ("s", C.c_double), ("r", C.c_double), ("z", C.c_double), ("n_entries", C.c_uint64),
                 ("buffer_entries", C.c_uint64), ("B", C.c_double), ("p", C.c_double), ("d", C.c_double)]
@@ -91,6 +95,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_compact.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_uint32, C.POINTER(_Out), C.c_void_p, C.c_size_t, C.c_void_p]
     L.lsm_compact_timed.restype = C.c_int
     L.lsm_compact_timed.argtypes = L.lsm_compact.argtypes + [C.POINTER(_CompactEvents)]
+    L.lsm_compact_remap.restype = C.c_int
+    L.lsm_compact_remap.argtypes = L.lsm_compact.argtypes + [C.POINTER(_Remap), C.POINTER(_CompactEvents)]
     L.lsm_compact_workspace_bytes.restype = C.c_size_t
     L.lsm_compact_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), C.c_uint32]
     L.lsm_build_fences.restype = C.c_int
@@ -138,10 +144,12 @@ def lsm_compact_workspace_bytes(run_lens: Sequence[int]) -> int:
 
 def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torch.Tensor] = None,
                 n_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
-                events: Optional[Tuple[int, int, int]] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+                events: Optional[Tuple[int, int, int]] = None, remap: Optional[torch.Tensor] = None
+                ) -> Tuple[torch.Tensor, torch.Tensor]:
     """Merge sorted runs (runs[0] newest).  Returns (out, n_out): out is int64 [capacity, 8]
     whose first n_out rows are the result, n_out a one-element int64 tensor on the device.
-    `events` = three raw hipEvent_t handles (or 0) for lsm_compact_timed."""
+    `events` = three raw hipEvent_t handles (or 0) for lsm_compact_timed; `remap` = int64 [n_files]
+    table of new pointer bases for lsm_compact_remap."""
     L = _load()
     runs = [_dev(r, "run") for r in runs]
     total = sum(int(r.shape[0]) for r in runs)
@@ -156,7 +164,12 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
     od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr())
     ws_ptr, ws_bytes = _dev(workspace, "workspace").data_ptr(), workspace.numel() * workspace.element_size()
-    if events is None:
+    if remap is not None:
+        rm = _Remap(_dev(remap, "remap table").data_ptr(), int(remap.shape[0]))
+        ev = _CompactEvents(*[C.c_void_p(e or None) for e in events]) if events is not None else None
+        rc = L.lsm_compact_remap(rd, len(runs), flags, C.byref(od), ws_ptr, ws_bytes, _stream_ptr(stream), C.byref(rm),
+                                 C.byref(ev) if ev is not None else None)
+    elif events is None:
         rc = L.lsm_compact(rd, len(runs), flags, C.byref(od), ws_ptr, ws_bytes, _stream_ptr(stream))
     else:
         ev = _CompactEvents(*[C.c_void_p(e or None) for e in events])

@@ -472,7 +472,8 @@ __device__ __forceinline__ bool tail_less(const uint4 a0, const uint4 a1, const 
 
 // two workgroups per compute unit = four waves per SIMD: at most 128 vector registers
 __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
-                                                               lsm_entry_t* out, uint64_t* n_out) {
+                                                               lsm_entry_t* out, uint64_t* n_out, const uint64_t* remap_base,
+                                                               uint32_t remap_files) {
     __shared__ MergeShared s;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -879,6 +880,12 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         for (int i = 0; i < kMergeItems; i++) {
             const uint32_t e = tid + i * kMergeThreads;
             if (e < n && (s.flag[pos[i]] & kFlagSurvive)) {
+                // pointer rewrite for merged tensor files (paper section 3.4): vptr = base[file] + offset
+                if (first == 0 && remap_files != 0 && (ent[i][2].z & 0xFF) == LSM_PUT && ent[i][3].y < remap_files) {
+                    const uint64_t v = remap_base[ent[i][3].y] + ent[i][3].x;
+                    ent[i][3].x = (uint32_t)v;
+                    ent[i][3].y = (uint32_t)(v >> 32);
+                }
                 const uint32_t slot = (uint32_t)s.prefix[pos[i]] - first;  // wraps for slots before this pass
                 if (slot < (uint32_t)kStageEntries) {
 #pragma unroll
@@ -960,7 +967,15 @@ extern "C" int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flag
 
 extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                                  size_t workspace_bytes, void* stream_v, const lsm_compact_events_t* ev) {
+    return lsm_compact_remap(runs, n_runs, flags, out, workspace, workspace_bytes, stream_v, nullptr, ev);
+}
+
+extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                                 size_t workspace_bytes, void* stream_v, const lsm_remap_t* remap, const lsm_compact_events_t* ev) {
     using namespace lsm;
+    if (remap != nullptr && remap->n_files != 0 && remap->base == nullptr) return LSM_ERR_NULL;
+    const uint64_t* remap_base = remap ? remap->base : nullptr;
+    const uint32_t remap_files = remap ? remap->n_files : 0;
     if (runs == nullptr || out == nullptr || out->n_out == nullptr) return LSM_ERR_NULL;
     if (n_runs == 0 || n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
     RunTable rt;
@@ -1034,7 +1049,7 @@ extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_
         return LSM_ERR_HIP;
     if (n_tiles > 0)
         hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
-                           out->entries, out->n_out);
+                           out->entries, out->n_out, remap_base, remap_files);
     if (ev && ev->after_merge && hipEventRecord(static_cast<hipEvent_t>(ev->after_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
     if (hipGetLastError() != hipSuccess) return LSM_ERR_HIP;

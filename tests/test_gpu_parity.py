@@ -317,3 +317,30 @@ def test_probe_with_bloom_filters_gives_the_same_answers(g, oracle, cfg1):
                 bloom = g.lsm_build_bloom(t.run, 16, out=torch.empty((3, 4), dtype=torch.int32, device=dev()))  # nearly all ones
             tree.append(g.TreeRun(t.run, t.fences, t.stride, t.level, bloom))
         assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)
+
+
+# ------------------------------------------------------------------ pointer rewrite during compaction (section 3.4)
+def test_compaction_with_pointer_rewrite(g, oracle, cfg1):
+    """lsm_compact_remap = compaction followed by the checker's pointer rewrite: several tensor files folded into
+    fewer, files outside the table and tombstones untouched; an empty table is plain compaction."""
+    print("pointer rewrite", flush=True)
+    runs = cfg1.runs
+    files = torch.cat([(r[:, 6] >> 32) & 0xFFFFFFFF for r in runs])
+    n_files = int(files.max().item()) + 1
+    assert n_files > 4
+    table_len = n_files - 2  # the two highest file ids stay as they are
+    rs = np.random.RandomState(9)
+    # old files f -> new file f // 4, placed one after the other inside it
+    starts = rs.randint(0, 1 << 20, size=table_len).cumsum()
+    base = torch.tensor([((f // 4) << 32) + int(starts[f]) for f in range(table_len)], dtype=torch.int64, device=dev())
+    for flags in (0, 1):
+        out, n_out = g.lsm_compact(runs, flags, remap=base)
+        torch.cuda.synchronize()
+        got = out[: int(n_out.item())]
+        plain = oracle.compact([r.cpu() for r in runs], flags & 1)
+        want = oracle.remap_pointers(plain, base.cpu().numpy().astype(np.uint64))
+        assert np.array_equal(as_bytes(got).reshape(-1, 64), want)
+        assert not np.array_equal(want, plain)
+        out2, n2 = g.lsm_compact(runs, flags, remap=base[:0])
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(out2[: int(n2.item())]).reshape(-1, 64), plain)

@@ -246,3 +246,31 @@ def test_planted_mistakes_are_caught(oracle):
     # a merge that prefers the lowest run index instead of the largest seqno would keep vptr=1
     assert brute.unpack(_oc(oracle, runs, False)[0])[3] == 2
     assert _oc(oracle, runs, True) == []
+
+
+# ------------------------------------------------------------------ pointer rewrite (section 3.4)
+def test_pointer_rewrite_against_plain_arithmetic(oracle):
+    """remap_pointers on packed entries vs the rule written out with Python integers: PUTs inside the table
+    move, tombstones and files outside the table do not; the identity table changes nothing."""
+    rs = np.random.RandomState(3)
+    raws = []
+    for i in range(300):
+        key = bytes(rs.randint(0, 256, size=32).astype(np.uint8))
+        file_id, offset = int(rs.randint(0, 12)), int(rs.randint(0, 1 << 31))
+        typ = brute.TOMBSTONE if i % 7 == 0 else brute.PUT
+        raws.append(brute.pack_entry(key, i, typ, (file_id << 32) | offset if typ == brute.PUT else 0, 77, b"\x05" * 7, 9))
+    run = brute.run_from_raw(sorted(raws, key=lambda r: r[:32]))
+    n_files = 8  # files 8..11 are outside the table
+    # files 0..7 concatenated into new file 100: base = start of each old file in the new one
+    sizes = [int(rs.randint(1 << 31, 1 << 32)) for _ in range(n_files)]
+    starts = [sum(sizes[:f]) for f in range(n_files)]  # may exceed 32 bits: the carry goes into the file field
+    base = [((100 << 32) + st) for st in starts]
+    got = oracle.remap_pointers(run, base)
+    for before, after in zip(brute.raws_of(run), brute.raws_of(got)):
+        key, seqno, typ, vptr, vlen = brute.unpack(before)
+        key2, seqno2, typ2, vptr2, vlen2 = brute.unpack(after)
+        assert (key, seqno, typ, vlen) == (key2, seqno2, typ2, vlen2) and before[41:48] == after[41:48] and before[60:] == after[60:]
+        f, off = vptr >> 32, vptr & 0xFFFFFFFF
+        assert vptr2 == ((100 << 32) + starts[f] + off if typ == brute.PUT and f < n_files else vptr)
+    assert np.array_equal(oracle.remap_pointers(run, [f << 32 for f in range(12)]), run)
+    assert np.array_equal(oracle.remap_pointers(run, []), run)
