@@ -40,7 +40,8 @@ class _Run(C.Structure):
 
 
 class _Out(C.Structure):
-    _fields_ = [("entries", C.c_void_p), ("capacity", C.c_uint64), ("n_out", C.c_void_p)]
+    _fields_ = [("entries", C.c_void_p), ("capacity", C.c_uint64), ("n_out", C.c_void_p), ("fence_keys", C.c_void_p),
+                ("fence_stride", C.c_uint32)]
 
 
 class _Fence(C.Structure):
@@ -144,12 +145,13 @@ def lsm_compact_workspace_bytes(run_lens: Sequence[int]) -> int:
 
 def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torch.Tensor] = None,
                 n_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
-                events: Optional[Tuple[int, int, int]] = None, remap: Optional[torch.Tensor] = None
-                ) -> Tuple[torch.Tensor, torch.Tensor]:
+                events: Optional[Tuple[int, int, int]] = None, remap: Optional[torch.Tensor] = None,
+                fences: Optional[torch.Tensor] = None, fence_stride: int = 64) -> Tuple[torch.Tensor, torch.Tensor]:
     """Merge sorted runs (runs[0] newest).  Returns (out, n_out): out is int64 [capacity, 8]
     whose first n_out rows are the result, n_out a one-element int64 tensor on the device.
     `events` = three raw hipEvent_t handles (or 0) for lsm_compact_timed; `remap` = int64 [n_files]
-    table of new pointer bases for lsm_compact_remap."""
+    table of new pointer bases for lsm_compact_remap; `fences` = int64 [>= ceil(capacity / fence_stride), 4]
+    that receives the fence index of the result (its first ceil(n_out / fence_stride) rows)."""
     L = _load()
     runs = [_dev(r, "run") for r in runs]
     total = sum(int(r.shape[0]) for r in runs)
@@ -162,7 +164,10 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
-    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr())
+    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
+              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0)
+    if fences is not None and fence_stride > 0 and fences.shape[0] * fence_stride < out.shape[0]:
+        raise ValueError("fences is too short for the output capacity")
     ws_ptr, ws_bytes = _dev(workspace, "workspace").data_ptr(), workspace.numel() * workspace.element_size()
     if remap is not None:
         rm = _Remap(_dev(remap, "remap table").data_ptr(), int(remap.shape[0]))

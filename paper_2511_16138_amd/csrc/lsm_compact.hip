@@ -470,10 +470,12 @@ __device__ __forceinline__ bool tail_less(const uint4 a0, const uint4 a1, const 
     return __builtin_bswap64(((uint64_t)a1.w << 32) | a1.z) < __builtin_bswap64(((uint64_t)b1.w << 32) | b1.z);
 }
 
-// two workgroups per compute unit = four waves per SIMD: at most 128 vector registers
+// two workgroups per compute unit = four waves per SIMD: at most 128 vector registers.
+// kExtras: the output pass also rewrites value pointers and / or writes the fence index (compiled out otherwise).
+template <bool kExtras>
 __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
                                                                lsm_entry_t* out, uint64_t* n_out, const uint64_t* remap_base,
-                                                               uint32_t remap_files) {
+                                                               uint32_t remap_files, uint4* fence_out, uint32_t fence_stride) {
     __shared__ MergeShared s;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -881,7 +883,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             const uint32_t e = tid + i * kMergeThreads;
             if (e < n && (s.flag[pos[i]] & kFlagSurvive)) {
                 // pointer rewrite for merged tensor files (paper section 3.4): vptr = base[file] + offset
-                if (first == 0 && remap_files != 0 && (ent[i][2].z & 0xFF) == LSM_PUT && ent[i][3].y < remap_files) {
+                if (kExtras && first == 0 && remap_files != 0 && (ent[i][2].z & 0xFF) == LSM_PUT && ent[i][3].y < remap_files) {
                     const uint64_t v = remap_base[ent[i][3].y] + ent[i][3].x;
                     ent[i][3].x = (uint32_t)v;
                     ent[i][3].y = (uint32_t)(v >> 32);
@@ -902,7 +904,16 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         }
         const uint32_t count = min(total - first, (uint32_t)kStageEntries);
         uint4* dst = reinterpret_cast<uint4*>(out + base + first);
-        for (uint32_t c = tid; c < count * 4; c += kMergeThreads) dst[(c & ~3u) | ((c ^ (c >> 2)) & 3)] = stage[c];
+        for (uint32_t c = tid; c < count * 4; c += kMergeThreads) {
+            const uint32_t part = (c ^ (c >> 2)) & 3;  // which 16 bytes of the entry stage[c] holds
+            const uint4 v = stage[c];
+            dst[(c & ~3u) | part] = v;
+            // fence index of the new run: the key of every fence_stride-th output entry
+            if (kExtras && fence_out != nullptr && part < 2) {
+                const uint64_t at = base + first + (c >> 2);
+                if (at % fence_stride == 0) fence_out[(at / fence_stride) * 2 + part] = v;
+            }
+        }
         first += kStageEntries;
         if (first < total) __syncthreads();  // the stage is reused
     } while (first < total);
@@ -995,6 +1006,8 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
     if (total > 0 && out->entries == nullptr) return LSM_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(out->entries) & 63) != 0) return LSM_ERR_BAD_ARG;
     if (out->capacity < total) return LSM_ERR_CAPACITY;
+    if (out->fence_keys != nullptr && (out->fence_stride == 0 || (reinterpret_cast<uintptr_t>(out->fence_keys) & 15) != 0))
+        return LSM_ERR_BAD_ARG;
     uint64_t lens[LSM_MAX_RUNS];
     for (uint32_t j = 0; j < n_runs; j++) lens[j] = runs[j].n;
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
@@ -1047,9 +1060,16 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
     }
     if (ev && ev->before_merge && hipEventRecord(static_cast<hipEvent_t>(ev->before_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
-    if (n_tiles > 0)
-        hipLaunchKernelGGL(merge_kernel, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
-                           out->entries, out->n_out, remap_base, remap_files);
+    if (n_tiles > 0) {
+        uint4* const fence_out = reinterpret_cast<uint4*>(out->fence_keys);
+        const uint32_t fence_stride = out->fence_keys ? out->fence_stride : 1u;
+        if (remap_files != 0 || fence_out != nullptr)
+            hipLaunchKernelGGL(merge_kernel<true>, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride);
+        else
+            hipLaunchKernelGGL(merge_kernel<false>, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride);
+    }
     if (ev && ev->after_merge && hipEventRecord(static_cast<hipEvent_t>(ev->after_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
     if (hipGetLastError() != hipSuccess) return LSM_ERR_HIP;

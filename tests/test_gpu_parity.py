@@ -344,3 +344,19 @@ def test_compaction_with_pointer_rewrite(g, oracle, cfg1):
         out2, n2 = g.lsm_compact(runs, flags, remap=base[:0])
         torch.cuda.synchronize()
         assert np.array_equal(as_bytes(out2[: int(n2.item())]).reshape(-1, 64), plain)
+
+
+@pytest.mark.parametrize("stride", [1, 64, 100])
+def test_fence_index_written_by_the_compaction(g, oracle, cfg1, stride):
+    """The fence keys lsm_compact writes along with the run equal those lsm_build_fences and the checker give."""
+    print("fused fences", stride, flush=True)
+    total = sum(int(r.shape[0]) for r in cfg1.runs)
+    for flags in (0, 1):
+        fences = torch.full(((total + stride - 1) // stride, 4), -1, dtype=torch.int64, device=dev())
+        out, n_out = g.lsm_compact(cfg1.runs, flags, fences=fences, fence_stride=stride)
+        torch.cuda.synchronize()
+        n = int(n_out.item())
+        want = oracle.build_fences(oracle.compact([r.cpu() for r in cfg1.runs], flags & 1), stride)
+        n_f = (n + stride - 1) // stride
+        assert np.array_equal(as_bytes(fences[:n_f]).reshape(-1, 32), want)
+        assert bool((fences[n_f:] == -1).all())  # nothing written past the end

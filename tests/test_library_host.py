@@ -36,7 +36,7 @@ def test_every_declared_entry_point_is_exported(lib):
 
 def test_struct_sizes_match_the_header():
     import paper_2511_16138_amd.binding as B
-    assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 24 and C.sizeof(B._Fence) == 24
+    assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 40 and C.sizeof(B._Fence) == 24
     assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 64 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
     assert C.sizeof(B._PolicyInput) == 72
 
@@ -45,21 +45,32 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     import paper_2511_16138_amd.binding as B
     n_out = C.c_uint64(123)
     run = B._Run(None, 0)
-    out = B._Out(None, 0, C.addressof(n_out))
+    out = B._Out(None, 0, C.addressof(n_out), None, 0)
     assert lib.lsm_compact(None, 1, 0, C.byref(out), None, 0, None) == -1          # NULL runs
     assert lib.lsm_compact(C.byref(run), 0, 0, C.byref(out), None, 0, None) == -2  # n_runs == 0
     assert lib.lsm_compact(C.byref(run), 65, 0, C.byref(out), None, 0, None) == -2
     bad = B._Run(None, 5)
     assert lib.lsm_compact(C.byref(bad), 1, 0, C.byref(out), None, 0, None) == -1  # n > 0 but no entries
     fake = B._Run(64 * 1000, 10)
-    small = B._Out(64 * 2000, 9, C.addressof(n_out))
+    small = B._Out(64 * 2000, 9, C.addressof(n_out), None, 0)
     assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(small), None, 0, None) == -3  # capacity
-    big = B._Out(64 * 2000, 10, C.addressof(n_out))
+    big = B._Out(64 * 2000, 10, C.addressof(n_out), None, 0)
     assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(big), None, 0, None) == -4    # workspace
     assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 16, None) == -4
     misaligned = B._Run(64 * 1000 + 8, 10)
     assert lib.lsm_compact(C.byref(misaligned), 1, 0, C.byref(big), 256 * 7, 1 << 20, None) == -2
     assert n_out.value == 123
+    # new entry points: the same kind of checks, all before any launch
+    fenced = B._Out(64 * 2000, 10, C.addressof(n_out), 16 * 5, 0)
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(fenced), 256 * 7, 1 << 20, None) == -2     # fence stride 0
+    odd = B._Out(64 * 2000, 10, C.addressof(n_out), 16 * 5 + 4, 64)
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(odd), 256 * 7, 1 << 20, None) == -2        # fence keys misaligned
+    table = B._Remap(None, 3)
+    assert lib.lsm_compact_remap(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 1 << 20, None, C.byref(table), None) == -1
+    assert lib.lsm_bloom_blocks(0, 16) == 1 and lib.lsm_bloom_blocks(9, 16) == 2 and lib.lsm_bloom_blocks(5, 0) == 0
+    assert lib.lsm_bloom_blocks(1 << 40, 16) == 0
+    assert lib.lsm_build_bloom(None, 64, 1, None) == -1 and lib.lsm_build_bloom(C.byref(fake), None, 1, None) == -1
+    assert lib.lsm_build_bloom(C.byref(fake), 64, 0, None) == -2 and lib.lsm_build_bloom(C.byref(fake), 64 + 8, 1, None) == -2
     assert lib.lsm_build_fences(C.byref(fake), 0, 4096, None) == -2
     assert lib.lsm_build_fences(None, 64, 4096, None) == -1
     assert lib.lsm_build_fences(C.byref(run), 64, None, None) == 0  # empty run: nothing to do
