@@ -8,7 +8,9 @@ A step is one pass of the whole index hot path over one batch of synthetic input
   4. lsm_probe        one batch of 4,096 longest-prefix requests against the merged run
 Inputs are generated on the GPU before the timed region and stay resident in HBM.
 
-Prints one JSON line; see the design doc for the definition of every field.
+Prints one JSON line.  `value` = input entries of the compaction per second of whole step; `roofline` = the merge
+kernel's algorithmic bytes (64 per input entry + 64 per survivor) over its duration against the HBM peak, `traffic`
+its measured HBM bytes; `cpu_baseline` = the CPU checker on a bounded sample; the other sections are labelled.
 """
 from __future__ import annotations
 
@@ -137,8 +139,8 @@ def main() -> int:
                          "whose HBM bytes are known; it scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the index shards by key range without any exchange, "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the index shards by key range without any exchange); "
+              "run with --gpus 1", file=sys.stderr)
         return 2
 
     import torch

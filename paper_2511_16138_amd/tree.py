@@ -46,13 +46,23 @@ class GpuBackend:
         self.bloom_bits = bloom_bits  # bits per key of the per-run Bloom filters; 0 = none
 
     def compact(self, runs: Sequence[Any], flags: int) -> Any:
-        out, n_out = self._b.lsm_compact(list(runs), flags)
+        import torch
+        total = sum(int(r.shape[0]) for r in runs)
+        fences = torch.empty(((total + self.fence_stride - 1) // self.fence_stride, 4), dtype=torch.int64, device=runs[0].device)
+        out, n_out = self._b.lsm_compact(list(runs), flags, fences=fences, fence_stride=self.fence_stride)
         n = int(n_out.item())
         if n < 0 or n > out.shape[0]:
             raise RuntimeError("lsm_compact reported a device-side failure")
-        return out[:n]
+        merged = out[:n]
+        # the compaction wrote the fence index of its output in the same pass: hand it out when asked for this run
+        self._fused = (merged.data_ptr(), n, fences[: (n + self.fence_stride - 1) // self.fence_stride])
+        return merged
 
     def build_fences(self, run: Any) -> Any:
+        fused = getattr(self, "_fused", None)
+        if fused is not None and fused[0] == run.data_ptr() and fused[1] == int(run.shape[0]) and fused[1] > 0:
+            self._fused = None
+            return fused[2]
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
     def build_bloom(self, run: Any) -> Any:
