@@ -198,6 +198,8 @@ def main() -> int:
         g.lsm_compact(runs, g.LSM_BOTTOMMOST, out=out, n_out=n_out_d, workspace=ws,
                       events=(ev_part[i].cuda_event, ev_merge0[i].cuda_event, ev_merge1[i].cuda_event))
         n_out = int(n_out_d.item())  # device -> host, synchronises
+        if not 0 <= n_out <= n_in:
+            raise RuntimeError(f"lsm_compact reported a device-side failure (n_out = {n_out})")
         ev_c1[i].record(stream)
         merged = out[:n_out]
         f = fences[: (n_out + 63) // 64]
