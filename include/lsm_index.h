@@ -247,6 +247,16 @@ int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t n_blocks, v
 int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, const lsm_hits_t* out_hits, void* stream);
 
 /*
+ * lsm_probe_length -- only the length of the longest cached prefix, found as appendix B describes "Probe": by a
+ * search over the prefix length with point lookups, not by a lookup of every block key.  Valid on PREFIX-CLOSED
+ * data: whenever block j of a request is live, blocks 0..j-1 are live too (what leaf-first eviction of cached
+ * sequences gives).  hit_len: DEVICE, n_req values; on such data equal to lsm_probe's.  On other data the value is
+ * some j with block j-1 live (or j == 0) and block j not live (or j == n_blocks).  About 67 point lookups for a
+ * request of 256 blocks, in two dependent rounds.  Errors as lsm_probe.
+ */
+int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* tree, uint32_t* hit_len, void* stream);
+
+/*
  * Cost model of the adaptive controller (host only, double arithmetic).
  *   L = smallest integer >= 1 with buffer_entries * T^L >= n_entries     (section 2.2: L = log_T(N e / M))
  *   W = T L / (B K)   update;  Z = K L p  empty point lookup;  R = K L p + 1  non-empty point

@@ -108,6 +108,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_build_bloom.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_uint64, C.c_void_p]
     L.lsm_probe.restype = C.c_int
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
+    L.lsm_probe_length.restype = C.c_int
+    L.lsm_probe_length.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.c_void_p, C.c_void_p]
     L.lsm_policy_levels.restype = C.c_uint32
     L.lsm_policy_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
     L.lsm_policy_cost.restype = C.c_double
@@ -224,6 +226,34 @@ class TreeRun:
     bloom: Optional[torch.Tensor] = None  # int32 [n_blocks, 4] from lsm_build_bloom, or None
 
 
+def _tree_descriptor(tree: Sequence[TreeRun]):
+    tr = (_TreeRun * max(1, len(tree)))()
+    for i, t in enumerate(tree):
+        tr[i].run = _Run(_dev(t.run, "tree run").data_ptr(), int(t.run.shape[0]))
+        tr[i].fence = _Fence(_dev(t.fences, "fences").data_ptr(), int(t.fences.shape[0]), t.stride)
+        if t.bloom is not None:
+            tr[i].bloom = _Bloom(_dev(t.bloom, "bloom filter").data_ptr(), int(t.bloom.shape[0]))
+        tr[i].level = t.level
+    return _Tree(tr, len(tree)), tr  # tr must outlive the call
+
+
+def lsm_probe_length(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],
+                     hit_len: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Length of the longest cached prefix of every request by a search over the prefix length
+    (prefix-closed data only; see the header)."""
+    L = _load()
+    _dev(qkeys, "qkeys")
+    n_req, max_blocks = int(qkeys.shape[0]), int(qkeys.shape[1])
+    if hit_len is None:
+        hit_len = torch.empty(n_req, dtype=torch.int32, device=qkeys.device)
+    td, _keep = _tree_descriptor(tree)
+    qd = _Queries(qkeys.data_ptr(), _dev(n_blocks, "n_blocks").data_ptr(), n_req, max_blocks)
+    rc = L.lsm_probe_length(C.byref(qd), C.byref(td), _dev(hit_len, "hit_len").data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_probe_length")
+    return hit_len
+
+
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],
               hit_len: Optional[torch.Tensor] = None, hits: Optional[torch.Tensor] = None, stream=None
               ) -> Tuple[torch.Tensor, torch.Tensor]:
@@ -235,14 +265,7 @@ def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRu
         hit_len = torch.empty(n_req, dtype=torch.int32, device=qkeys.device)
     if hits is None:
         hits = torch.empty((n_req, max_blocks, 2), dtype=torch.int64, device=qkeys.device)
-    tr = (_TreeRun * max(1, len(tree)))()
-    for i, t in enumerate(tree):
-        tr[i].run = _Run(_dev(t.run, "tree run").data_ptr(), int(t.run.shape[0]))
-        tr[i].fence = _Fence(_dev(t.fences, "fences").data_ptr(), int(t.fences.shape[0]), t.stride)
-        if t.bloom is not None:
-            tr[i].bloom = _Bloom(_dev(t.bloom, "bloom filter").data_ptr(), int(t.bloom.shape[0]))
-        tr[i].level = t.level
-    td = _Tree(tr, len(tree))
+    td, _keep = _tree_descriptor(tree)
     qd = _Queries(qkeys.data_ptr(), _dev(n_blocks, "n_blocks").data_ptr(), n_req, max_blocks)
     hd = _Hits(_dev(hit_len, "hit_len").data_ptr(), _dev(hits, "hits").data_ptr())
     rc = L.lsm_probe(C.byref(qd), C.byref(td), C.byref(hd), _stream_ptr(stream))

@@ -63,14 +63,9 @@ __device__ __forceinline__ int compare_key(const Key& q, uint4 lo, LoadHi load_h
     return 0;
 }
 
-__global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
-                                                               uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len,
-                                                               lsm_hit_t* hits) {
-    __shared__ ProbeShared s;
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWave - 1);
+// Copies the run descriptors and the top-level fence table into LDS (all threads of the workgroup call this).
+__device__ __forceinline__ void probe_setup(ProbeShared& s, const TreeTable& tree, const int tid) {
     const uint32_t n_runs = tree.n_runs;
-
     // ---- top-level fence table: an equal share of the slots for every run
     const uint32_t share = n_runs ? kTopSlots / n_runs : 0;
     if (tid < (int)n_runs) {
@@ -96,6 +91,114 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
     }
     __syncthreads();
 
+}
+
+// Looks one block key per lane up in the tree (every lane of the wave calls this; lanes with mine == false idle).
+// Returns whether the key's newest version is a live PUT (true for idle lanes) and sets h to its hit record.
+__device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTable& tree, const uint32_t n_runs,
+                                             const uint64_t run_mask, const bool any_bloom, const bool mine, const Key& q, uint4& h) {
+    bool live = !mine, found = !mine;
+    // (0) Bloom filters of the runs that have one: one 16-byte read per run, all runs of a group of
+    //     eight requested together, decides which runs this key is searched in
+    uint64_t maybe = ~0ull;
+    if (mine && any_bloom) {
+        uint4 mask;
+        const uint64_t bh = bloom_hash(q, mask);
+        for (uint32_t rb = 0; rb < n_runs; rb += 8) {
+            uint4 w[8];
+#pragma unroll
+            for (int g = 0; g < 8; g++) {
+                const uint32_t r = rb + g;
+                const uint32_t blocks = r < n_runs ? tree.run[r].bloom_blocks : 0;
+                w[g] = make_uint4(~0u, ~0u, ~0u, ~0u);
+                if (blocks) w[g] = tree.run[r].bloom[bloom_block(bh, blocks)];
+            }
+#pragma unroll
+            for (int g = 0; g < 8; g++)
+                if (bloom_excludes(w[g], mask)) maybe &= ~(1ull << (rb + g));
+        }
+    }
+    maybe &= run_mask;
+    // every lane walks its own list of admitted runs, newest first, so lanes that need different
+    // runs search them at the same time; the walk of a lane ends at the first run that holds its key
+    while (__ballot(!found && maybe != 0) != 0) {
+        const bool act = !found && maybe != 0;
+        const uint32_t r = act ? (uint32_t)__builtin_ctzll(maybe) : 0;
+        maybe &= maybe - 1;  // 0 stays 0
+        // (1) top-level fences in LDS: number of top keys <= q
+        uint32_t lo = 0, hi = act ? s.n_top[r] : 0;
+        const uint32_t first_slot = s.first_slot[r];
+        while (__ballot(lo < hi) != 0) {
+            if (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1, slot = first_slot + mid;
+                const int c = compare_key(q, s.top_lo[slot], [&] { return s.top_hi[slot]; });
+                if (c < 0) hi = mid;
+                else lo = mid + 1;
+            }
+        }
+        // (2) the fences between two top keys, in global memory: number of fences <= q
+        const uint8_t* fences = s.fences[r];
+        if (lo > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the lane is idle)
+            const uint32_t ts = s.top_stride[r];
+            const uint64_t nf = s.n_fences[r], end = (uint64_t)lo * ts;
+            hi = (uint32_t)(end < nf ? end : nf);
+            lo = (lo - 1) * ts + 1;  // fence (lo-1)*ts is <= q
+        } else {
+            hi = 0;
+        }
+        while (__ballot(lo < hi) != 0) {
+            if (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                const uint8_t* fp = fences + (uint64_t)mid * LSM_KEY_BYTES;
+                const int c = compare_key(q, *reinterpret_cast<const uint4*>(fp), [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
+                if (c < 0) hi = mid;
+                else lo = mid + 1;
+            }
+        }
+        // (3) the page of the last fence <= q: first entry whose key is >= q
+        const lsm_entry_t* page = s.entries[r];
+        uint32_t page_len = 0;
+        if (lo > 0) {  // lo = fences <= q
+            const uint32_t stride = s.stride[r];
+            const uint64_t start = (uint64_t)(lo - 1) * stride, left = s.n[r] - start;
+            page += start;
+            page_len = (uint32_t)(left < stride ? left : stride);
+        }
+        lo = 0;
+        hi = page_len;
+        while (__ballot(lo < hi) != 0) {
+            if (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                const uint4* ep = reinterpret_cast<const uint4*>(page + mid);
+                const int c = compare_key(q, ep[0], [&] { return ep[1]; });
+                if (c > 0) lo = mid + 1;
+                else hi = mid;
+            }
+        }
+        // (4) is it there?
+        if (lo < page_len) {
+            const uint4* e = reinterpret_cast<const uint4*>(page + lo);
+            if (compare_key(q, e[0], [&] { return e[1]; }) == 0) {
+                found = true;
+                const uint4 meta = e[2], val = e[3];  // seqno | type + pad, vptr | vlen + pad
+                if ((meta.z & 0xFF) == LSM_PUT) {
+                    live = true;
+                    h = make_uint4(val.x, val.y, val.z, r);
+                }
+            }
+        }
+    }
+    return live;
+}
+
+__global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
+                                                               uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len,
+                                                               lsm_hit_t* hits) {
+    __shared__ ProbeShared s;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const uint32_t n_runs = tree.n_runs;
+    probe_setup(s, tree, tid);
     const uint64_t run_mask = n_runs >= 64 ? ~0ull : (1ull << n_runs) - 1;
     bool any_bloom = false;
     for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
@@ -111,101 +214,10 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
             const uint32_t j = c0 + lane;
             uint4 h = make_uint4(0, 0, 0, 0);
             if (!done && c0 < nb) {
-                const bool mine = j < nb;
-                bool live = !mine;  // lanes past the request's length do not end the prefix
-                bool found = !mine;
+                const bool mine = j < nb;  // lanes past the request's length do not end the prefix
                 Key q = {{0, 0, 0, 0}};
                 if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
-                // (0) Bloom filters of the runs that have one: one 16-byte read per run, all runs of a group of
-                //     eight requested together, decides which runs this key is searched in
-                uint64_t maybe = ~0ull;
-                if (mine && any_bloom) {
-                    uint4 mask;
-                    const uint64_t bh = bloom_hash(q, mask);
-                    for (uint32_t rb = 0; rb < n_runs; rb += 8) {
-                        uint4 w[8];
-#pragma unroll
-                        for (int g = 0; g < 8; g++) {
-                            const uint32_t r = rb + g;
-                            const uint32_t blocks = r < n_runs ? tree.run[r].bloom_blocks : 0;
-                            w[g] = make_uint4(~0u, ~0u, ~0u, ~0u);
-                            if (blocks) w[g] = tree.run[r].bloom[bloom_block(bh, blocks)];
-                        }
-#pragma unroll
-                        for (int g = 0; g < 8; g++)
-                            if (bloom_excludes(w[g], mask)) maybe &= ~(1ull << (rb + g));
-                    }
-                }
-                maybe &= run_mask;
-                // every lane walks its own list of admitted runs, newest first, so lanes that need different
-                // runs search them at the same time; the walk of a lane ends at the first run that holds its key
-                while (__ballot(!found && maybe != 0) != 0) {
-                    const bool act = !found && maybe != 0;
-                    const uint32_t r = act ? (uint32_t)__builtin_ctzll(maybe) : 0;
-                    maybe &= maybe - 1;  // 0 stays 0
-                    // (1) top-level fences in LDS: number of top keys <= q
-                    uint32_t lo = 0, hi = act ? s.n_top[r] : 0;
-                    const uint32_t first_slot = s.first_slot[r];
-                    while (__ballot(lo < hi) != 0) {
-                        if (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1, slot = first_slot + mid;
-                            const int c = compare_key(q, s.top_lo[slot], [&] { return s.top_hi[slot]; });
-                            if (c < 0) hi = mid;
-                            else lo = mid + 1;
-                        }
-                    }
-                    // (2) the fences between two top keys, in global memory: number of fences <= q
-                    const uint8_t* fences = s.fences[r];
-                    if (lo > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the lane is idle)
-                        const uint32_t ts = s.top_stride[r];
-                        const uint64_t nf = s.n_fences[r], end = (uint64_t)lo * ts;
-                        hi = (uint32_t)(end < nf ? end : nf);
-                        lo = (lo - 1) * ts + 1;  // fence (lo-1)*ts is <= q
-                    } else {
-                        hi = 0;
-                    }
-                    while (__ballot(lo < hi) != 0) {
-                        if (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1;
-                            const uint8_t* fp = fences + (uint64_t)mid * LSM_KEY_BYTES;
-                            const int c = compare_key(q, *reinterpret_cast<const uint4*>(fp), [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
-                            if (c < 0) hi = mid;
-                            else lo = mid + 1;
-                        }
-                    }
-                    // (3) the page of the last fence <= q: first entry whose key is >= q
-                    const lsm_entry_t* page = s.entries[r];
-                    uint32_t page_len = 0;
-                    if (lo > 0) {  // lo = fences <= q
-                        const uint32_t stride = s.stride[r];
-                        const uint64_t start = (uint64_t)(lo - 1) * stride, left = s.n[r] - start;
-                        page += start;
-                        page_len = (uint32_t)(left < stride ? left : stride);
-                    }
-                    lo = 0;
-                    hi = page_len;
-                    while (__ballot(lo < hi) != 0) {
-                        if (lo < hi) {
-                            const uint32_t mid = (lo + hi) >> 1;
-                            const uint4* ep = reinterpret_cast<const uint4*>(page + mid);
-                            const int c = compare_key(q, ep[0], [&] { return ep[1]; });
-                            if (c > 0) lo = mid + 1;
-                            else hi = mid;
-                        }
-                    }
-                    // (4) is it there?
-                    if (lo < page_len) {
-                        const uint4* e = reinterpret_cast<const uint4*>(page + lo);
-                        if (compare_key(q, e[0], [&] { return e[1]; }) == 0) {
-                            found = true;
-                            const uint4 meta = e[2], val = e[3];  // seqno | type + pad, vptr | vlen + pad
-                            if ((meta.z & 0xFF) == LSM_PUT) {
-                                live = true;
-                                h = make_uint4(val.x, val.y, val.z, r);
-                            }
-                        }
-                    }
-                }
+                const bool live = probe_lookup(s, tree, n_runs, run_mask, any_bloom, mine, q, h);
                 const uint64_t dead = __ballot(!live);
                 if (dead) {
                     const uint32_t first = (uint32_t)__ffsll((unsigned long long)dead) - 1;
@@ -220,19 +232,58 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
     }
 }
 
+// The length of the longest cached prefix by a search over the prefix length (appendix B, "Probe") instead of a
+// lookup of every block key: valid when the tree is prefix-closed (block j of a request live => blocks 0..j-1
+// live).  One wave per request, two rounds: 64 evenly spaced blocks, then the blocks between the last live and the
+// first dead one of those.
+__global__ void __launch_bounds__(kProbeThreads) probe_length_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
+                                                                      uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len) {
+    __shared__ ProbeShared s;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const uint32_t n_runs = tree.n_runs;
+    probe_setup(s, tree, tid);
+    const uint64_t run_mask = n_runs >= 64 ? ~0ull : (1ull << n_runs) - 1;
+    bool any_bloom = false;
+    for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
+    const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
+    for (uint32_t req = blockIdx.x * (kProbeThreads / kWave) + tid / kWave; req < n_req; req += waves) {
+        uint32_t nb = n_blocks[req];
+        if (nb > max_blocks) nb = max_blocks;
+        const uint8_t* qrow = qkeys + (uint64_t)req * max_blocks * LSM_KEY_BYTES;
+        uint32_t lo = 0, hi = nb;  // blocks below lo are live, block hi is not (or hi == nb)
+        while (lo < hi) {
+            // lane l asks for block lo + (l + 1) * step - 1, the last lane that has one for block hi - 1
+            const uint32_t span = hi - lo, step = (span + kWave - 1) / kWave, lanes = (span + step - 1) / step;
+            const bool mine = (uint32_t)lane < lanes;
+            uint32_t j = lo + ((uint32_t)lane + 1) * step - 1;
+            if (j > hi - 1) j = hi - 1;
+            Key q = {{0, 0, 0, 0}};
+            if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
+            uint4 h;
+            const bool live = probe_lookup(s, tree, n_runs, run_mask, any_bloom, mine, q, h);
+            const uint64_t dead = __ballot(!live);
+            if (dead == 0) {
+                lo = hi;  // block hi - 1 is live: so is everything below it
+            } else {
+                const uint32_t first = (uint32_t)__ffsll((unsigned long long)dead) - 1;  // first lane whose block is not live
+                uint32_t dead_at = lo + (first + 1) * step - 1;
+                if (dead_at > hi - 1) dead_at = hi - 1;
+                hi = dead_at;
+                lo = lo + first * step;  // the block of lane first - 1 (or everything below lo) is live
+            }
+        }
+        if (lane == 0) hit_len[req] = lo;
+    }
+}
+
 }  // namespace lsm
 
-extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, const lsm_hits_t* out_hits, void* stream) {
+// Checks a tree descriptor and copies it into the by-value table the kernels take.
+static int make_tree_table(const lsm_tree_t* tree, lsm::TreeTable& tt) {
     using namespace lsm;
-    if (queries == nullptr || tree == nullptr || out_hits == nullptr) return LSM_ERR_NULL;
-    if (queries->max_blocks == 0 || queries->max_blocks > LSM_MAX_BLOCKS || tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
-    if (queries->n_req == 0) return LSM_OK;
-    if (queries->keys == nullptr || queries->n_blocks == nullptr || out_hits->hit_len == nullptr || out_hits->hits == nullptr)
-        return LSM_ERR_NULL;
+    if (tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
     if (tree->n_runs > 0 && tree->runs == nullptr) return LSM_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(queries->keys) & 15) != 0 || (reinterpret_cast<uintptr_t>(out_hits->hits) & 15) != 0)
-        return LSM_ERR_BAD_ARG;
-    TreeTable tt;
     tt.n_runs = 0;
     for (uint32_t r = 0; r < tree->n_runs; r++) {
         const lsm_tree_run_t& tr = tree->runs[r];
@@ -260,14 +311,53 @@ extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, c
     }
     tt.n_runs = tree->n_runs;
     for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, 0, 1, 0, nullptr};
+    return LSM_OK;
+}
+
+// Workgroups for n_req requests (one wave each): at most four per compute unit, each striding over the requests.
+static int probe_grid(uint32_t n_req, uint32_t& blocks) {
     int device = 0, cus = 0;
     if (hipGetDevice(&device) != hipSuccess ||
         hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || cus <= 0)
         return LSM_ERR_HIP;
-    const uint32_t per_block = kProbeThreads / kWave;
-    uint32_t blocks = (queries->n_req + per_block - 1) / per_block;
+    const uint32_t per_block = lsm::kProbeThreads / lsm::kWave;
+    blocks = (n_req + per_block - 1) / per_block;
     if (blocks > (uint32_t)cus * 4) blocks = (uint32_t)cus * 4;
+    return LSM_OK;
+}
+
+extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, const lsm_hits_t* out_hits, void* stream) {
+    using namespace lsm;
+    if (queries == nullptr || tree == nullptr || out_hits == nullptr) return LSM_ERR_NULL;
+    if (queries->max_blocks == 0 || queries->max_blocks > LSM_MAX_BLOCKS || tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    if (queries->n_req == 0) return LSM_OK;
+    if (queries->keys == nullptr || queries->n_blocks == nullptr || out_hits->hit_len == nullptr || out_hits->hits == nullptr)
+        return LSM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(queries->keys) & 15) != 0 || (reinterpret_cast<uintptr_t>(out_hits->hits) & 15) != 0)
+        return LSM_ERR_BAD_ARG;
+    TreeTable tt;
+    uint32_t blocks = 0;
+    int rc = make_tree_table(tree, tt);
+    if (rc == LSM_OK) rc = probe_grid(queries->n_req, blocks);
+    if (rc != LSM_OK) return rc;
     hipLaunchKernelGGL(probe_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
                        queries->n_blocks, queries->n_req, queries->max_blocks, out_hits->hit_len, out_hits->hits);
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+}
+
+extern "C" int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* tree, uint32_t* hit_len, void* stream) {
+    using namespace lsm;
+    if (queries == nullptr || tree == nullptr) return LSM_ERR_NULL;
+    if (queries->max_blocks == 0 || queries->max_blocks > LSM_MAX_BLOCKS || tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    if (queries->n_req == 0) return LSM_OK;
+    if (queries->keys == nullptr || queries->n_blocks == nullptr || hit_len == nullptr) return LSM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(queries->keys) & 15) != 0) return LSM_ERR_BAD_ARG;
+    TreeTable tt;
+    uint32_t blocks = 0;
+    int rc = make_tree_table(tree, tt);
+    if (rc == LSM_OK) rc = probe_grid(queries->n_req, blocks);
+    if (rc != LSM_OK) return rc;
+    hipLaunchKernelGGL(probe_length_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
+                       queries->n_blocks, queries->n_req, queries->max_blocks, hit_len);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

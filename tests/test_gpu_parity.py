@@ -360,3 +360,52 @@ def test_fence_index_written_by_the_compaction(g, oracle, cfg1, stride):
         n_f = (n + stride - 1) // stride
         assert np.array_equal(as_bytes(fences[:n_f]).reshape(-1, 32), want)
         assert bool((fences[n_f:] == -1).all())  # nothing written past the end
+
+
+# ------------------------------------------------------------------ prefix length by search (appendix B)
+def test_probe_length_equals_probe_on_prefix_closed_data(g, oracle, cfg1):
+    """The generator evicts leaf first, so its trees are prefix-closed: the search over the prefix length gives the
+    checker's first-miss length, with and without Bloom filters, on several runs and on the compacted run."""
+    from workloads import lsm
+    print("probe length", flush=True)
+    q, nb = lsm.queries_config1(cfg1, 4096)
+    want = oracle.probe(q, nb, [r.cpu() for r in cfg1.runs])[0]
+    tree = build_tree(g, cfg1.runs)
+    got = g.lsm_probe_length(q, nb, tree)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy().astype(np.uint32), want)
+    filtered = [g.TreeRun(t.run, t.fences, t.stride, t.level, g.lsm_build_bloom(t.run, 16)) for t in tree]
+    assert np.array_equal(g.lsm_probe_length(q, nb, filtered).cpu().numpy().astype(np.uint32), want)
+    merged = compact_gpu(g, cfg1.runs, 1).contiguous()
+    assert np.array_equal(g.lsm_probe_length(q, nb, build_tree(g, [merged])).cpu().numpy().astype(np.uint32), want)
+    # long and short rows, rows of length 0
+    nb2 = nb.clone()
+    nb2[::7] = 0
+    nb2[1::7] = 1
+    want2 = oracle.probe(q, nb2, [r.cpu() for r in cfg1.runs])[0]
+    assert np.array_equal(g.lsm_probe_length(q, nb2, tree).cpu().numpy().astype(np.uint32), want2)
+
+
+def test_probe_length_on_data_with_holes(g, oracle):
+    """Without prefix closure the result is still a boundary: block j-1 live (or j = 0), block j not (or j = n)."""
+    print("probe length with holes", flush=True)
+    rs = np.random.RandomState(12)
+    keys = sorted({bytes(rs.randint(0, 256, size=32).astype(np.uint8)) for _ in range(300)})
+    present = [k for i, k in enumerate(keys) if rs.rand() < 0.7]
+    run = brute.run_from_raw([brute.pack_entry(k, i + 1, TOMBSTONE if rs.rand() < 0.1 else PUT, 1000 + i, 5) for i, k in enumerate(present)])
+    live = {brute.unpack(r)[0] for r in brute.raws_of(run) if brute.unpack(r)[2] == PUT}
+    n_req, max_blocks = 64, 200
+    q = np.zeros((n_req, max_blocks, 32), dtype=np.uint8)
+    rows = []
+    for r in range(n_req):
+        row = [keys[i] for i in rs.choice(len(keys), size=max_blocks, replace=False)]
+        rows.append(row)
+        q[r] = np.frombuffer(b"".join(row), dtype=np.uint8).reshape(max_blocks, 32)
+    nb = rs.randint(0, max_blocks + 1, size=n_req).astype(np.int32)
+    qd = torch.from_numpy(q.view(np.int64).reshape(n_req, max_blocks, 4)).to(dev())
+    got = g.lsm_probe_length(qd, torch.from_numpy(nb).to(dev()), build_tree(g, [to_dev(run)])).cpu().numpy()
+    for r in range(n_req):
+        j = int(got[r])
+        assert 0 <= j <= nb[r]
+        assert j == 0 or rows[r][j - 1] in live
+        assert j == nb[r] or rows[r][j] not in live
