@@ -146,13 +146,23 @@ __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTab
         } else {
             hi = 0;
         }
+        // four-way steps: three fence keys are requested together, half as many dependent round trips
         while (__ballot(lo < hi) != 0) {
             if (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                const uint8_t* fp = fences + (uint64_t)mid * LSM_KEY_BYTES;
-                const int c = compare_key(q, *reinterpret_cast<const uint4*>(fp), [&] { return *reinterpret_cast<const uint4*>(fp + 16); });
-                if (c < 0) hi = mid;
-                else lo = mid + 1;
+                const uint32_t w = hi - lo;
+                const uint32_t m1 = lo + (w >> 2), m2 = lo + (w >> 1), m3 = lo + ((3 * w) >> 2);  // lo <= m1 <= m2 <= m3 < hi
+                const uint8_t *f1 = fences + (uint64_t)m1 * LSM_KEY_BYTES, *f2 = fences + (uint64_t)m2 * LSM_KEY_BYTES,
+                              *f3 = fences + (uint64_t)m3 * LSM_KEY_BYTES;
+                const uint4 a1 = *reinterpret_cast<const uint4*>(f1), a2 = *reinterpret_cast<const uint4*>(f2),
+                            a3 = *reinterpret_cast<const uint4*>(f3);
+                const int c1 = compare_key(q, a1, [&] { return *reinterpret_cast<const uint4*>(f1 + 16); });
+                const int c2 = compare_key(q, a2, [&] { return *reinterpret_cast<const uint4*>(f2 + 16); });
+                const int c3 = compare_key(q, a3, [&] { return *reinterpret_cast<const uint4*>(f3 + 16); });
+                // number of fences <= q: a fence m with q < fence[m] bounds it from above
+                if (c3 >= 0) lo = m3 + 1;
+                else if (c2 >= 0) lo = m2 + 1, hi = m3;
+                else if (c1 >= 0) lo = m1 + 1, hi = m2;
+                else hi = m1;
             }
         }
         // (3) the page of the last fence <= q: first entry whose key is >= q
@@ -168,11 +178,19 @@ __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTab
         hi = page_len;
         while (__ballot(lo < hi) != 0) {
             if (lo < hi) {
-                const uint32_t mid = (lo + hi) >> 1;
-                const uint4* ep = reinterpret_cast<const uint4*>(page + mid);
-                const int c = compare_key(q, ep[0], [&] { return ep[1]; });
-                if (c > 0) lo = mid + 1;
-                else hi = mid;
+                const uint32_t w = hi - lo;
+                const uint32_t m1 = lo + (w >> 2), m2 = lo + (w >> 1), m3 = lo + ((3 * w) >> 2);
+                const uint4 *e1 = reinterpret_cast<const uint4*>(page + m1), *e2 = reinterpret_cast<const uint4*>(page + m2),
+                            *e3 = reinterpret_cast<const uint4*>(page + m3);
+                const uint4 a1 = e1[0], a2 = e2[0], a3 = e3[0];
+                const int c1 = compare_key(q, a1, [&] { return e1[1]; });
+                const int c2 = compare_key(q, a2, [&] { return e2[1]; });
+                const int c3 = compare_key(q, a3, [&] { return e3[1]; });
+                // first entry whose key is >= q
+                if (c3 > 0) lo = m3 + 1;
+                else if (c2 > 0) lo = m2 + 1, hi = m3;
+                else if (c1 > 0) lo = m1 + 1, hi = m2;
+                else hi = m1;
             }
         }
         // (4) is it there?
