@@ -64,11 +64,19 @@ def test_config4_full_tree_sampled_probe_batches(g, oracle):
         got_f = as_bytes(f.fences).reshape(-1, 32)
         idx = np.unique(np.linspace(0, got_f.shape[0] - 1, 4096).astype(np.int64))
         assert np.array_equal(got_f[idx], r[idx * 64, :32])
+    # Bloom filters of every level: the largest one in full, and the probe must not change with them
+    filtered = [g.TreeRun(t.run, t.fences, t.stride, t.level, g.lsm_build_bloom(t.run, 16)) for t in tree]
+    torch.cuda.synchronize()
+    for t, r in zip(filtered, runs_cpu):
+        assert np.array_equal(as_bytes(t.bloom).reshape(-1, 16), oracle.build_bloom(r, int(t.bloom.shape[0])))
     for stream in (0, 101, 255):
         print("  batch", stream, flush=True)
         q, nb = lsm.queries_config4(w, 4096, stream=stream)
         got = probe_gpu(g, q, nb, tree)
         want = oracle.probe(q, nb, runs_cpu)
         assert_probe_equal(oracle, got, want)
+        assert_probe_equal(oracle, probe_gpu(g, q, nb, filtered), want)
+        for t in (tree, filtered):  # the generator's data is prefix-closed: the search over the length agrees
+            assert np.array_equal(g.lsm_probe_length(q, nb, t).cpu().numpy().astype(np.uint32), want[0])
         miss = float((want[0] == 0).mean())
         assert 0.25 < miss < 0.45 and want[0].max() >= 32
