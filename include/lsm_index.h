@@ -9,6 +9,7 @@
  *
  *   lsm_compact       merge sorted runs into one run (section 2.2, compaction); lsm_compact_remap also rewrites
  *                     value pointers for merged tensor files (section 3.4)
+ *   lsm_flush_buffer  the write buffer as a sorted run (section 2.2)
  *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
  *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes)
  *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
@@ -72,6 +73,7 @@ typedef enum {
 enum {
     LSM_MAX_RUNS = 64,          /* runs per lsm_compact call and per lsm_tree_t            */
     LSM_MAX_BLOCKS = 256,       /* block keys per probe request                            */
+    LSM_MAX_BUFFER = 65536,     /* entries per lsm_flush_buffer call                       */
     LSM_KEY_BYTES = 32,
     LSM_DEFAULT_FENCE_STRIDE = 64 /* one fence per 4 KiB page of entries                   */
 };
@@ -211,6 +213,20 @@ int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, co
 /* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments.
  * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per 1984 entries. */
 size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
+
+/*
+ * lsm_flush_buffer -- the write buffer as a sorted run (section 2.2: writes go to an in-memory buffer that is
+ * flushed as a sorted run when it is full).  buffer: DEVICE, 64-byte aligned, n <= LSM_MAX_BUFFER entries in the
+ * order they were written, possibly several versions of a key.  Result: ascending by key, one entry per key -
+ * the one with the largest seqno, and among equal seqnos the one written last; tombstones are entries like any
+ * other.  out as for lsm_compact (capacity >= n; fence_keys optional).  workspace: DEVICE scratch of at least
+ * lsm_flush_workspace_bytes(n) = 4 * n bytes, 4-byte aligned.  Every entry is compared with every other (n^2 key
+ * compares from LDS, twice): meant for write buffers of a few thousand entries.
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (n > LSM_MAX_BUFFER, misaligned), LSM_ERR_CAPACITY, LSM_ERR_WORKSPACE, LSM_ERR_HIP.
+ */
+size_t lsm_flush_workspace_bytes(uint64_t n);
+int lsm_flush_buffer(const lsm_entry_t* buffer, uint64_t n, const lsm_out_t* out, void* workspace, size_t workspace_bytes,
+                     void* stream);
 
 /*
  * lsm_build_fences -- fence_keys_out[i] = run->entries[i*stride].key for 0 <= i < ceil(n/stride)

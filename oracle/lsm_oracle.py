@@ -124,6 +124,21 @@ def build_fences(run, stride: int) -> np.ndarray:
     return out
 
 
+def flush_buffer(buffer) -> np.ndarray:
+    """The write buffer as a sorted run (section 2.2): ascending by key, of several versions of a key the one with
+    the largest seqno, among equal seqnos the one written last (= later in the buffer)."""
+    buf = as_run(buffer)
+    rec = buf.view(ENTRY_DTYPE).reshape(-1)
+    order = sorted(range(buf.shape[0]), key=lambda i: (bytes(rec["key"][i]), -int(rec["seqno"][i]), -i))
+    keep, last = [], None
+    for i in order:
+        k = bytes(rec["key"][i])
+        if k != last:
+            keep.append(i)
+            last = k
+    return buf[keep] if keep else buf[:0]
+
+
 def remap_pointers(run, base) -> np.ndarray:
     """Pointer rewrite for merged tensor files (section 3.4): a value pointer is (file_id << 32) | offset;
     every PUT whose file_id is inside the table gets base[file_id] + offset, everything else stays."""

@@ -102,6 +102,10 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_compact_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), C.c_uint32]
     L.lsm_build_fences.restype = C.c_int
     L.lsm_build_fences.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_void_p, C.c_void_p]
+    L.lsm_flush_workspace_bytes.restype = C.c_size_t
+    L.lsm_flush_workspace_bytes.argtypes = [C.c_uint64]
+    L.lsm_flush_buffer.restype = C.c_int
+    L.lsm_flush_buffer.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(_Out), C.c_void_p, C.c_size_t, C.c_void_p]
     L.lsm_bloom_blocks.restype = C.c_uint64
     L.lsm_bloom_blocks.argtypes = [C.c_uint64, C.c_uint32]
     L.lsm_build_bloom.restype = C.c_int
@@ -183,6 +187,24 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
         rc = L.lsm_compact_timed(rd, len(runs), flags, C.byref(od), ws_ptr, ws_bytes, _stream_ptr(stream), C.byref(ev))
     if rc != 0:
         raise LsmError(rc, "lsm_compact")
+    return out, n_out
+
+
+def lsm_flush_buffer(buffer: torch.Tensor, out: Optional[torch.Tensor] = None, n_out: Optional[torch.Tensor] = None,
+                     fences: Optional[torch.Tensor] = None, fence_stride: int = 64, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """The write buffer (int64 [n, 8], entries in the order written) as a sorted run; returns (out, n_out) like lsm_compact."""
+    L = _load()
+    n = int(_dev(buffer, "buffer").shape[0])
+    if out is None:
+        out = torch.empty((max(n, 1), 8), dtype=torch.int64, device=buffer.device)
+    if n_out is None:
+        n_out = torch.empty(1, dtype=torch.int64, device=buffer.device)
+    ws = torch.empty(max(int(L.lsm_flush_workspace_bytes(n)), 4), dtype=torch.uint8, device=buffer.device)
+    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
+              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0)
+    rc = L.lsm_flush_buffer(buffer.data_ptr(), n, C.byref(od), ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_flush_buffer")
     return out, n_out
 
 

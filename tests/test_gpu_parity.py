@@ -409,3 +409,31 @@ def test_probe_length_on_data_with_holes(g, oracle):
         assert 0 <= j <= nb[r]
         assert j == 0 or rows[r][j - 1] in live
         assert j == nb[r] or rows[r][j] not in live
+
+
+# ------------------------------------------------------------------ write-buffer flush (section 2.2)
+@pytest.mark.parametrize("n,n_keys", [(0, 10), (1, 10), (255, 40), (256, 4000), (3600, 3000), (3600, 50), (10000, 100000)])
+def test_flush_of_the_write_buffer(g, oracle, n, n_keys):
+    """Unsorted entries with repeated keys and repeated seqnos -> the checker's sorted run, with its fence index."""
+    print("flush", n, n_keys, flush=True)
+    rs = np.random.RandomState(n + n_keys)
+    alphabet = rs.randint(0, 256, size=(n_keys, 32)).astype(np.uint8)
+    a = np.zeros((n, 64), dtype=np.uint8)
+    if n:
+        a[:, :32] = alphabet[rs.randint(0, n_keys, size=n)]
+        rec = a.view(oracle.ENTRY_DTYPE).reshape(-1)
+        rec["seqno"] = rs.randint(0, 6, size=n) if n_keys <= 50 else rs.randint(0, 1 << 40, size=n)
+        rec["type"] = (rs.rand(n) < 0.2).astype(np.uint8)
+        rec["vptr"] = np.arange(n)
+        rec["vlen"] = 655360
+    buf = to_dev(a)
+    fences = torch.full(((n + 63) // 64 + 1, 4), -1, dtype=torch.int64, device=dev())
+    out, n_out = g.lsm_flush_buffer(buf, fences=fences, fence_stride=64)
+    torch.cuda.synchronize()
+    want = oracle.flush_buffer(a)
+    m = int(n_out.item())
+    assert m == want.shape[0]
+    assert np.array_equal(as_bytes(out[:m]).reshape(-1, 64), want)
+    assert np.array_equal(as_bytes(fences[: (m + 63) // 64]).reshape(-1, 32), oracle.build_fences(want, 64))
+    if m:  # a flushed buffer is a run like any other: it compacts and probes
+        assert np.array_equal(as_bytes(compact_gpu(g, [out[:m].contiguous()], 0)).reshape(-1, 64), want)

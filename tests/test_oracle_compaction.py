@@ -274,3 +274,19 @@ def test_pointer_rewrite_against_plain_arithmetic(oracle):
         assert vptr2 == ((100 << 32) + starts[f] + off if typ == brute.PUT and f < n_files else vptr)
     assert np.array_equal(oracle.remap_pointers(run, [f << 32 for f in range(12)]), run)
     assert np.array_equal(oracle.remap_pointers(run, []), run)
+
+
+# ------------------------------------------------------------------ write-buffer flush (section 2.2)
+def test_flush_buffer_equals_merging_one_entry_runs(oracle):
+    """Flushing a buffer = compacting its entries as one-entry runs, the last written first (so that equal seqnos go
+    to the later write): checked against the sort-and-deduplicate reference on raw bytes."""
+    rs = np.random.RandomState(21)
+    alphabet = [bytes(rs.randint(0, 256, size=32).astype(np.uint8)) for _ in range(60)]
+    for n in (0, 1, 2, 257, 700):
+        raws = [brute.pack_entry(alphabet[int(rs.randint(len(alphabet)))], int(rs.randint(0, 5)) if i % 3 else int(rs.randint(0, 1 << 40)),
+                                 TOMBSTONE if rs.rand() < 0.3 else PUT, i, i % 7) for i in range(n)]
+        want = brute.compact([[r] for r in reversed(raws)], False)
+        got = oracle.flush_buffer(brute.run_from_raw(raws))
+        assert brute.raws_of(got) == want
+        keys = [r[:32] for r in brute.raws_of(got)]
+        assert keys == sorted(set(r[:32] for r in raws))
