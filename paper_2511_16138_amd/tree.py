@@ -65,6 +65,10 @@ class GpuBackend:
             return fused[2]
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
+    def flush_buffer(self, buffer: Any) -> Any:
+        out, n_out = self._b.lsm_flush_buffer(buffer.contiguous())
+        return out[: int(n_out.item())]
+
     def build_bloom(self, run: Any) -> Any:
         return self._b.lsm_build_bloom(run.contiguous(), self.bloom_bits) if self.bloom_bits else None
 
@@ -121,6 +125,10 @@ class AdaptiveLsmTree:
     def flush(self, run: Any) -> None:
         """A sorted run from the write buffer enters level 1."""
         self._arrive(0, self._index(run))
+
+    def flush_unsorted(self, buffer: Any) -> None:
+        """The write buffer as it was filled (any order, repeated keys): sorted and deduplicated by the backend first."""
+        self.flush(self.backend.flush_buffer(buffer))
 
     def _arrive(self, level: int, newcomer: LevelRun) -> None:
         while len(self.levels) <= level:
@@ -186,14 +194,17 @@ class AdaptiveLsmTree:
         self.size_ratio, self.runs_per_level = T, K
 
 
-def run_mixed_trace(tree: AdaptiveLsmTree, trace, on_probe=None, on_compaction=None) -> None:
+def run_mixed_trace(tree: AdaptiveLsmTree, trace, on_probe=None, on_compaction=None, shuffle_writes=None) -> None:
     """Replay a workloads.lsm.MixedTrace: flushes and probe batches in time order."""
     for (kind, i, _phase), n_writes in zip(trace.events, trace.write_ops_between):
         if n_writes:
             tree.note_writes(n_writes)
         if kind == "flush":
             before = len(tree.trace)
-            tree.flush(trace.flush_runs[i])
+            if shuffle_writes is not None:  # hand the buffer over in the order the generator "wrote" it, not sorted
+                tree.flush_unsorted(trace.flush_runs[i][shuffle_writes(i, int(trace.flush_runs[i].shape[0]))])
+            else:
+                tree.flush(trace.flush_runs[i])
             if on_compaction is not None:
                 for ev in tree.trace[before:]:
                     on_compaction(ev)

@@ -31,18 +31,19 @@ class OracleBackend:
         return self.o.policy_choose(*a)
 
 
-def _replay(backend, trace, runs, keep_probes):
+def _replay(backend, trace, runs, keep_probes, shuffle_writes=None):
     from paper_2511_16138_amd.tree import AdaptiveLsmTree, run_mixed_trace
     tree = AdaptiveLsmTree(backend, trace.buffer_entries, size_ratio=trace.size_ratio, window_ops=4 * trace.batch_requests)
     for level, r in enumerate(runs):
         tree.load_level(level, [r])
-    run_mixed_trace(tree, trace, on_probe=lambda i, q, nb, out: keep_probes.append(out))
+    run_mixed_trace(tree, trace, on_probe=lambda i, q, nb, out: keep_probes.append(out), shuffle_writes=shuffle_writes)
     return tree
 
 
 @pytest.mark.parametrize("tree_total,buffer_entries,ops,shares,bloom_bits", [(400_000, 360, 4096, (0.9, 0.5, 0.1), 0),
                                                                              (2_000_000, 900, 8192, (0.9, 0.5, 0.02), 0),
-                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), 16)])
+                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), 16),
+                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), -1)])
 def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops, shares, bloom_bits):
     from paper_2511_16138_amd.tree import GpuBackend
     from workloads import lsm
@@ -51,7 +52,11 @@ def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops,
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
 
     gpu_probes, cpu_probes = [], []
-    gpu_tree = _replay(GpuBackend(bloom_bits=bloom_bits), tr, tr.workload.runs, gpu_probes)  # the checker has no filters
+    shuffle = None
+    if bloom_bits < 0:  # the GPU side gets every write buffer in a random order and sorts it itself (lsm_flush_buffer)
+        bloom_bits = 0
+        shuffle = lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())
+    gpu_tree = _replay(GpuBackend(bloom_bits=bloom_bits), tr, tr.workload.runs, gpu_probes, shuffle)  # the checker has no filters
     torch.cuda.synchronize()
 
     cpu_trace = lsm.MixedTrace(tr.workload, tr.buffer_entries, tr.size_ratio, tr.flush_runs.cpu(), tr.events, tr.batch_requests,
