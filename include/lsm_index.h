@@ -273,6 +273,17 @@ int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, const lsm_hi
 int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* tree, uint32_t* hit_len, void* stream);
 
 /*
+ * lsm_range_bounds -- where a key range starts and ends in every run of a tree: the first step of a range lookup
+ * (section 2.2 "Range Lookups"; appendix B: get_batch "performs range scans to retrieve keys and tensor
+ * locations").  lo_key, hi_key: HOST, 32 bytes each.  bounds_out: DEVICE, 2 * n_runs uint64:
+ *   bounds_out[2r] = number of entries of run r with key < lo_key, bounds_out[2r+1] = number with key < hi_key.
+ * The range's content is then one lsm_compact with LSM_BOTTOMMOST over the slices
+ * runs[r].entries[bounds[2r] .. bounds[2r+1]) (newest version of every key in [lo_key, hi_key), live PUTs only).
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG, LSM_ERR_HIP.
+ */
+int lsm_range_bounds(const lsm_tree_t* tree, const uint8_t* lo_key, const uint8_t* hi_key, uint64_t* bounds_out, void* stream);
+
+/*
  * Cost model of the adaptive controller (host only, double arithmetic).
  *   L = smallest integer >= 1 with buffer_entries * T^L >= n_entries     (section 2.2: L = log_T(N e / M))
  *   W = T L / (B K)   update;  Z = K L p  empty point lookup;  R = K L p + 1  non-empty point

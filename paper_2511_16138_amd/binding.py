@@ -114,6 +114,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
     L.lsm_probe_length.restype = C.c_int
     L.lsm_probe_length.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.c_void_p, C.c_void_p]
+    L.lsm_range_bounds.restype = C.c_int
+    L.lsm_range_bounds.argtypes = [C.POINTER(_Tree), C.c_char_p, C.c_char_p, C.c_void_p, C.c_void_p]
     L.lsm_policy_levels.restype = C.c_uint32
     L.lsm_policy_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
     L.lsm_policy_cost.restype = C.c_double
@@ -274,6 +276,28 @@ def lsm_probe_length(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence
     if rc != 0:
         raise LsmError(rc, "lsm_probe_length")
     return hit_len
+
+
+def lsm_range_bounds(tree: Sequence[TreeRun], lo_key: bytes, hi_key: bytes, stream=None) -> torch.Tensor:
+    """int64 [n_runs, 2]: entries of every run below lo_key and below hi_key."""
+    L = _load()
+    assert len(lo_key) == 32 and len(hi_key) == 32
+    out = torch.zeros((len(tree), 2), dtype=torch.int64, device=tree[0].run.device if tree else "cuda")
+    td, _keep = _tree_descriptor(tree)
+    rc = L.lsm_range_bounds(C.byref(td), lo_key, hi_key, out.data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_range_bounds")
+    return out
+
+
+def lsm_range_scan(tree: Sequence[TreeRun], lo_key: bytes, hi_key: bytes, stream=None) -> torch.Tensor:
+    """The live entries with lo_key <= key < hi_key, newest version of each, ascending: bounds, then one compaction of the slices."""
+    bounds = lsm_range_bounds(tree, lo_key, hi_key, stream).cpu().tolist()
+    slices = [t.run[a:b] for t, (a, b) in zip(tree, bounds)]
+    if not slices:
+        return torch.empty((0, 8), dtype=torch.int64)
+    out, n_out = lsm_compact(slices, LSM_BOTTOMMOST, stream=stream)
+    return out[: int(n_out.item())]
 
 
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],

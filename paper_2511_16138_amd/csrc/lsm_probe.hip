@@ -295,6 +295,15 @@ __global__ void __launch_bounds__(kProbeThreads) probe_length_kernel(TreeTable t
     }
 }
 
+// One thread per (run, bound): entries of the run below the key, by bisection over the run itself.
+__global__ void range_bounds_kernel(TreeTable tree, Key lo_key, Key hi_key, uint64_t* bounds) {
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= 2 * tree.n_runs) return;
+    const TreeRun& run = tree.run[t >> 1];
+    bool eq;
+    bounds[t] = run.n ? lower_bound_eq(run.entries, 0, run.n, (t & 1) ? hi_key : lo_key, eq) : 0;
+}
+
 }  // namespace lsm
 
 // Checks a tree descriptor and copies it into the by-value table the kernels take.
@@ -377,5 +386,25 @@ extern "C" int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* 
     if (rc != LSM_OK) return rc;
     hipLaunchKernelGGL(probe_length_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
                        queries->n_blocks, queries->n_req, queries->max_blocks, hit_len);
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+}
+
+extern "C" int lsm_range_bounds(const lsm_tree_t* tree, const uint8_t* lo_key, const uint8_t* hi_key, uint64_t* bounds_out, void* stream) {
+    using namespace lsm;
+    if (tree == nullptr || lo_key == nullptr || hi_key == nullptr) return LSM_ERR_NULL;
+    if (tree->n_runs == 0) return LSM_OK;
+    if (bounds_out == nullptr) return LSM_ERR_NULL;
+    TreeTable tt;
+    const int rc = make_tree_table(tree, tt);
+    if (rc != LSM_OK) return rc;
+    Key k[2];
+    const uint8_t* src[2] = {lo_key, hi_key};
+    for (int b = 0; b < 2; b++)
+        for (int w = 0; w < 4; w++) {
+            uint64_t v = 0;
+            for (int i = 0; i < 8; i++) v = (v << 8) | src[b][8 * w + i];  // big-endian words: numeric order = byte order
+            k[b].w[w] = v;
+        }
+    hipLaunchKernelGGL(range_bounds_kernel, dim3(1), dim3(2 * LSM_MAX_RUNS), 0, static_cast<hipStream_t>(stream), tt, k[0], k[1], bounds_out);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

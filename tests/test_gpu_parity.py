@@ -437,3 +437,26 @@ def test_flush_of_the_write_buffer(g, oracle, n, n_keys):
     assert np.array_equal(as_bytes(fences[: (m + 63) // 64]).reshape(-1, 32), oracle.build_fences(want, 64))
     if m:  # a flushed buffer is a run like any other: it compacts and probes
         assert np.array_equal(as_bytes(compact_gpu(g, [out[:m].contiguous()], 0)).reshape(-1, 64), want)
+
+
+# ------------------------------------------------------------------ range lookups (section 2.2, appendix B get_batch)
+def test_range_scan_equals_filtered_compaction(g, oracle, cfg1):
+    """Entries of a key range, newest version of each, live only = the checker's last-level compaction of all runs
+    cut to the range; one family's range, a range between two stored keys, an empty one and everything."""
+    print("range scan", flush=True)
+    tree = build_tree(g, cfg1.runs)
+    full = oracle.compact([r.cpu() for r in cfg1.runs], 1)
+    keys = [bytes(k) for k in full[:, :32]]
+    fam = keys[len(keys) // 3][:8]
+    ranges = [(fam + bytes(24), fam + b"\xff" * 24), (keys[100], keys[5000]), (keys[7], keys[7]),
+              (bytes(32), b"\xff" * 32), (keys[-1], b"\xff" * 32)]
+    for lo, hi in ranges:
+        want = full[[i for i, k in enumerate(keys) if lo <= k < hi]] if lo < hi else full[:0]
+        bounds = g.lsm_range_bounds(tree, lo, hi).cpu().numpy()
+        for (a, b), r in zip(bounds, cfg1.runs):  # every bound is the lower bound of its key in its run
+            rk = as_bytes(r).reshape(-1, 64)[:, :32]
+            for at, key in ((int(a), lo), (int(b), hi)):
+                assert (at == 0 or bytes(rk[at - 1]) < key) and (at == r.shape[0] or bytes(rk[at]) >= key)
+        got = g.lsm_range_scan(tree, lo, hi)
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(got).reshape(-1, 64), want)
