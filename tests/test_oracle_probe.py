@@ -131,6 +131,22 @@ def test_generated_requests_hit_what_was_inserted(oracle):
             seen[k] = int(seq[i])
 
 
+
+def test_generated_data_is_prefix_closed(oracle):
+    """Leaf-first eviction keeps the data prefix-closed: in every generated request the live block keys are exactly
+    the first hit_len ones (what makes the search over the prefix length of appendix B valid on these inputs)."""
+    from workloads import lsm
+    w = lsm.config1()
+    runs = [oracle.as_run(r) for r in w.runs]
+    live = {bytes(k) for k in oracle.compact(runs, 1)[:, :32]}  # newest version is a PUT
+    q, nb = lsm.queries_config1(w, 512)
+    hit_len = oracle.probe(q, nb, runs)[0]
+    qb = q.numpy().view(np.uint8).reshape(q.shape[0], q.shape[1], 32)
+    for r in range(qb.shape[0]):
+        flags = [bytes(qb[r, j]) in live for j in range(int(nb[r]))]
+        assert flags == [j < hit_len[r] for j in range(int(nb[r]))]
+
+
 # ---------------------------------------------------------------- fences
 def test_fences_are_strided_keys_and_bound_searches(oracle):
     rs = np.random.RandomState(15)
