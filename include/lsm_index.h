@@ -13,7 +13,9 @@
  *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
  *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes)
  *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
- *                     section 2.2, "Point Lookups")
+ *                     section 2.2, "Point Lookups"); lsm_probe_length gives the length alone by a
+ *                     search over the prefix length
+ *   lsm_range_bounds  where a key range lies in every run (section 2.2, "Range Lookups")
  *   lsm_policy_*      the adaptive controller's cost model (section 2.2 costs, section 3.3)
  *
  * Conventions
