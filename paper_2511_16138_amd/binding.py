@@ -290,16 +290,6 @@ def lsm_range_bounds(tree: Sequence[TreeRun], lo_key: bytes, hi_key: bytes, stre
     return out
 
 
-def lsm_range_scan(tree: Sequence[TreeRun], lo_key: bytes, hi_key: bytes, stream=None) -> torch.Tensor:
-    """The live entries with lo_key <= key < hi_key, newest version of each, ascending: bounds, then one compaction of the slices."""
-    bounds = lsm_range_bounds(tree, lo_key, hi_key, stream).cpu().tolist()
-    slices = [t.run[a:b] for t, (a, b) in zip(tree, bounds)]
-    if not slices:
-        return torch.empty((0, 8), dtype=torch.int64)
-    out, n_out = lsm_compact(slices, LSM_BOTTOMMOST, stream=stream)
-    return out[: int(n_out.item())]
-
-
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],
               hit_len: Optional[torch.Tensor] = None, hits: Optional[torch.Tensor] = None, stream=None
               ) -> Tuple[torch.Tensor, torch.Tensor]:

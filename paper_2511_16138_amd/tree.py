@@ -213,3 +213,16 @@ def run_mixed_trace(tree: AdaptiveLsmTree, trace, on_probe=None, on_compaction=N
             out = tree.probe(q, nb)
             if on_probe is not None:
                 on_probe(i, q, nb, out)
+
+
+def range_scan(tree_runs: Sequence[Any], lo_key: bytes, hi_key: bytes) -> Any:
+    """Range lookup (section 2.2 "Range Lookups"; appendix B, get_batch): the live entries with lo_key <= key < hi_key,
+    newest version of each, ascending.  Two library calls: the bounds of the range in every run, then one last-level
+    compaction of the slices.  tree_runs: binding.TreeRun objects, newest run first."""
+    from . import binding as b
+    bounds = b.lsm_range_bounds(tree_runs, lo_key, hi_key).cpu().tolist()
+    slices = [t.run[lo:hi] for t, (lo, hi) in zip(tree_runs, bounds)]
+    if not slices:
+        return None
+    out, n_out = b.lsm_compact(slices, b.LSM_BOTTOMMOST)
+    return out[: int(n_out.item())]

@@ -443,6 +443,7 @@ def test_flush_of_the_write_buffer(g, oracle, n, n_keys):
 def test_range_scan_equals_filtered_compaction(g, oracle, cfg1):
     """Entries of a key range, newest version of each, live only = the checker's last-level compaction of all runs
     cut to the range; one family's range, a range between two stored keys, an empty one and everything."""
+    from paper_2511_16138_amd.tree import range_scan
     print("range scan", flush=True)
     tree = build_tree(g, cfg1.runs)
     full = oracle.compact([r.cpu() for r in cfg1.runs], 1)
@@ -457,6 +458,6 @@ def test_range_scan_equals_filtered_compaction(g, oracle, cfg1):
             rk = as_bytes(r).reshape(-1, 64)[:, :32]
             for at, key in ((int(a), lo), (int(b), hi)):
                 assert (at == 0 or bytes(rk[at - 1]) < key) and (at == r.shape[0] or bytes(rk[at]) >= key)
-        got = g.lsm_range_scan(tree, lo, hi)
+        got = range_scan(tree, lo, hi)
         torch.cuda.synchronize()
         assert np.array_equal(as_bytes(got).reshape(-1, 64), want)
