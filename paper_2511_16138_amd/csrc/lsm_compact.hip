@@ -114,7 +114,8 @@ __device__ __forceinline__ uint64_t group_max_u64(uint64_t v, int group) {
     return v;
 }
 
-constexpr int kTailKeys = 4;  // ranges this short are finished from registers
+constexpr int kTailKeys = 4;        // ranges this short are finished from registers
+constexpr int kTailKeysCached = 2;  // the same for searches on the cached sample arrays
 
 // One step's bookkeeping once every lane has its lower bound lb (and whether the record there equals the pivot).
 __device__ __forceinline__ void select_update(uint64_t& lo, uint64_t& hi, uint64_t& best, const uint64_t lb, const bool eq,
@@ -137,11 +138,13 @@ template <bool kCached, typename E>
 __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint64_t hi, const uint64_t r, const bool own,
                                                  const int member, const int group, const int group_base) {
     uint64_t best = lo;
-    // phase 1: pivots and lower bounds from memory, until every range of the group is at most kTailKeys long
+    // on the cached sample arrays a shorter tail keeps the kernel at 64 registers (8 waves per SIMD), worth more there
+    constexpr int kTail = kCached ? kTailKeysCached : kTailKeys;
+    // phase 1: pivots and lower bounds from memory, until every range of the group is at most kTail long
     for (uint32_t iter = 0;; iter++) {
         const uint64_t width = hi - lo;
         const uint64_t widest = group_max_u64((width << 6) | (uint64_t)member, group);
-        const bool active = (widest >> 6) > (uint64_t)kTailKeys;
+        const bool active = (widest >> 6) > (uint64_t)kTail;
         if (__ballot(active) == 0) break;
         const int src = (int)(widest & 63);
         // bisection steps take the roundest position of the middle quarter when the records are in HBM
@@ -181,11 +184,11 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
         if (own && active) lb = kCached ? lower_bound_eq4(run, lo, hi, pivot, eq) : lower_bound_eq(run, lo, hi, pivot, eq);
         select_update(lo, hi, best, lb, eq, mid, member == src, active, own, r, group);
     }
-    // phase 2: the same steps on the at most kTailKeys keys per range that are left, held in registers
+    // phase 2: the same steps on the at most kTail keys per range that are left, held in registers
     const uint64_t base = lo;
-    const int cnt = (int)(hi - lo);  // <= kTailKeys
-    Key kk[kTailKeys];
-    for (int i = 0; i < kTailKeys; i++) kk[i] = i < cnt ? load_key(run + base + i) : Key{{0, 0, 0, 0}};
+    const int cnt = (int)(hi - lo);  // <= kTail
+    Key kk[kTail];
+    for (int i = 0; i < kTail; i++) kk[i] = i < cnt ? load_key(run + base + i) : Key{{0, 0, 0, 0}};
     for (;;) {
         const uint64_t width = hi - lo;
         const uint64_t widest = group_max_u64((width << 6) | (uint64_t)member, group);
@@ -195,14 +198,14 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
         const uint64_t mid = lo + (width >> 1);
         const int at = (int)(mid - base);
         Key pivot = kk[0];
-        for (int i = 1; i < kTailKeys; i++)
+        for (int i = 1; i < kTail; i++)
             if (at == i) pivot = kk[i];
         for (int w = 0; w < 4; w++) pivot.w[w] = __shfl(pivot.w[w], group_base + src, kWave);
         uint64_t lb = base;
-        for (int i = 0; i < kTailKeys; i++) lb += (i < cnt && key_less(kk[i], pivot)) ? 1 : 0;
+        for (int i = 0; i < kTail; i++) lb += (i < cnt && key_less(kk[i], pivot)) ? 1 : 0;
         lb = lb < lo ? lo : (lb > hi ? hi : lb);
         bool eq = false;
-        for (int i = 0; i < kTailKeys; i++) eq = eq || (lb < hi && lb == base + i && key_equal(kk[i], pivot));
+        for (int i = 0; i < kTail; i++) eq = eq || (lb < hi && lb == base + i && key_equal(kk[i], pivot));
         select_update(lo, hi, best, lb, eq, mid, member == src, active, own, r, group);
     }
     return best;
