@@ -32,7 +32,7 @@ constexpr int kMergeItems = 4;
 constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
 constexpr int kRoundItems = 4;                         // outputs per thread in a merge round
 constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
-constexpr uint64_t kCoarseStride = 32;                 // every 32nd boundary is searched over whole sequences first
+constexpr uint64_t kCoarseStride = 16;                 // every 16th boundary is searched over whole sequences first
 constexpr uint64_t kSampleStride = 32;                 // one key in 32 is copied for the sampled partition
 constexpr uint64_t kSampledMinTiles = 65;              // inputs of fewer tiles search the runs directly
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
