@@ -154,12 +154,14 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
         if (iter % 3 != 2) {
             // interpolation steps: the candidates are the merged ranks [sum lo, sum hi); aim the pivot at
             // the same fraction of the widest range as a target rank is of that interval.  The target
-            // is r minus, then r plus, about two standard deviations of the estimate (2 * sqrt of the
-            // interval), so that two steps bracket x from both sides.  Every third step takes the
-            // widest range's node of the fixed search tree, which keeps the worst case logarithmic.
+            // is r minus, then r plus, a margin of the order of the estimate's standard deviation (the
+            // square root of the interval: one such on the cached sample arrays, a quarter where every probe
+            // is an HBM access and a missed bracket costs less than a wide one - both measured), so that two
+            // steps bracket x from both sides.  Every third step is a bisection step, which keeps the worst
+            // case logarithmic.
             const uint64_t rank_lo = group_sum_u64(own ? lo : 0, group), rank_hi = group_sum_u64(own ? hi : 0, group);
             uint64_t span = rank_hi - rank_lo, ahead = r > rank_lo ? r - rank_lo : 0;
-            const uint64_t margin = span ? 2ull << ((64 - __builtin_clzll(span)) >> 1) : 0;
+            const uint64_t margin = span ? (1ull << ((64 - __builtin_clzll(span)) >> 1)) >> (kCached ? 0 : 2) : 0;
             if (iter % 3 == 0) ahead = ahead > margin ? ahead - margin : 0;
             else ahead += margin;
             if (ahead > span) ahead = span;
