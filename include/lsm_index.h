@@ -213,7 +213,7 @@ int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, co
                       size_t workspace_bytes, void* stream, const lsm_remap_t* remap, const lsm_compact_events_t* ev);
 
 /* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments.
- * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per 1984 entries. */
+ * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per (2048 - n_runs) entries. */
 size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
 
 /*

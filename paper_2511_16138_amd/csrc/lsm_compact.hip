@@ -31,7 +31,9 @@ constexpr int kMergeThreads = 512;
 constexpr int kMergeItems = 4;
 constexpr int kTileCap = kMergeThreads * kMergeItems;  // entries per tile
 constexpr int kRoundItems = 4;                         // outputs per thread in a merge round
-constexpr int kTileNominal = kTileCap - LSM_MAX_RUNS;  // boundary spacing in merged rank
+// Boundary spacing in merged rank for k runs: a tile is at most k - 1 entries longer than this (keys are unique
+// inside a run, so the boundary key's rank is less than k short of its target), which is the tile capacity.
+__host__ __device__ inline uint64_t tile_nominal(uint32_t k) { return (uint64_t)kTileCap - k; }
 constexpr uint64_t kCoarseStride = 16;                 // every 16th boundary is searched over whole sequences first
 constexpr uint64_t kSampleStride = 32;                 // one key in 32 is copied for the sampled partition
 constexpr uint64_t kSampledMinTiles = 65;              // inputs of fewer tiles search the runs directly
@@ -238,7 +240,7 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
     // coarse pass: b = coarse, 2*coarse, ...; fine pass: every b in 1..n_tiles-1 that is not a multiple of coarse
     const uint64_t b = fine_pass ? g.slot + g.slot / (coarse - 1) + 1 : (g.slot + 1) * coarse;
     const bool valid = b < n_tiles;
-    const uint64_t r = b * (uint64_t)kTileNominal;
+    const uint64_t r = b * tile_nominal(rt.k);
     const bool own = valid && g.member < (int)rt.k;
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
     uint64_t lo = 0, hi = own ? rt.n[g.member] : 0;
@@ -279,7 +281,7 @@ __global__ void __launch_bounds__(256) sample_kernel(RunTable rt, SampleTable st
 }
 
 __device__ __forceinline__ uint64_t sample_target(uint64_t b, int side, uint32_t k) {
-    const uint64_t r = b * (uint64_t)kTileNominal;
+    const uint64_t r = b * tile_nominal(k);
     return side ? (r + kSampleStride - 1) / kSampleStride + 2ull * k - 1 : r / kSampleStride;
 }
 
@@ -319,7 +321,7 @@ __global__ void __launch_bounds__(256) bracket_partition_kernel(RunTable rt, Wor
     const GroupLane g = group_lane(group);
     const uint64_t b = g.slot + 1;
     const bool own = b < n_tiles && g.member < (int)rt.k;
-    const uint64_t r = b * (uint64_t)kTileNominal;
+    const uint64_t r = b * tile_nominal(rt.k);
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
     uint64_t lo = 0, hi = 0, yhi = 0;
     if (own) {
@@ -940,14 +942,14 @@ __global__ void validate_kernel(RunTable rt, Workspace ws) {
     if (bad) atomicOr(&ws.hdr->validate_status, bad);
 }
 
-static uint64_t tiles_for(uint64_t total) { return (total + kTileNominal - 1) / kTileNominal; }
+static uint64_t tiles_for(uint64_t total, uint32_t k) { return (total + tile_nominal(k) - 1) / tile_nominal(k); }
 static uint64_t coarse_rows(uint64_t n_tiles) { return n_tiles > 1 ? (n_tiles - 1) / kCoarseStride : 0; }
 
 // Lays the workspace out; with base == nullptr it only measures.  Returns the bytes used.
 static size_t carve(void* base, const uint64_t* run_lens, uint32_t k, Workspace* ws) {
     uint64_t total = 0;
     for (uint32_t j = 0; j < k; j++) total += run_lens[j];
-    const uint64_t n_tiles = tiles_for(total), n_coarse = coarse_rows(n_tiles);
+    const uint64_t n_tiles = tiles_for(total, k), n_coarse = coarse_rows(n_tiles);
     char* p = static_cast<char*>(base);
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -1018,7 +1020,7 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
         workspace_bytes < lsm_compact_workspace_bytes(lens, n_runs))
         return LSM_ERR_WORKSPACE;
-    const uint64_t n_tiles = tiles_for(total);
+    const uint64_t n_tiles = tiles_for(total, n_runs);
     if (n_tiles >= (1ull << 31)) return LSM_ERR_BAD_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     Workspace ws;
