@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 # HBM bytes of one merge_kernel launch on the full configuration, from the FETCH_SIZE and WRITE_SIZE counters of
 # rocprofv3 scaled by a streaming kernel of known size (profiles/compaction_cfg3_tiered16_hbm_traffic.md)
-MERGE_KERNEL_TRAFFIC_BYTES = 4.356e9 + 2.933e9
+MERGE_KERNEL_TRAFFIC_BYTES = 4.355e9 + 2.933e9
 
 
 def cpu_baseline(sample_runs):
