@@ -230,28 +230,13 @@ __device__ __forceinline__ GroupLane group_lane(int group) {
     return g;
 }
 
-// Direct search over the runs, for inputs of a few tiles.  The kernel runs twice: first for the
-// boundaries that are multiples of `coarse` (search over whole runs), then for the others, whose
-// search starts from the enclosing coarse boundaries (splits are monotone in the boundary number,
-// so those are valid bounds).
-__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group,
-                                                         uint64_t coarse, int fine_pass) {
+// Direct search over whole runs, for inputs of a few dozen tiles: one launch, one group per interior boundary.
+__global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group) {
     const GroupLane g = group_lane(group);
-    // coarse pass: b = coarse, 2*coarse, ...; fine pass: every b in 1..n_tiles-1 that is not a multiple of coarse
-    const uint64_t b = fine_pass ? g.slot + g.slot / (coarse - 1) + 1 : (g.slot + 1) * coarse;
-    const bool valid = b < n_tiles;
-    const uint64_t r = b * tile_nominal(rt.k);
-    const bool own = valid && g.member < (int)rt.k;
+    const uint64_t b = g.slot + 1;
+    const bool own = b < n_tiles && g.member < (int)rt.k;
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
-    uint64_t lo = 0, hi = own ? rt.n[g.member] : 0;
-    if (fine_pass && own) {
-        const uint64_t below = b - b % coarse, above = below + coarse < n_tiles ? below + coarse : n_tiles;
-        lo = ws.splits[below * rt.k + g.member];
-        hi = ws.splits[above * rt.k + g.member];
-        if (hi > rt.n[g.member]) hi = rt.n[g.member];  // only inputs that break the precondition
-        if (lo > hi) lo = hi;
-    }
-    const uint64_t best = select_split<false>(run, lo, hi, r, own, g.member, group, g.group_base);
+    const uint64_t best = select_split<false>(run, 0, own ? rt.n[g.member] : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
@@ -1049,11 +1034,9 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
         const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);  // selection problems per workgroup
         auto blocks = [&](uint64_t problems) { return dim3((uint32_t)((problems + per_block - 1) / per_block)); };
         if (n_tiles < kSampledMinTiles) {
-            const uint64_t n_fine = (n_tiles - 1) - n_coarse;
-            if (n_coarse > 0)
-                hipLaunchKernelGGL(partition_kernel, blocks(n_coarse), dim3(256), 0, stream, rt, ws, n_tiles, group, kCoarseStride, 0);
-            if (n_fine > 0)
-                hipLaunchKernelGGL(partition_kernel, blocks(n_fine), dim3(256), 0, stream, rt, ws, n_tiles, group, kCoarseStride, 1);
+            // a few dozen boundaries: every one searched over whole runs (a coarse pass first would be a second
+            // dependent launch, which costs more than the longer searches)
+            hipLaunchKernelGGL(partition_kernel, blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
         } else {
             uint64_t m_max = 0;
             for (uint32_t j = 0; j < n_runs; j++) m_max = ws.st.m[j] > m_max ? ws.st.m[j] : m_max;
