@@ -36,7 +36,7 @@ constexpr int kRoundItems = 4;                         // outputs per thread in 
 __host__ __device__ inline uint64_t tile_nominal(uint32_t k) { return (uint64_t)kTileCap - k; }
 constexpr uint64_t kCoarseStride = 16;                 // every 16th boundary is searched over whole sequences first
 constexpr uint64_t kSampleStride = 32;                 // one key in 32 is copied for the sampled partition
-constexpr uint64_t kSampledMinTiles = 65;              // inputs of fewer tiles search the runs directly
+constexpr uint64_t kSampledMinTiles = 2048;            // inputs of fewer tiles search the runs directly (measured crossover)
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
 
 // Tile status word: top two bits = state, low 62 bits = value.

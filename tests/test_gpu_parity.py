@@ -49,7 +49,7 @@ def test_generator_is_identical_on_cpu_and_gpu(cfg1):
     assert all(torch.equal(a.cpu(), b) for a, b in zip(cfg1.runs, w.runs))
 
 
-@pytest.mark.parametrize("scale,flags", [(256, 1), (256, 0), (64, 1)])
+@pytest.mark.parametrize("scale,flags", [(256, 1), (256, 0), (64, 1), (12, 1)])  # scale 12: 5.6M entries, the sampled partition
 def test_scaled_config3_tiered_16way(g, oracle, scale, flags):
     from workloads import lsm
     print("config3 scale", scale, "flags", flags, flush=True)
