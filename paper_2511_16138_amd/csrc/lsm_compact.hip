@@ -482,6 +482,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     //      tickets come back in a different order than the workgroup numbers for 99 % of the tiles.)  The waits
     //      are bounded in any case.
     if (wave == 0) {
+        __builtin_amdgcn_s_setprio(3);  // the other waves wait for this one: let it issue first
         const uint64_t t = blockIdx.x;
         uint64_t a = 0, b = 0;
         const bool mine = lane < (int)k;
@@ -511,6 +512,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             s.failed = ok ? 0 : 1;
             s.inexact = 0;
         }
+        __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();
     const uint64_t tile = s.tile;
@@ -856,12 +858,14 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
 
     // ---- output offset of this tile: wave 0 looks back while the other waves already stage their survivors
     if (wave == 0) {
+        __builtin_amdgcn_s_setprio(3);  // the stores of the whole tile wait for this wave
         bool failed;
         uint64_t base = lookback(ws.status, tile, total, s.failed != 0, &failed);
         if (lane == 0) {
             s.base = base;
             if (failed) s.failed = 1;
         }
+        __builtin_amdgcn_s_setprio(0);
     }
 
     // ---- survivors leave through an LDS stage so that the global stores are contiguous; the four
