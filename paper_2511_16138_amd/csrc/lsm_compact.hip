@@ -520,6 +520,8 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     const uint32_t n = s.n;
 
     // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
+    // the few instructions of a memory phase should not queue behind the other workgroup's merge arithmetic
+    __builtin_amdgcn_s_setprio(2);
     uint4 ent[kMergeItems][4];
     uint32_t pos[kMergeItems];  // merged position of the entry
     {
@@ -558,6 +560,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         }
     }
     if (tid == 0) s.flag[n] = 0;
+    __builtin_amdgcn_s_setprio(0);
     __syncthreads();
 
     // ---- merge rounds: lists of `width` runs each are merged pairwise.  Surrogates are compared as whole
@@ -865,12 +868,12 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
             s.base = base;
             if (failed) s.failed = 1;
         }
-        __builtin_amdgcn_s_setprio(0);
     }
 
     // ---- survivors leave through an LDS stage so that the global stores are contiguous; the four
     //      16-byte parts of a slot are rotated by the slot number to spread them over the banks
     uint4* stage = &s.buf[0][0];
+    __builtin_amdgcn_s_setprio(2);  // output is a memory phase again
     uint64_t base = 0;
     uint32_t first = 0;
     do {
