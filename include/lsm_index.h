@@ -26,8 +26,9 @@
  *     Calls return as soon as the work is enqueued unless stated otherwise; outputs are
  *     valid once the stream has been synchronised.
  *   - Every function returns 0 (LSM_OK) or a negative lsm_status; nothing throws or aborts.
- *     Argument errors are detected on the host before anything is launched, so a failed
- *     call has written nothing.
+ *     Argument errors are detected on the host before anything is launched, so a call
+ *     that fails with one of them has written nothing.  (LSM_ERR_UNSORTED / LSM_ERR_BAD_ENTRY / LSM_ERR_INTERNAL
+ *     are found on the device: the workspace, and for LSM_ERR_INTERNAL the output, have been written by then.)
  *   - Keys are ordered as 32-byte big-endian byte strings (memcmp order).  All other fields
  *     are little-endian.  There is no floating point on the device.
  */
@@ -197,8 +198,8 @@ int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, co
 
 /*
  * lsm_compact_remap -- lsm_compact that also rewrites the value pointers of the entries it writes (section 3.4,
- * automatic tensor-file merging: when tensor files are merged "during scheduled compaction cycles", the file id
- * and offset stored in the index entries are updated).  A value pointer is (file_id << 32) | offset.  For every
+ * automatic tensor-file merging: tensor files are merged in the background as part of the compaction schedule, and
+ * the file id and offset stored in the index entries then have to follow).  A value pointer is (file_id << 32) | offset.  For every
  * surviving PUT whose file_id < n_files:  vptr_out = base[file_id] + offset  (64-bit addition; base[f] is the new
  * (file_id << 32) | offset of old file f's first byte).  Other entries - tombstones, files outside the table -
  * are copied unchanged.  base: DEVICE, n_files x uint64.  remap == NULL or n_files == 0 is exactly lsm_compact.
@@ -276,8 +277,8 @@ int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* tree, uint3
 
 /*
  * lsm_range_bounds -- where a key range starts and ends in every run of a tree: the first step of a range lookup
- * (section 2.2 "Range Lookups"; appendix B: get_batch "performs range scans to retrieve keys and tensor
- * locations").  lo_key, hi_key: HOST, 32 bytes each.  bounds_out: DEVICE, 2 * n_runs uint64:
+ * (section 2.2, range lookups; appendix B: get_batch first scans a key range of the index for the keys and the
+ * places of their tensors).  lo_key, hi_key: HOST, 32 bytes each.  bounds_out: DEVICE, 2 * n_runs uint64:
  *   bounds_out[2r] = number of entries of run r with key < lo_key, bounds_out[2r+1] = number with key < hi_key.
  * The range's content is then one lsm_compact with LSM_BOTTOMMOST over the slices
  * runs[r].entries[bounds[2r] .. bounds[2r+1]) (newest version of every key in [lo_key, hi_key), live PUTs only).
