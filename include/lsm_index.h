@@ -70,7 +70,8 @@ typedef enum {
     LSM_ERR_UNSORTED = -5,  /* LSM_VALIDATE: a run is not strictly ascending by key        */
     LSM_ERR_BAD_ENTRY = -6, /* LSM_VALIDATE: a type byte is neither PUT nor TOMBSTONE      */
     LSM_ERR_HIP = -7,       /* a HIP call failed                                           */
-    LSM_ERR_INTERNAL = -8   /* a device-side consistency check failed (see lsm_compact)    */
+    LSM_ERR_INTERNAL = -8,  /* a device-side consistency check failed (see lsm_compact)    */
+    LSM_ERR_STATIC_LIMIT = -9 /* lsm_compact_static: the input needs more scratch than the library's static array holds */
 } lsm_status;
 
 enum {
@@ -78,6 +79,7 @@ enum {
     LSM_MAX_BLOCKS = 256,       /* block keys per probe request                            */
     LSM_MAX_BUFFER = 65536,     /* entries per lsm_flush_buffer call                       */
     LSM_KEY_BYTES = 32,
+    LSM_STATIC_SCRATCH_BYTES = 8 << 20, /* scratch held inside the library for lsm_compact_static      */
     LSM_DEFAULT_FENCE_STRIDE = 64 /* one fence per 4 KiB page of entries                   */
 };
 
@@ -212,6 +214,19 @@ typedef struct {
 
 int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                       size_t workspace_bytes, void* stream, const lsm_remap_t* remap, const lsm_compact_events_t* ev);
+
+/*
+ * lsm_compact_static -- lsm_compact without a workspace argument, for callers that cannot allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch memory is a
+ * static device array of LSM_STATIC_SCRATCH_BYTES (8 MiB) inside the library, which every GPU the library runs on
+ * holds until the process ends; the call allocates and frees nothing.  The caller still passes inputs and outputs.
+ * Limit: inputs with lsm_compact_workspace_bytes(...) > LSM_STATIC_SCRATCH_BYTES (about 4 million entries for 16
+ * runs) are rejected with LSM_ERR_STATIC_LIMIT before anything is launched.  LSM_VALIDATE is rejected with
+ * LSM_ERR_BAD_ARG (it copies to the host and waits).  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on one GPU (two streams, two threads) race and give undefined results; calls that follow each
+ * other on one stream are fine, whatever their sizes.  Result and other errors exactly as lsm_compact.
+ */
+int lsm_compact_static(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* stream);
 
 /* Bytes of workspace lsm_compact needs for runs of these lengths (HOST array). 0 on bad arguments.
  * About one byte per input entry (a copy of every 32nd key) plus 24 * n_runs bytes per (2048 - n_runs) entries. */

@@ -98,6 +98,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_compact_timed.argtypes = L.lsm_compact.argtypes + [C.POINTER(_CompactEvents)]
     L.lsm_compact_remap.restype = C.c_int
     L.lsm_compact_remap.argtypes = L.lsm_compact.argtypes + [C.POINTER(_Remap), C.POINTER(_CompactEvents)]
+    L.lsm_compact_static.restype = C.c_int
+    L.lsm_compact_static.argtypes = [C.POINTER(_Run), C.c_uint32, C.c_uint32, C.POINTER(_Out), C.c_void_p]
     L.lsm_compact_workspace_bytes.restype = C.c_size_t
     L.lsm_compact_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), C.c_uint32]
     L.lsm_build_fences.restype = C.c_int
@@ -189,6 +191,20 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
         rc = L.lsm_compact_timed(rd, len(runs), flags, C.byref(od), ws_ptr, ws_bytes, _stream_ptr(stream), C.byref(ev))
     if rc != 0:
         raise LsmError(rc, "lsm_compact")
+    return out, n_out
+
+
+def lsm_compact_static(runs: Sequence[torch.Tensor], flags: int, out: torch.Tensor, n_out: torch.Tensor, stream=None,
+                       fences: Optional[torch.Tensor] = None, fence_stride: int = 64) -> Tuple[torch.Tensor, torch.Tensor]:
+    """lsm_compact on the library's own static scratch: nothing is allocated, here or in the library, so the caller
+    passes every buffer (out int64 [capacity, 8], n_out int64 [1])."""
+    runs = [_dev(r, "run") for r in runs]
+    rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
+    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
+              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0)
+    rc = _load().lsm_compact_static(rd, len(runs), flags, C.byref(od), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_compact_static")
     return out, n_out
 
 

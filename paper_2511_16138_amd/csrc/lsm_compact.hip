@@ -23,6 +23,8 @@
 //                     surviving byte written once.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "lsm_common.h"
 
 namespace lsm {
@@ -1077,4 +1079,45 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
         if (n == ~0ull) return LSM_ERR_INTERNAL;
     }
     return LSM_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// lsm_compact_static: the same compaction for callers that cannot allocate device memory.  The workspace is a
+// file-scope device array; each GPU holds its own copy at its own address, looked up once per device.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[LSM_STATIC_SCRATCH_BYTES];
+
+namespace lsm {
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[kMaxDevices];  // device address of `scratch` on device d, once known
+
+// Device address of this GPU's copy of `scratch` (the array's name itself is only a host-side handle).
+static int scratch_address(void** ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LSM_ERR_HIP;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return LSM_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LSM_OK;
+}
+}  // namespace lsm
+
+extern "C" int lsm_compact_static(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* stream) {
+    if (runs == nullptr) return LSM_ERR_NULL;
+    if (n_runs == 0 || n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    if (flags & LSM_VALIDATE) return LSM_ERR_BAD_ARG;  // validation copies a status word to the host and waits
+    uint64_t lens[LSM_MAX_RUNS];
+    for (uint32_t j = 0; j < n_runs; j++) lens[j] = runs[j].n;
+    if (lsm_compact_workspace_bytes(lens, n_runs) > (size_t)LSM_STATIC_SCRATCH_BYTES) return LSM_ERR_STATIC_LIMIT;
+    void* ws = nullptr;
+    const int rc = lsm::scratch_address(&ws);
+    if (rc != LSM_OK) return rc;
+    // every word of the scratch that a call reads is written by that call's own kernels first (init_kernel clears the
+    // tile status words), so what the previous call left behind does not matter
+    return lsm_compact_remap(runs, n_runs, flags, out, ws, LSM_STATIC_SCRATCH_BYTES, stream, nullptr, nullptr);
 }

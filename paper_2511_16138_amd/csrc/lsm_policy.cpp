@@ -58,6 +58,7 @@ extern "C" const char* lsm_strerror(int code) {
         case LSM_ERR_BAD_ENTRY: return "an input entry has an invalid type byte";
         case LSM_ERR_HIP: return "a HIP call failed";
         case LSM_ERR_INTERNAL: return "device-side consistency check failed";
+        case LSM_ERR_STATIC_LIMIT: return "input too large for the library's static scratch (use lsm_compact with a workspace)";
         default: return "unknown status";
     }
 }

@@ -89,7 +89,14 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     tr[0].run, tr[0].fence = B._Run(64 * 1000, 100), B._Fence(4096, 1, 64)        # needs 2 fences
     q = B._Queries(4096, 8192, 4, 16)
     assert lib.lsm_probe(C.byref(q), C.byref(B._Tree(tr, 1)), C.byref(hits), None) == -2
-    for code in range(-8, 1):
+    # the entry point without a workspace argument: same checks, plus its size limit, all before any launch
+    assert lib.lsm_compact_static(None, 1, 0, C.byref(out), None) == -1
+    assert lib.lsm_compact_static(C.byref(run), 0, 0, C.byref(out), None) == -2
+    assert lib.lsm_compact_static(C.byref(fake), 1, 2, C.byref(big), None) == -2      # LSM_VALIDATE needs the host
+    huge = B._Run(64 * 1000, 1 << 26)
+    assert lib.lsm_compact_static(C.byref(huge), 1, 0, C.byref(big), None) == -9      # beyond the static scratch
+    assert n_out.value == 123
+    for code in range(-9, 1):
         assert lib.lsm_strerror(code) and lib.lsm_strerror(code) != b"unknown status"
     assert lib.lsm_strerror(-99) == b"unknown status"
 
