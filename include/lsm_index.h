@@ -118,7 +118,7 @@ typedef struct {
  *   h = 0x5EED251116138; for i = 0..3: h = mix(h ^ k_i);   g = mix(h ^ 0x9E3779B97F4A7C15)
  *   block = ((h >> 32) * n_blocks) >> 32;   bit_j = (g >> (7 j)) & 127 for j = 0..5
  * A key is in the filter when the six bits are set in its block; bit b of a block is bit (b & 31) of the
- * block's little-endian 32-bit word b >> 5.  No false negatives; about 1 % false positives at 16 bits per key.
+ * block's little-endian 32-bit word b >> 5.  No false negatives; about 0.2 % false positives at 16 bits per key (lsm_policy_filter_fpr).
  */
 typedef struct {
     const void* blocks; /* DEVICE, n_blocks x 16 bytes, 16-byte aligned; NULL = the run has no filter */
@@ -326,6 +326,14 @@ uint32_t lsm_policy_levels(uint64_t n_entries, uint64_t buffer_entries, uint32_t
 double lsm_policy_cost(const lsm_policy_input_t* in, uint32_t T, uint32_t K);
 int lsm_policy_choose(const lsm_policy_input_t* in, uint32_t t_min, uint32_t t_max, uint32_t* best_T,
                       uint32_t* best_K);
+
+/*
+ * lsm_policy_filter_fpr -- the false-positive rate p of the lookup costs (section 2.2) for a run filtered by
+ * lsm_build_bloom with `bits_per_key` bits per key: the expectation, over the Poisson number of keys that share a
+ * 128-bit block, of the probability that six bits drawn for a foreign key are all set.  0 bits per key = no filter:
+ * returns 1.  About 0.0022 at 16 bits per key.
+ */
+double lsm_policy_filter_fpr(uint32_t bits_per_key);
 
 const char* lsm_strerror(int code);
 

@@ -124,6 +124,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_policy_cost.argtypes = [C.POINTER(_PolicyInput), C.c_uint32, C.c_uint32]
     L.lsm_policy_choose.restype = C.c_int
     L.lsm_policy_choose.argtypes = [C.POINTER(_PolicyInput), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    L.lsm_policy_filter_fpr.restype = C.c_double
+    L.lsm_policy_filter_fpr.argtypes = [C.c_uint32]
     L.lsm_strerror.restype = C.c_char_p
     L.lsm_strerror.argtypes = [C.c_int]
     _lib = L
@@ -337,6 +339,10 @@ def lsm_policy_levels(n_entries: int, buffer_entries: int, T: int) -> int:
 def lsm_policy_cost(w, s, r, z, n_entries, buffer_entries, T, K, B, p, d) -> float:
     pin = _policy_input(w, s, r, z, n_entries, buffer_entries, B, p, d)
     return float(_load().lsm_policy_cost(C.byref(pin), T, K))
+
+
+def lsm_policy_filter_fpr(bits_per_key: int) -> float:
+    return float(_load().lsm_policy_filter_fpr(bits_per_key))
 
 
 def lsm_policy_choose(w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d) -> Tuple[int, int]:

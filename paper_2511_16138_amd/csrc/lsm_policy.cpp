@@ -1,5 +1,6 @@
 // Cost model of the adaptive controller (paper section 2.2 operation costs, section 3.3
 // weighted total) and the status strings.  Host code only.
+#include <math.h>
 #include <stdint.h>
 
 #include "lsm_index.h"
@@ -45,6 +46,22 @@ extern "C" int lsm_policy_choose(const lsm_policy_input_t* in, uint32_t t_min, u
         }
     }
     return LSM_OK;
+}
+
+// p of the lookup costs for the blocked filter of lsm_build_bloom: a block of 128 bits receives a Poisson number of
+// keys (mean 128 / bits_per_key), each key sets six bits drawn with repetition, and a key that was never inserted
+// passes when its own six bits are all set.
+extern "C" double lsm_policy_filter_fpr(uint32_t bits_per_key) {
+    if (bits_per_key == 0) return 1.0;
+    const double mean = 128.0 / (double)bits_per_key;
+    double weight = exp(-mean), p = 0.0;  // Poisson weight of a block with no key: such a block passes nothing
+    const int last = (int)(mean + 12.0 * sqrt(mean) + 50.0);
+    for (int keys = 1; keys <= last; keys++) {
+        weight *= mean / (double)keys;
+        const double bit_set = 1.0 - pow(1.0 - 1.0 / 128.0, 6.0 * (double)keys);
+        p += weight * pow(bit_set, 6.0);
+    }
+    return p;
 }
 
 extern "C" const char* lsm_strerror(int code) {

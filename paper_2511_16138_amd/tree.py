@@ -3,19 +3,22 @@
 This sequences the library calls for a mixed workload (paper section 3.3 and appendix C):
 flushed runs enter level 1, a level that holds more than K runs is compacted, a level that
 outgrows its capacity M * T**level is moved down, and a sliding window of operation counts
-re-tunes K through the cost model.  All index work (merging, fence building, lookups, the
+re-tunes (T, K) through the cost model.  All index work (merging, fence building, lookups, the
 cost model itself) is done by the backend = the GPU library; nothing here touches entries.
 
 Readings of the paper used here (it gives no constants):
   * a sliding window over the last `window_ops` operations; a write operation is one inserted
-    sequence, a read one probe request; reads that find nothing are "empty probes" (z), the
-    others are split evenly between range reads (s) and point reads (r), as both "derive from
-    successful reads";
+    sequence, a read one probe request; reads that find nothing count as empty probes (z), the
+    others are split evenly between range reads (s) and point reads (r), since the paper takes
+    both coefficients from the successful reads;
   * once the window is full, the (T, K) search is re-run whenever the L1 distance between the
     window's mix and the mix at the last search exceeds `shift_threshold`;
-  * lazy transition: a level adopts the current K the next time a run arrives at it.  A larger
-    K leaves resident runs as they are (the newcomer is placed beside them); a smaller K merges
-    all runs of the level at that next arrival.
+  * lazy transition: a level adopts the current T and K the next time a run arrives at it (data
+    flowing between levels).  A larger K leaves resident runs as they are (the newcomer is placed
+    beside them); a smaller K merges all runs of the level at that next arrival; a new T changes
+    the level's capacity M * T**level from then on;
+  * p of the lookup costs is the false-positive rate of the Bloom filters the backend builds
+    (lsm_policy_filter_fpr of their bits per key), 1 without filters.
 """
 from __future__ import annotations
 
@@ -82,6 +85,9 @@ class GpuBackend:
     def policy_choose(self, w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d) -> Tuple[int, int]:
         return self._b.lsm_policy_choose(w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p, d)
 
+    def filter_fpr(self) -> float:
+        return self._b.lsm_policy_filter_fpr(self.bloom_bits)
+
 
 @dataclass
 class AdaptiveLsmTree:
@@ -93,19 +99,29 @@ class AdaptiveLsmTree:
     shift_threshold: float = 0.2
     t_grid: Tuple[int, int] = (10, 10)
     page_entries: float = 64.0          # B
-    filter_fpr: float = 1.0             # p (no Bloom filters)
+    filter_fpr: Optional[float] = None  # p; None = ask the backend (1 when it builds no Bloom filters)
     levels: List[List[LevelRun]] = field(default_factory=list)   # levels[0] = level 1; runs newest first
     level_k: List[int] = field(default_factory=list)             # K each level is currently run with
+    level_t: List[int] = field(default_factory=list)             # T each level is currently run with
     trace: List[tuple] = field(default_factory=list)
     _events: Any = field(default_factory=lambda: __import__("collections").deque())  # (writes, hits, empties, blocks hit)
     _win: List[float] = field(default_factory=lambda: [0, 0, 0, 0.0])  # sums over _events
     _last_mix: Optional[Tuple[float, float, float, float]] = None
 
+    def __post_init__(self) -> None:
+        if self.filter_fpr is None:
+            fpr = getattr(self.backend, "filter_fpr", None)
+            self.filter_fpr = float(fpr()) if fpr else 1.0
+
     # ------------------------------------------------------------------ structure
-    def load_level(self, level: int, runs_newest_first: Sequence[Any]) -> None:
+    def _ensure_level(self, level: int) -> None:
         while len(self.levels) <= level:
             self.levels.append([])
             self.level_k.append(self.runs_per_level)
+            self.level_t.append(self.size_ratio)
+
+    def load_level(self, level: int, runs_newest_first: Sequence[Any]) -> None:
+        self._ensure_level(level)
         self.levels[level] = [self._index(r) for r in runs_newest_first]
 
     def _index(self, run: Any) -> LevelRun:
@@ -114,7 +130,7 @@ class AdaptiveLsmTree:
         return LevelRun(run, self.backend.build_fences(run), build_bloom(run) if build_bloom else None)
 
     def capacity(self, level: int) -> int:
-        return self.buffer_entries * self.size_ratio ** (level + 1)
+        return self.buffer_entries * self.level_t[level] ** (level + 1)
 
     def total_entries(self) -> int:
         return sum(r.n for lv in self.levels for r in lv)
@@ -131,10 +147,11 @@ class AdaptiveLsmTree:
         self.flush(self.backend.flush_buffer(buffer))
 
     def _arrive(self, level: int, newcomer: LevelRun) -> None:
-        while len(self.levels) <= level:
-            self.levels.append([])
-            self.level_k.append(self.runs_per_level)
-        self.level_k[level] = self.runs_per_level  # lazy transition: K is adopted when a run arrives
+        self._ensure_level(level)
+        if (self.level_t[level], self.level_k[level]) != (self.size_ratio, self.runs_per_level):
+            self.trace.append(("adopt", level + 1, self.size_ratio, self.runs_per_level))
+        # lazy transition: the level takes the current parameters when data flows into it
+        self.level_t[level], self.level_k[level] = self.size_ratio, self.runs_per_level
         lv = self.levels[level]
         lv.insert(0, newcomer)
         if len(lv) <= self.level_k[level]:

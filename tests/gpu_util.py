@@ -40,3 +40,23 @@ def assert_probe_equal(oracle, got, want):
     whl, whits = want
     assert np.array_equal(hl, whl)
     assert np.array_equal(hits.view(oracle.HIT_DTYPE).reshape(whits.shape), whits)
+
+
+def oracle_probe_threads(oracle, q, nb, runs, threads=16):
+    """oracle.probe with the requests split over threads (the C checker runs without the interpreter lock).  The
+    arithmetic is the checker's; only the batch is cut into slices and the results are put back together."""
+    from concurrent.futures import ThreadPoolExecutor
+    if hasattr(q, "detach"):
+        q = q.detach().cpu().contiguous().numpy()
+    if hasattr(nb, "detach"):
+        nb = nb.detach().cpu().numpy()
+    n = int(nb.shape[0])
+    q = np.ascontiguousarray(q).view(np.uint8).reshape(n, -1, 32)
+    runs = [oracle.as_run(r) for r in runs]
+    cuts = np.linspace(0, n, min(threads, max(n, 1)) + 1).astype(np.int64)
+    parts = [(int(a), int(b)) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(lambda ab: oracle.probe(q[ab[0]:ab[1]], nb[ab[0]:ab[1]], runs), parts))
+    if not res:
+        return oracle.probe(q, nb, runs)
+    return np.concatenate([r[0] for r in res]), np.concatenate([r[1] for r in res])

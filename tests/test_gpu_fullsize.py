@@ -2,13 +2,15 @@
 
 The CPU checker is fast enough (tens of millions of entries per second per core on the GPU
 box's host) to merge the full inputs, so compaction outputs are compared entry by entry.
-Probes against the 100M-entry tree are compared on sampled batches.
+Probes against the 100M-entry tree: all 256 batches (the checker's requests split over the host's cores).
+The mixed configuration: the whole trace on the 400M-entry tree, every compaction output and every probe batch.
 """
+import time
 import numpy as np
 import pytest
 import torch
 
-from gpu_util import as_bytes, assert_probe_equal, build_tree, compact_gpu, dev, probe_gpu
+from gpu_util import as_bytes, assert_probe_equal, build_tree, compact_gpu, dev, oracle_probe_threads, probe_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -52,8 +54,9 @@ def test_config3_full_tiered_16_way(g, oracle):
     assert 0.66 < ratio < 0.70  # about 0.95 / 1.4 of the inputs survive
 
 
-def test_config4_full_tree_sampled_probe_batches(g, oracle):
-    """5-level, 100M-entry tree; 3 of the 256 batches of 4,096 requests are checked in full."""
+def test_config4_full_tree_all_probe_batches(g, oracle):
+    """5-level, 100M-entry tree; all 256 batches of 4,096 requests (2^20 requests): hit_len and every hit byte.
+    Every 16th batch is also run with Bloom filters and through the search over the prefix length."""
     from workloads import lsm
     print("config4 full tree", flush=True)
     w = lsm.config4(device=dev())
@@ -64,19 +67,49 @@ def test_config4_full_tree_sampled_probe_batches(g, oracle):
         got_f = as_bytes(f.fences).reshape(-1, 32)
         idx = np.unique(np.linspace(0, got_f.shape[0] - 1, 4096).astype(np.int64))
         assert np.array_equal(got_f[idx], r[idx * 64, :32])
-    # Bloom filters of every level: the largest one in full, and the probe must not change with them
+    # Bloom filters of every level in full, and the probe must not change with them
     filtered = [g.TreeRun(t.run, t.fences, t.stride, t.level, g.lsm_build_bloom(t.run, 16)) for t in tree]
     torch.cuda.synchronize()
     for t, r in zip(filtered, runs_cpu):
         assert np.array_equal(as_bytes(t.bloom).reshape(-1, 16), oracle.build_bloom(r, int(t.bloom.shape[0])))
-    for stream in (0, 101, 255):
-        print("  batch", stream, flush=True)
+    t0, misses, requests = time.time(), 0, 0
+    for stream in range(256):
         q, nb = lsm.queries_config4(w, 4096, stream=stream)
         got = probe_gpu(g, q, nb, tree)
-        want = oracle.probe(q, nb, runs_cpu)
+        want = oracle_probe_threads(oracle, q, nb, runs_cpu)
         assert_probe_equal(oracle, got, want)
-        assert_probe_equal(oracle, probe_gpu(g, q, nb, filtered), want)
-        for t in (tree, filtered):  # the generator's data is prefix-closed: the search over the length agrees
-            assert np.array_equal(g.lsm_probe_length(q, nb, t).cpu().numpy().astype(np.uint32), want[0])
-        miss = float((want[0] == 0).mean())
-        assert 0.25 < miss < 0.45 and want[0].max() >= 32
+        misses += int((want[0] == 0).sum())
+        requests += int(want[0].shape[0])
+        if stream % 16 == 0:
+            print(f"  batch {stream} ok ({time.time() - t0:.0f} s)", flush=True)
+            assert_probe_equal(oracle, probe_gpu(g, q, nb, filtered), want)
+            for t in (tree, filtered):  # the generator's data is prefix-closed: the search over the length agrees
+                assert np.array_equal(g.lsm_probe_length(q, nb, t).cpu().numpy().astype(np.uint32), want[0])
+            assert want[0].max() >= 32
+    assert requests == 1 << 20 and 0.25 < misses / requests < 0.45
+
+
+def test_config5_full_mixed_trace_on_400m_tree(oracle):
+    """The mixed, shifting workload at its stated size: 6 levels, 400M entries, three phases of 2^18 operations with
+    read shares 90 / 50 / 10 %, Bloom filters of 16 bits per key, (T, K) searched over T in 2..16.  Compared with the
+    plain driver on the CPU checker: every compaction output byte for byte, every probe batch, every log record."""
+    from test_gpu_mixed import replay_both
+    from workloads import lsm
+    print("config5 full: generating", flush=True)
+    t0 = time.time()
+    tr = lsm.config5(device=dev())
+    sizes = [int(r.shape[0]) for r in tr.workload.runs]
+    assert sum(sizes) == 400_000_000 and len(sizes) == 6 and tr.buffer_entries == 3600
+    n_flush = sum(1 for e in tr.events if e[0] == "flush")
+    n_batches = sum(1 for e in tr.events if e[0] == "probe")
+    print(f"  tree {sizes}, {n_flush} flushes, {n_batches} probe batches ({time.time() - t0:.0f} s)", flush=True)
+    assert n_flush > 4000 and n_batches >= 90
+    gpu, n_probe = replay_both(oracle, tr, 16, (2, 16), 16,
+                               progress=lambda msg: print(f"  {msg} ({time.time() - t0:.0f} s)", flush=True))
+    assert n_probe == n_batches
+    comp = [e for e in gpu.trace if e[0] == "compact"]
+    pol = [(e[1], e[2]) for e in gpu.trace if e[0] == "policy"]
+    print("  policy (T, K):", pol, "compactions:", len(comp), "entries merged:", sum(e[3] for e in comp), flush=True)
+    assert len(comp) > 2000 and max(e[3] for e in comp) > 10_000_000    # compactions down to the fourth level
+    assert pol[0][1] == 1 and max(k for _, k in pol) > 1, pol            # leveling under reads, more runs under writes
+    assert len({t for t, _ in pol}) > 1 or pol[0][0] != 10, pol

@@ -1,7 +1,7 @@
-"""Configuration 5 (mixed, shifting workload): the host driver with the GPU library as its
-backend against the same driver with the CPU checker as its backend.  Every probe batch,
-the sequence of compactions (sizes in and out), the policy decisions and the final tree
-must be identical."""
+"""Configuration 5 (mixed, shifting workload): the package's host driver on the GPU library against the plain driver
+of oracle/lsm_driver_oracle.py on the CPU checker.  The two share no code.  Every probe batch (all hit bytes), the
+sequence of compactions (level, run count, sizes in and out, last-level flag), the moves between levels, the policy
+decisions, the levels' transitions of (T, K) and the final tree must be identical."""
 import numpy as np
 import pytest
 import torch
@@ -11,72 +11,89 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-class OracleBackend:
-    def __init__(self, oracle, stride=64):
-        self.o, self.stride = oracle, stride
+def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, progress=None):
+    """Run the trace through both drivers in step: every compaction output and every probe batch is compared as it is
+    produced (so that no more than one of each is alive at a time), the logs after every event."""
+    from gpu_util import oracle_probe_threads
+    from oracle import lsm_driver_oracle as drv
+    from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
+    window = window_batches * tr.batch_requests
+    gpu_out, cpu_out = [], []
 
-    def compact(self, runs, flags):
-        return self.o.compact([self.o.as_run(r) for r in runs], flags & 1)
+    class Recording(GpuBackend):
+        def compact(self, runs, flags):
+            merged = super().compact(runs, flags)
+            gpu_out.append(merged)
+            return merged
 
-    def build_fences(self, run):
-        return self.o.build_fences(self.o.as_run(run), self.stride)
+    gpu = AdaptiveLsmTree(Recording(bloom_bits=bloom_bits), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window,
+                          t_grid=t_grid)
+    cpu = drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=t_grid,
+                           page_entries=64.0, fpr=drv.bloom_fpr(bloom_bits), on_compact=cpu_out.append,
+                           probe_fn=lambda q, nb, runs: oracle_probe_threads(oracle, q, nb, runs))
+    for level, r in enumerate(tr.workload.runs):
+        gpu.load_level(level, [r])
+        cpu.install(level + 1, [r.cpu()])
+    n_probe = 0
+    for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
+        if n_writes:
+            gpu.note_writes(n_writes)
+            cpu.writes(n_writes)
+        if kind == "flush":
+            run = tr.flush_runs[i]
+            if shuffle is not None:   # the GPU side gets the write buffer in the order it was "written" and sorts it itself
+                gpu.flush_unsorted(run[shuffle(i, int(run.shape[0]))])
+            else:
+                gpu.flush(run)
+            cpu.flush(run.cpu())
+            assert len(gpu_out) == len(cpu_out)
+            for got, want in zip(gpu_out, cpu_out):   # every compaction of this flush, byte for byte
+                assert np.array_equal(oracle.as_run(got), want), f"flush {i}: a compaction output differs"
+            gpu_out.clear()
+            cpu_out.clear()
+        else:
+            q, nb = tr.probe_batch(i)
+            ghl, ghits = gpu.probe(q, nb)
+            chl, chits = cpu.probe(q.cpu(), nb.cpu())
+            assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl), f"probe batch {i}: hit_len"
+            assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits), f"probe batch {i}"
+            n_probe += 1
+            if progress:
+                progress(f"probe batch {i} ok, {len(gpu.trace)} log records")
+        assert len(gpu.trace) == len(cpu.log) and gpu.trace[-1:] == cpu.log[-1:], (kind, i, gpu.trace[-3:], cpu.log[-3:])
+    assert gpu.trace == cpu.log
+    assert [len(lv) for lv in gpu.levels] == [len(lv.runs) for lv in cpu.levels]
+    for glv, clv in zip(gpu.levels, cpu.levels):
+        for gr, cr in zip(glv, clv.runs):
+            assert np.array_equal(oracle.as_run(gr.run), cr)
+            assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
+            if bloom_bits:
+                assert np.array_equal(gr.bloom.cpu().numpy().view(np.uint8).reshape(-1, 16), oracle.build_bloom(cr, int(gr.bloom.shape[0])))
+    assert [(t, k) for t, k in zip(gpu.level_t, gpu.level_k)] == [(lv.T, lv.K) for lv in cpu.levels]
+    return gpu, n_probe
 
-    def probe(self, q, nb, tree):
-        return self.o.probe(q, nb, [self.o.as_run(t.run) for t in tree])
 
-    def hit_len_to_host(self, hit_len):
-        return [int(x) for x in hit_len]
-
-    def policy_choose(self, *a):
-        return self.o.policy_choose(*a)
-
-
-def _replay(backend, trace, runs, keep_probes, shuffle_writes=None):
-    from paper_2511_16138_amd.tree import AdaptiveLsmTree, run_mixed_trace
-    tree = AdaptiveLsmTree(backend, trace.buffer_entries, size_ratio=trace.size_ratio, window_ops=4 * trace.batch_requests)
-    for level, r in enumerate(runs):
-        tree.load_level(level, [r])
-    run_mixed_trace(tree, trace, on_probe=lambda i, q, nb, out: keep_probes.append(out), shuffle_writes=shuffle_writes)
-    return tree
-
-
-@pytest.mark.parametrize("tree_total,buffer_entries,ops,shares,bloom_bits", [(400_000, 360, 4096, (0.9, 0.5, 0.1), 0),
-                                                                             (2_000_000, 900, 8192, (0.9, 0.5, 0.02), 0),
-                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), 16),
-                                                                             (400_000, 360, 4096, (0.9, 0.5, 0.1), -1)])
-def test_mixed_trace_gpu_equals_checker(oracle, tree_total, buffer_entries, ops, shares, bloom_bits):
-    from paper_2511_16138_amd.tree import GpuBackend
+@pytest.mark.parametrize("tree_total,buffer_entries,ops,bloom_bits,t_grid,shuffled", [
+    (400_000, 360, 4096, 16, (2, 16), False),    # filters on: p = 0.0022, the full (T, K) grid
+    (2_000_000, 900, 8192, 16, (10, 10), False),  # T fixed at 10: only K moves
+    (400_000, 360, 4096, 0, (2, 16), False),     # no filters: p = 1
+    (400_000, 360, 4096, 16, (2, 16), True),     # write buffers handed over unsorted (lsm_flush_buffer)
+])
+def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled):
     from workloads import lsm
-    print("mixed trace", tree_total, buffer_entries, ops, flush=True)
-    tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=512, read_shares=shares)
+    print("mixed trace", tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, flush=True)
+    tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=128)
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
-
-    gpu_probes, cpu_probes = [], []
-    shuffle = None
-    if bloom_bits < 0:  # the GPU side gets every write buffer in a random order and sorts it itself (lsm_flush_buffer)
-        bloom_bits = 0
-        shuffle = lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())
-    gpu_tree = _replay(GpuBackend(bloom_bits=bloom_bits), tr, tr.workload.runs, gpu_probes, shuffle)  # the checker has no filters
-    torch.cuda.synchronize()
-
-    cpu_trace = lsm.MixedTrace(tr.workload, tr.buffer_entries, tr.size_ratio, tr.flush_runs.cpu(), tr.events, tr.batch_requests,
-                               tr.write_ops_between)
-    cpu_tree = _replay(OracleBackend(oracle), cpu_trace, [r.cpu() for r in tr.workload.runs], cpu_probes)
-
-    assert gpu_tree.trace == cpu_tree.trace
-    kinds = {e[0] for e in gpu_tree.trace}
-    assert {"compact", "probe", "policy"} <= kinds
-    ks = [e[2] for e in gpu_tree.trace if e[0] == "policy"]
-    assert ks[0] == 1, ks  # leveling in the read-heavy phase
-    if shares[2] < 0.05:   # with p = 1 and B = 64 the model leaves leveling only above ~93 % writes
-        assert max(ks) > 1, ks
-        assert any(e[0] == "compact" and e[2] > 2 for e in gpu_tree.trace)  # several runs per level were merged at once
-    assert len(gpu_probes) == len(cpu_probes) > 0
-    for (ghl, ghits), (chl, chits) in zip(gpu_probes, cpu_probes):
-        assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl)
-        assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits)
-    assert [len(lv) for lv in gpu_tree.levels] == [len(lv) for lv in cpu_tree.levels]
-    for glv, clv in zip(gpu_tree.levels, cpu_tree.levels):
-        for gr, cr in zip(glv, clv):
-            assert np.array_equal(oracle.as_run(gr.run), oracle.as_run(cr.run))
-            assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), cr.fences)
+    shuffle = (lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())) if shuffled else None
+    gpu, n_probe = replay_both(oracle, tr, bloom_bits, t_grid, 16, shuffle)
+    kinds = {e[0] for e in gpu.trace}
+    assert {"compact", "probe", "policy", "move"} <= kinds and n_probe >= 6
+    pol = [(e[1], e[2]) for e in gpu.trace if e[0] == "policy"]
+    assert pol[0][1] == 1, pol                     # leveling while reads dominate (phase 90:10)
+    if bloom_bits:
+        # with filters the lookups are cheap enough that the write-heavy phase (10:90) leaves leveling
+        assert max(k for _, k in pol) > 1, pol
+        assert "adopt" in kinds
+        assert any(e[0] == "compact" and e[2] > 2 for e in gpu.trace)   # several runs of a level merged at once
+    if t_grid[0] != t_grid[1]:
+        assert len({t for t, _ in pol}) > 1 or pol[0][0] != tr.size_ratio, pol   # the size ratio moves as well
