@@ -25,13 +25,44 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
-# HBM bytes of one merge_kernel launch on the full configuration, from the FETCH_SIZE and WRITE_SIZE counters of
-# rocprofv3 scaled by a streaming kernel of known size (profiles/compaction_cfg3_tiered16_hbm_traffic.md)
-MERGE_KERNEL_TRAFFIC_BYTES = 4.355e9 + 2.933e9
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "compaction_cfg3_tiered16_hbm_traffic.md")
+MERGE_KERNEL_SOURCE = os.path.join(ROOT, "paper_2511_16138_amd", "csrc", "lsm_compact.hip")
 
 
-def cpu_baseline(sample_runs):
-    """The CPU checker (single thread, as it stands) on the same workload (host copies made by the caller)."""
+def measured_traffic(section: str, source: str):
+    """HBM bytes per launch of a kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary under profiles/ (the
+    line `traffic <section>: bytes_per_launch=... source_sha256=...`).  None when there is no such line or when the
+    kernel's source file has changed since the counters were taken."""
+    import hashlib
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+        sha = hashlib.sha256(open(source, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    m = re.search(r"traffic %s: bytes_per_launch=(\d+) source_sha256=([0-9a-f]{64})" % re.escape(section), text)
+    return int(m.group(1)) if m and m.group(2) == sha else None
+
+
+def host_description():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"cpu_model": model, "logical_cpus": os.cpu_count()}
+
+
+def cpu_baseline(sample_runs, threads: int):
+    """The CPU checker as it stands on the same workload (host copies made by the caller): (i) the single-thread heap
+    merge, (ii) the same merge over `threads` key ranges at once - splitters are every (n / threads)-th key of the
+    largest run, every thread merges the slices of all runs inside its range, the outputs are concatenated."""
+    import bisect
+    from concurrent.futures import ThreadPoolExecutor
+
     from oracle import lsm_oracle
     lsm_oracle.build()
     sample = [lsm_oracle.as_run(r) for r in sample_runs]
@@ -40,14 +71,61 @@ def cpu_baseline(sample_runs):
     t0 = time.perf_counter()
     out = lsm_oracle.compact(sample, lsm_oracle.FLAG_BOTTOMMOST)
     dt = time.perf_counter() - t0
-    return {"value": n_in / dt, "unit": "merged entries/s", "cores": 1, "kind": "oracle",
-            "sample": f"heap merge of all {sample_per_run} entries of each of the {len(sample)} runs "
-                      f"({n_in} in, {out.shape[0]} out, {dt:.1f} s)"}
+    host = host_description()
+    result = {"value": n_in / dt, "unit": "merged entries/s", "cores": 1, "kind": "oracle",
+              "sample": f"heap merge of all {sample_per_run} entries of each of the {len(sample)} runs "
+                        f"({n_in} in, {out.shape[0]} out, {dt:.1f} s)", "host": host}
+
+    class KeysOf:  # run[i].key as bytes, for bisect (order = the checker's key order = bytes order)
+        def __init__(self, run):
+            self.run = run
+
+        def __len__(self):
+            return self.run.shape[0]
+
+        def __getitem__(self, i):
+            return self.run[i, :32].tobytes()
+
+    t0 = time.perf_counter()
+    largest = max(sample, key=lambda r: r.shape[0])
+    splitters = [largest[(i * largest.shape[0]) // threads, :32].tobytes() for i in range(1, threads)]
+    cuts = [[0] + [bisect.bisect_left(KeysOf(r), k) for k in splitters] + [r.shape[0]] for r in sample]
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        parts = list(ex.map(lambda i: lsm_oracle.compact([r[c[i]:c[i + 1]] for r, c in zip(sample, cuts)],
+                                                         lsm_oracle.FLAG_BOTTOMMOST), range(threads)))
+    n_par = sum(p.shape[0] for p in parts)
+    dt_par = time.perf_counter() - t0
+    assert n_par == out.shape[0], "the range-partitioned merge gave another count"
+    result["all_cores"] = {"value": n_in / dt_par, "unit": "merged entries/s", "cores": threads, "kind": "oracle",
+                           "sample": f"the same merge over {threads} key ranges at once ({dt_par:.1f} s)"}
+    return result
+
+
+def probe_useful_bytes(nb, hit_len, hits, n_runs: int, filtered: bool, stride: int = 64):
+    """Bytes a probe batch must move by the per-key formula: a request needs its hit_len found keys and the first
+    missing one looked up; a lookup reads the 32-byte key, writes 16 bytes of result and, in every run it has to search
+    until the key is resolved, the final 64-byte entry plus log2(stride) more entries of the in-page search (the fence
+    levels above the page count as cached).  Without filters a found key searches run_idx + 1 runs and a missing one
+    all runs; with filters only the run that holds the key, plus one 16-byte filter block per run consulted."""
+    import math
+    n = nb.to(hit_len.dtype)
+    first_miss = (hit_len < n).sum().item()
+    found = int(hit_len.sum().item())
+    keys = found + int(first_miss)
+    run_idx = (hits[..., 1] >> 32)  # high half of the second word
+    col = __import__("torch").arange(hits.shape[1], device=hits.device)[None, :]
+    searched_for_found = int(((run_idx + 1) * (col < hit_len[:, None])).sum().item())
+    per_search = (1 + int(math.ceil(math.log2(stride)))) * 64
+    if filtered:
+        return keys * 48 + found * per_search + (searched_for_found + int(first_miss) * n_runs) * 16
+    return keys * 48 + (searched_for_found + int(first_miss) * n_runs) * per_search
 
 
 def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     """Lookup-heavy configuration: batches of 4,096 longest-prefix requests (Zipf(0.99) prefixes, 30 % misses,
-    up to 256 block keys each) against the 5-level, 100M-entry tree.  Returns probes/s and key lookups/s."""
+    up to 256 block keys each) against the 5-level, 100M-entry tree.  Returns probes/s and key lookups/s (medians over
+    the batches) and the rate of useful bytes against the HBM peak."""
+    import statistics
     w = lsm.config4(device=dev, scale=scale)
     plain = [g.TreeRun(r, g.lsm_build_fences(r, 64), 64, i + 1) for i, r in enumerate(w.runs)]
     torch.cuda.synchronize()
@@ -59,44 +137,40 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     hit_len = torch.empty(4096, dtype=torch.int32, device=dev)
     hits = torch.empty((4096, 256, 2), dtype=torch.int64, device=dev)
 
-    def timed(tree):
+    def timed(call):
         for q, nb in batches[:2]:
-            g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
+            call(q, nb)
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for q, nb in batches:
-            g.lsm_probe(q, nb, tree, hit_len=hit_len, hits=hits)
-        e1.record()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in batches]
+        for (q, nb), (e0, e1) in zip(batches, evs):
+            e0.record()
+            call(q, nb)
+            e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n_batches
+        return statistics.median(e0.elapsed_time(e1) for e0, e1 in evs)
 
-    ms_plain = timed(plain)
+    ms_plain = timed(lambda q, nb: g.lsm_probe(q, nb, plain, hit_len=hit_len, hits=hits))
     plain_len = hit_len.clone()
-    ms = timed(filtered)
+    useful_plain = probe_useful_bytes(batches[-1][1], hit_len, hits, len(plain), False)
+    ms = timed(lambda q, nb: g.lsm_probe(q, nb, filtered, hit_len=hit_len, hits=hits))
     assert bool((plain_len == hit_len).all()), "filters changed a probe result"
-
-    def timed_length(tree):  # length of the prefix only, by search over the length (the generator's data is prefix-closed)
-        for q, nb in batches[:2]:
-            g.lsm_probe_length(q, nb, tree, hit_len=hit_len)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for q, nb in batches:
-            g.lsm_probe_length(q, nb, tree, hit_len=hit_len)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n_batches
-
-    ms_len = timed_length(filtered)
+    useful = probe_useful_bytes(batches[-1][1], hit_len, hits, len(filtered), True)
+    # length of the prefix only, by search over the length (the generator's data is prefix-closed)
+    ms_len = timed(lambda q, nb: g.lsm_probe_length(q, nb, filtered, hit_len=hit_len))
     assert bool((plain_len == hit_len).all()), "the search over the prefix length gave another length"
-    ms_len_plain = timed_length(plain)
+    ms_len_plain = timed(lambda q, nb: g.lsm_probe_length(q, nb, plain, hit_len=hit_len))
     keys = sum(int(nb.sum().item()) for _, nb in batches) / n_batches
+    traffic = measured_traffic("probe_kernel_cfg4_filtered", os.path.join(ROOT, "paper_2511_16138_amd", "csrc", "lsm_probe.hip"))
     return {"workload": "configs[3]: 5-level tree of %d entries, batches of 4096 requests, Bloom filters of 16 bits per key on every run"
                         % sum(int(r.shape[0]) for r in w.runs),
             "batches_timed": n_batches, "ms_per_batch": ms, "probes_per_s": 4096 / (ms * 1e-3),
-            "requested_keys_per_s": keys / (ms * 1e-3), "mean_hit_len_last_batch": float(hit_len.float().mean().item()),
-            "without_filters": {"ms_per_batch": ms_plain, "probes_per_s": 4096 / (ms_plain * 1e-3)},
+            "requested_keys_per_s": keys / (ms * 1e-3), "mean_hit_len_last_batch": float(plain_len.float().mean().item()),
+            "probe_roofline": {"bound": "hbm", "kernel": "probe_kernel", "achieved": useful / (ms * 1e-3) / 1e9,
+                               "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": useful / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                               "useful_bytes_per_batch": useful, "traffic": traffic},
+            "without_filters": {"ms_per_batch": ms_plain, "probes_per_s": 4096 / (ms_plain * 1e-3),
+                                "useful_bytes_per_batch": useful_plain,
+                                "useful_gbps": useful_plain / (ms_plain * 1e-3) / 1e9},
             "length_only": {"ms_per_batch": ms_len, "probes_per_s": 4096 / (ms_len * 1e-3),
                             "without_filters_ms_per_batch": ms_len_plain},
             "bloom_build_ms_all_runs": bloom_build_ms}
@@ -109,7 +183,8 @@ def mixed_config5(g, lsm, torch, dev, scale: int):
     from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
     tr = lsm.config5(device=dev, tree_total=400_000_000 // scale, buffer_entries=max(36, 3600 // scale),
                      ops_per_phase=(1 << 18) // scale)
-    tree = AdaptiveLsmTree(GpuBackend(), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests)
+    tree = AdaptiveLsmTree(GpuBackend(bloom_bits=16), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests,
+                           t_grid=(2, 16))
     for level, r in enumerate(tr.workload.runs):
         tree.load_level(level, [r])
     batches = {i: tr.probe_batch(i) for kind, i, _ in tr.events if kind == "probe"}
@@ -150,7 +225,7 @@ def main() -> int:
     ap.add_argument("--scale", type=int, default=1, help="divide the workload size (1 = the full configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe-config", action="store_true", help="skip the extra probe measurement on the 100M-entry tree")
-    ap.add_argument("--mixed", action="store_true", help="also replay the mixed workload of the 400M-entry tree (about a minute)")
+    ap.add_argument("--no-mixed", action="store_true", help="skip the replay of the mixed workload on the 400M-entry tree")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="before the steps, run a plain streaming kernel (dst = src + 1 over 1 GiB of int64, 5 launches) "
                          "whose HBM bytes are known; it scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -235,17 +310,21 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    import statistics
     sl = range(args.warmup, n_total)
     mean = lambda xs: sum(xs) / max(1, len(xs))
-    ms_partition = mean([ev_part[i].elapsed_time(ev_merge0[i]) for i in sl])
-    ms_merge = mean([ev_merge0[i].elapsed_time(ev_merge1[i]) for i in sl])
-    ms_compact = mean([ev_part[i].elapsed_time(ev_merge1[i]) for i in sl])
-    ms_fence = mean([ev_c1[i].elapsed_time(ev_f1[i]) for i in sl])
-    ms_probe = mean([ev_f1[i].elapsed_time(ev_p1[i]) for i in sl])
+    med = lambda xs: statistics.median(xs) if xs else 0.0
+    t_part = [ev_part[i].elapsed_time(ev_merge0[i]) for i in sl]
+    t_merge = [ev_merge0[i].elapsed_time(ev_merge1[i]) for i in sl]
+    t_compact = [ev_part[i].elapsed_time(ev_merge1[i]) for i in sl]
+    t_fence = [ev_c1[i].elapsed_time(ev_f1[i]) for i in sl]
+    t_probe = [ev_f1[i].elapsed_time(ev_p1[i]) for i in sl]
+    ms_partition, ms_merge, ms_compact, ms_fence, ms_probe = med(t_part), med(t_merge), med(t_compact), med(t_fence), med(t_probe)
+    ms_merge_mean = mean(t_merge)  # the roofline figure divides by the average launch duration
     ms_step = elapsed * 1e3 / args.steps
 
     algo_bytes = 64 * (n_in + n_out)  # every input entry read once, every survivor written once
-    achieved = algo_bytes / (ms_merge * 1e-3) / 1e9
+    achieved = algo_bytes / (ms_merge_mean * 1e-3) / 1e9
     result = {
         "metric": "compaction merged entries/s (HBM GB/s % peak); prefix probes/s",
         "value": n_in / (ms_step * 1e-3),
@@ -263,9 +342,10 @@ def main() -> int:
         "probes_per_s": int(q.shape[0]) / (ms_probe * 1e-3),
         "probe_key_lookups_per_s": n_keys / (ms_probe * 1e-3),
         "ms": {"partition_kernels": ms_partition, "merge_kernel": ms_merge, "compact_total": ms_compact,
-               "fence_build": ms_fence, "probe_batch": ms_probe, "generate_inputs_s": gen_s},
+               "fence_build": ms_fence, "probe_batch": ms_probe, "statistic": "median over the timed steps",
+               "merge_kernel_mean": ms_merge_mean, "generate_inputs_s": gen_s},
         "roofline": {"bound": "hbm", "kernel": "merge_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": MERGE_KERNEL_TRAFFIC_BYTES if args.scale == 1 else None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic("merge_kernel_cfg3", MERGE_KERNEL_SOURCE) if args.scale == 1 else None,
                      "algorithmic_bytes": algo_bytes},
     }
     # second denominator: a plain device-to-device copy that moves the same number of bytes (half read, half written)
@@ -289,11 +369,11 @@ def main() -> int:
     if not args.no_probe_config:
         result["probe_config"] = probe_config4(g, lsm, torch, dev, 16, args.scale)
         torch.cuda.empty_cache()
-    if args.mixed:
+    if not args.no_mixed:
         result["mixed_config"] = mixed_config5(g, lsm, torch, dev, args.scale)
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cpu_sample)
+        result["cpu_baseline"] = cpu_baseline(cpu_sample, min(16, os.cpu_count() or 1))
     print(json.dumps(result))
     return 0
 

@@ -77,7 +77,7 @@ typedef enum {
 enum {
     LSM_MAX_RUNS = 64,          /* runs per lsm_compact call and per lsm_tree_t            */
     LSM_MAX_BLOCKS = 256,       /* block keys per probe request                            */
-    LSM_MAX_BUFFER = 65536,     /* entries per lsm_flush_buffer call                       */
+    LSM_MAX_BUFFER = 262144,    /* entries per lsm_flush_buffer call                       */
     LSM_KEY_BYTES = 32,
     LSM_STATIC_SCRATCH_BYTES = 8 << 20, /* scratch held inside the library for lsm_compact_static      */
     LSM_DEFAULT_FENCE_STRIDE = 64 /* one fence per 4 KiB page of entries                   */
@@ -238,8 +238,10 @@ size_t lsm_compact_workspace_bytes(const uint64_t* run_lens, uint32_t n_runs);
  * order they were written, possibly several versions of a key.  Result: ascending by key, one entry per key -
  * the one with the largest seqno, and among equal seqnos the one written last; tombstones are entries like any
  * other.  out as for lsm_compact (capacity >= n; fence_keys optional).  workspace: DEVICE scratch of at least
- * lsm_flush_workspace_bytes(n) = 4 * n bytes, 4-byte aligned.  Every entry is compared with every other (n^2 key
- * compares from LDS, twice): meant for write buffers of a few thousand entries.
+ * lsm_flush_workspace_bytes(n) bytes, 256-byte aligned (4 * n bytes up to 8,192 entries; beyond that about 70 bytes
+ * per entry: room for the sorted segments and for the merge).  Up to 8,192 entries every entry is compared with
+ * every other (key compares from LDS); a larger buffer is cut into segments of 4,096 entries in write order, the
+ * segments are sorted that way in one launch and then merged by the compaction kernels.  The call does not wait.
  * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (n > LSM_MAX_BUFFER, misaligned), LSM_ERR_CAPACITY, LSM_ERR_WORKSPACE, LSM_ERR_HIP.
  */
 size_t lsm_flush_workspace_bytes(uint64_t n);

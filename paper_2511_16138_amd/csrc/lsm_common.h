@@ -177,8 +177,16 @@ __device__ __forceinline__ bool bloom_excludes(const uint4 w, const uint4 mask) 
 // Run descriptors passed to kernels by value.
 struct RunTable {
     const lsm_entry_t* ptr[LSM_MAX_RUNS];
-    uint64_t n[LSM_MAX_RUNS];
+    uint64_t n[LSM_MAX_RUNS];  // run lengths; upper bounds when n_dev is given
+    const uint64_t* n_dev;     // optional: the run lengths in device memory (written by an earlier kernel of the stream)
     uint32_t k;
 };
+__device__ __forceinline__ uint64_t run_len(const RunTable& rt, uint32_t j) { return rt.n_dev ? rt.n_dev[j] : rt.n[j]; }
+
+// Compaction of runs whose exact lengths are only known on the device (n_upper[j] >= n_dev[j]; launch sizes come from
+// the upper bounds, surplus tiles stay empty).  Used inside the library; arguments are checked by the caller.
+// Needs a workspace of lsm_compact_workspace_bytes(n_upper, k) bytes.
+int compact_device_lengths(const lsm_entry_t* const* ptr, const uint64_t* n_upper, const uint64_t* n_dev, uint32_t k, uint32_t flags,
+                           const lsm_out_t* out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace lsm

@@ -85,7 +85,7 @@ __global__ void init_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint64_
     for (uint64_t t = i; t < n_tiles; t += stride) ws.status[t] = 0;
     if (i < rt.k) {
         ws.splits[i] = 0;
-        ws.splits[n_tiles * rt.k + i] = rt.n[i];
+        ws.splits[n_tiles * rt.k + i] = run_len(rt, (uint32_t)i);
         ws.ycoarse[i] = 0;
         ws.ycoarse[(n_coarse + 1) * rt.k + i] = ws.st.m[i];
     }
@@ -238,7 +238,7 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
     const uint64_t b = g.slot + 1;
     const bool own = b < n_tiles && g.member < (int)rt.k;
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
-    const uint64_t best = select_split<false>(run, 0, own ? rt.n[g.member] : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
+    const uint64_t best = select_split<false>(run, 0, own ? run_len(rt, g.member) : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
@@ -982,43 +982,18 @@ extern "C" int lsm_compact_timed(const lsm_run_t* runs, uint32_t n_runs, uint32_
     return lsm_compact_remap(runs, n_runs, flags, out, workspace, workspace_bytes, stream_v, nullptr, ev);
 }
 
-extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
-                                 size_t workspace_bytes, void* stream_v, const lsm_remap_t* remap, const lsm_compact_events_t* ev) {
-    using namespace lsm;
-    if (remap != nullptr && remap->n_files != 0 && remap->base == nullptr) return LSM_ERR_NULL;
-    const uint64_t* remap_base = remap ? remap->base : nullptr;
-    const uint32_t remap_files = remap ? remap->n_files : 0;
-    if (runs == nullptr || out == nullptr || out->n_out == nullptr) return LSM_ERR_NULL;
-    if (n_runs == 0 || n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
-    RunTable rt;
-    rt.k = n_runs;
+namespace lsm {
+
+// Enqueues the kernels of one compaction.  rt.n are the run lengths the launch sizes are taken from.
+static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t* out, void* workspace, hipStream_t stream,
+                             const uint64_t* remap_base, uint32_t remap_files, const lsm_compact_events_t* ev) {
+    const uint32_t n_runs = rt.k;
     uint64_t total = 0;
-    for (uint32_t j = 0; j < LSM_MAX_RUNS; j++) {
-        rt.ptr[j] = nullptr;
-        rt.n[j] = 0;
-    }
-    for (uint32_t j = 0; j < n_runs; j++) {
-        if (runs[j].n > 0 && runs[j].entries == nullptr) return LSM_ERR_NULL;
-        if ((reinterpret_cast<uintptr_t>(runs[j].entries) & 63) != 0) return LSM_ERR_BAD_ARG;
-        rt.ptr[j] = runs[j].entries;
-        rt.n[j] = runs[j].n;
-        total += runs[j].n;
-    }
-    if (total > 0 && out->entries == nullptr) return LSM_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(out->entries) & 63) != 0) return LSM_ERR_BAD_ARG;
-    if (out->capacity < total) return LSM_ERR_CAPACITY;
-    if (out->fence_keys != nullptr && (out->fence_stride == 0 || (reinterpret_cast<uintptr_t>(out->fence_keys) & 15) != 0))
-        return LSM_ERR_BAD_ARG;
-    uint64_t lens[LSM_MAX_RUNS];
-    for (uint32_t j = 0; j < n_runs; j++) lens[j] = runs[j].n;
-    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
-        workspace_bytes < lsm_compact_workspace_bytes(lens, n_runs))
-        return LSM_ERR_WORKSPACE;
+    for (uint32_t j = 0; j < n_runs; j++) total += rt.n[j];
     const uint64_t n_tiles = tiles_for(total, n_runs);
     if (n_tiles >= (1ull << 31)) return LSM_ERR_BAD_ARG;
-    hipStream_t stream = static_cast<hipStream_t>(stream_v);
     Workspace ws;
-    carve(workspace, lens, n_runs, &ws);
+    carve(workspace, rt.n, n_runs, &ws);
     const uint64_t n_coarse = coarse_rows(n_tiles);  // boundaries kCoarseStride, 2 * kCoarseStride, ... < n_tiles
 
     uint32_t init_blocks = (uint32_t)((n_tiles + 255) / 256);
@@ -1079,6 +1054,60 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
         if (n == ~0ull) return LSM_ERR_INTERNAL;
     }
     return LSM_OK;
+}
+
+int compact_device_lengths(const lsm_entry_t* const* ptr, const uint64_t* n_upper, const uint64_t* n_dev, uint32_t k, uint32_t flags,
+                           const lsm_out_t* out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    if (k == 0 || k > LSM_MAX_RUNS || (flags & LSM_VALIDATE)) return LSM_ERR_BAD_ARG;
+    if (workspace == nullptr || workspace_bytes < lsm_compact_workspace_bytes(n_upper, k)) return LSM_ERR_WORKSPACE;
+    RunTable rt;
+    rt.k = k;
+    rt.n_dev = n_dev;
+    uint64_t total = 0;
+    for (uint32_t j = 0; j < LSM_MAX_RUNS; j++) {
+        rt.ptr[j] = j < k ? ptr[j] : nullptr;
+        rt.n[j] = j < k ? n_upper[j] : 0;
+        total += rt.n[j];
+    }
+    // with lengths that are only bounds the sampled partition would copy samples from beyond the runs' ends
+    if (tiles_for(total, k) >= kSampledMinTiles) return LSM_ERR_BAD_ARG;
+    return launch_compaction(rt, flags, out, workspace, stream, nullptr, 0, nullptr);
+}
+
+}  // namespace lsm
+
+extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
+                                 size_t workspace_bytes, void* stream_v, const lsm_remap_t* remap, const lsm_compact_events_t* ev) {
+    using namespace lsm;
+    if (remap != nullptr && remap->n_files != 0 && remap->base == nullptr) return LSM_ERR_NULL;
+    const uint64_t* remap_base = remap ? remap->base : nullptr;
+    const uint32_t remap_files = remap ? remap->n_files : 0;
+    if (runs == nullptr || out == nullptr || out->n_out == nullptr) return LSM_ERR_NULL;
+    if (n_runs == 0 || n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    RunTable rt;
+    rt.k = n_runs;
+    rt.n_dev = nullptr;
+    uint64_t total = 0;
+    for (uint32_t j = 0; j < LSM_MAX_RUNS; j++) {
+        rt.ptr[j] = nullptr;
+        rt.n[j] = 0;
+    }
+    for (uint32_t j = 0; j < n_runs; j++) {
+        if (runs[j].n > 0 && runs[j].entries == nullptr) return LSM_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(runs[j].entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+        rt.ptr[j] = runs[j].entries;
+        rt.n[j] = runs[j].n;
+        total += runs[j].n;
+    }
+    if (total > 0 && out->entries == nullptr) return LSM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(out->entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+    if (out->capacity < total) return LSM_ERR_CAPACITY;
+    if (out->fence_keys != nullptr && (out->fence_stride == 0 || (reinterpret_cast<uintptr_t>(out->fence_keys) & 15) != 0))
+        return LSM_ERR_BAD_ARG;
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
+        workspace_bytes < lsm_compact_workspace_bytes(rt.n, n_runs))
+        return LSM_ERR_WORKSPACE;
+    return launch_compaction(rt, flags, out, workspace, static_cast<hipStream_t>(stream_v), remap_base, remap_files, ev);
 }
 
 // ---------------------------------------------------------------------------------------

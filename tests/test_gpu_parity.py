@@ -412,7 +412,10 @@ def test_probe_length_on_data_with_holes(g, oracle):
 
 
 # ------------------------------------------------------------------ write-buffer flush (section 2.2)
-@pytest.mark.parametrize("n,n_keys", [(0, 10), (1, 10), (255, 40), (256, 4000), (3600, 3000), (3600, 50), (10000, 100000)])
+@pytest.mark.parametrize("n,n_keys", [(0, 10), (1, 10), (255, 40), (256, 4000), (3600, 3000), (3600, 50), (8192, 6000),
+                                      # beyond 8,192 entries: sorted segments of 4,096, merged by the compaction kernels
+                                      (8193, 5000), (10000, 100000), (50000, 40), (100000, 30000), (20000, 10 ** 7),
+                                      (262144, 200000)])
 def test_flush_of_the_write_buffer(g, oracle, n, n_keys):
     """Unsorted entries with repeated keys and repeated seqnos -> the checker's sorted run, with its fence index."""
     print("flush", n, n_keys, flush=True)

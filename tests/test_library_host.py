@@ -68,7 +68,8 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     table = B._Remap(None, 3)
     assert lib.lsm_compact_remap(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 1 << 20, None, C.byref(table), None) == -1
     assert lib.lsm_flush_workspace_bytes(3600) == 14400 and lib.lsm_flush_workspace_bytes(1 << 20) == 0
-    assert lib.lsm_flush_buffer(64 * 10, 70000, C.byref(big), 256, 1 << 20, None) == -2   # too many entries
+    assert 64 * 100000 < lib.lsm_flush_workspace_bytes(100000) < 80 * 100000   # sorted segments + merge workspace
+    assert lib.lsm_flush_buffer(64 * 10, 300000, C.byref(big), 256, 1 << 20, None) == -2  # too many entries
     assert lib.lsm_flush_buffer(None, 5, C.byref(big), 256, 1 << 20, None) == -1
     assert lib.lsm_flush_buffer(64 * 10, 11, C.byref(big), 256, 1 << 20, None) == -3      # capacity 10
     assert lib.lsm_flush_buffer(64 * 10, 10, C.byref(big), 256, 8, None) == -4            # workspace
