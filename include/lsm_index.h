@@ -78,6 +78,7 @@ enum {
     LSM_MAX_RUNS = 64,          /* runs per lsm_compact call and per lsm_tree_t            */
     LSM_MAX_BLOCKS = 256,       /* block keys per probe request                            */
     LSM_MAX_BUFFER = 262144,    /* entries per lsm_flush_buffer call                       */
+    LSM_RANGE_MAX_ENTRIES = 2048, /* entries one range of lsm_range_scan may hold (all versions) */
     LSM_KEY_BYTES = 32,
     LSM_STATIC_SCRATCH_BYTES = 8 << 20, /* scratch held inside the library for lsm_compact_static      */
     LSM_DEFAULT_FENCE_STRIDE = 64 /* one fence per 4 KiB page of entries                   */
@@ -302,6 +303,57 @@ int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* tree, uint3
  * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG, LSM_ERR_HIP.
  */
 int lsm_range_bounds(const lsm_tree_t* tree, const uint8_t* lo_key, const uint8_t* hi_key, uint64_t* bounds_out, void* stream);
+
+/*
+ * lsm_range_scan -- the content of many key ranges in one call (appendix B, get_batch: range scans over the index give
+ * the keys of the cached blocks under a prefix and the places of their tensors; section 2.2, range lookups).
+ * For range i, [lo_keys[i], hi_keys[i]): the entries of the tree whose key lies in the range, newest version of each
+ * key, live PUTs only, ascending - what a last-level lsm_compact of the runs cut to the range gives.  They are written
+ * to out->entries[i * max_entries ...] (whole 64-byte entries: key, value pointer and length make the read list for
+ * the tensor files) and their number to out->counts[i].  One workgroup handles one range: it finds the range in every
+ * run and merges the pieces like a tile of a compaction.  A range whose pieces hold more than LSM_RANGE_MAX_ENTRIES
+ * entries in all, or whose result has more than max_entries, gets counts[i] = LSM_RANGE_OVERFLOW and nothing
+ * meaningful in its slot: use lsm_range_bounds and lsm_compact for it.  lo >= hi is an empty range.
+ * lo_keys, hi_keys: DEVICE, n_ranges x 32 bytes, 16-byte aligned.  entries: DEVICE, 64-byte aligned,
+ * n_ranges x max_entries entries.  counts: DEVICE, n_ranges.  Fence indices and filters of the tree are not used.
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (max_entries == 0 or > LSM_RANGE_MAX_ENTRIES, misaligned), LSM_ERR_HIP.
+ */
+typedef struct {
+    const uint8_t* lo_keys;
+    const uint8_t* hi_keys;
+    uint32_t n_ranges;
+    uint32_t max_entries; /* slot pitch of the result, in entries */
+} lsm_ranges_t;
+
+typedef struct {
+    lsm_entry_t* entries;
+    uint32_t* counts;
+} lsm_range_out_t;
+
+#define LSM_RANGE_OVERFLOW 0xFFFFFFFFu
+
+int lsm_range_scan(const lsm_ranges_t* ranges, const lsm_tree_t* tree, const lsm_range_out_t* out, void* stream);
+
+/*
+ * lsm_compact_batch -- many independent small compactions in one call (section 2.2: the flush / compaction cycle of
+ * the small upper levels; with several trees or key-range shards their compactions do not depend on each other).
+ * Job j merges jobs[j].runs into jobs[j].out exactly as lsm_compact would with jobs[j].flags; all jobs share two
+ * kernel launches (one partition, one tile merge), and every job's count goes to its own out.n_out on the device.
+ * Restrictions: LSM_VALIDATE and out.fence_keys are not supported here; a job of 2048 tiles or more (about 4 million
+ * entries) is rejected with LSM_ERR_BAD_ARG - use lsm_compact for it.  Inputs and outputs of different jobs must not
+ * overlap.  jobs, and the run arrays they point to: HOST, read during the call.  workspace: DEVICE, 256-byte
+ * aligned, lsm_compact_batch_workspace_bytes(jobs, n_jobs) bytes (0 on bad arguments); the call copies a table of
+ * the jobs into it.  Errors as lsm_compact.
+ */
+typedef struct {
+    const lsm_run_t* runs; /* HOST array of n_runs descriptors */
+    uint32_t n_runs;
+    uint32_t flags;
+    lsm_out_t out;
+} lsm_compact_job_t;
+
+size_t lsm_compact_batch_workspace_bytes(const lsm_compact_job_t* jobs, uint32_t n_jobs);
+int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Cost model of the adaptive controller (host only, double arithmetic).

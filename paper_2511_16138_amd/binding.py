@@ -76,6 +76,18 @@ class _Remap(C.Structure):
     _fields_ = [("base", C.c_void_p), ("n_files", C.c_uint32)]
 
 
+class _Ranges(C.Structure):
+    _fields_ = [("lo_keys", C.c_void_p), ("hi_keys", C.c_void_p), ("n_ranges", C.c_uint32), ("max_entries", C.c_uint32)]
+
+
+class _RangeOut(C.Structure):
+    _fields_ = [("entries", C.c_void_p), ("counts", C.c_void_p)]
+
+
+class _CompactJob(C.Structure):
+    _fields_ = [("runs", C.POINTER(_Run)), ("n_runs", C.c_uint32), ("flags", C.c_uint32), ("out", _Out)]
+
+
 class _PolicyInput(C.Structure):
     _fields_ = [("w", C.c_double), ("s", C.c_double), ("r", C.c_double), ("z", C.c_double), ("n_entries", C.c_uint64),
                 ("buffer_entries", C.c_uint64), ("B", C.c_double), ("p", C.c_double), ("d", C.c_double)]
@@ -118,6 +130,12 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_probe_length.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.c_void_p, C.c_void_p]
     L.lsm_range_bounds.restype = C.c_int
     L.lsm_range_bounds.argtypes = [C.POINTER(_Tree), C.c_char_p, C.c_char_p, C.c_void_p, C.c_void_p]
+    L.lsm_range_scan.restype = C.c_int
+    L.lsm_range_scan.argtypes = [C.POINTER(_Ranges), C.POINTER(_Tree), C.POINTER(_RangeOut), C.c_void_p]
+    L.lsm_compact_batch_workspace_bytes.restype = C.c_size_t
+    L.lsm_compact_batch_workspace_bytes.argtypes = [C.POINTER(_CompactJob), C.c_uint32]
+    L.lsm_compact_batch.restype = C.c_int
+    L.lsm_compact_batch.argtypes = [C.POINTER(_CompactJob), C.c_uint32, C.c_void_p, C.c_size_t, C.c_void_p]
     L.lsm_policy_levels.restype = C.c_uint32
     L.lsm_policy_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
     L.lsm_policy_cost.restype = C.c_double
@@ -306,6 +324,60 @@ def lsm_range_bounds(tree: Sequence[TreeRun], lo_key: bytes, hi_key: bytes, stre
     if rc != 0:
         raise LsmError(rc, "lsm_range_bounds")
     return out
+
+
+LSM_RANGE_OVERFLOW = 0xFFFFFFFF
+LSM_RANGE_MAX_ENTRIES = 2048
+
+
+def lsm_range_scan(tree: Sequence[TreeRun], lo_keys: torch.Tensor, hi_keys: torch.Tensor, max_entries: int = 256,
+                   entries: Optional[torch.Tensor] = None, counts: Optional[torch.Tensor] = None, stream=None
+                   ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Live content of the key ranges [lo_keys[i], hi_keys[i]) (int64 [n, 4] key tensors on the GPU).  Returns
+    (entries int64 [n, max_entries, 8], counts int64 [n]); counts[i] == LSM_RANGE_OVERFLOW marks a range that did not
+    fit (more than 2048 entries in its pieces, or more than max_entries results)."""
+    L = _load()
+    n = int(_dev(lo_keys, "lo_keys").shape[0])
+    assert tuple(_dev(hi_keys, "hi_keys").shape) == tuple(lo_keys.shape) and lo_keys.shape[1] == 4
+    dev = lo_keys.device
+    if entries is None:
+        entries = torch.empty((n, max_entries, 8), dtype=torch.int64, device=dev)
+    raw = torch.empty(n, dtype=torch.int32, device=dev) if counts is None else counts
+    td, _keep = _tree_descriptor(tree)
+    rd = _Ranges(lo_keys.data_ptr(), hi_keys.data_ptr(), n, max_entries)
+    od = _RangeOut(_dev(entries, "entries").data_ptr(), _dev(raw, "counts").data_ptr())
+    rc = L.lsm_range_scan(C.byref(rd), C.byref(td), C.byref(od), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_range_scan")
+    return entries, (raw.to(torch.int64) & 0xFFFFFFFF) if counts is None else raw
+
+
+def lsm_compact_batch(jobs: Sequence[Tuple[Sequence[torch.Tensor], int]], stream=None
+                      ) -> Tuple[List[torch.Tensor], torch.Tensor]:
+    """Many independent small compactions in one call.  jobs = [(runs, flags), ...].  Returns (outs, n_out): outs[j] is
+    int64 [capacity_j, 8] (a slice of one allocation), n_out int64 [n_jobs] on the device."""
+    L = _load()
+    n_jobs = len(jobs)
+    dev = next((r.device for runs, _ in jobs for r in runs), torch.device("cuda"))
+    totals = [sum(int(r.shape[0]) for r in runs) for runs, _ in jobs]
+    out_all = torch.empty((max(sum(totals), 1), 8), dtype=torch.int64, device=dev)
+    n_out = torch.empty(max(n_jobs, 1), dtype=torch.int64, device=dev)
+    outs, keep, jd, at = [], [], (_CompactJob * max(1, n_jobs))(), 0
+    for j, ((runs, flags), total) in enumerate(zip(jobs, totals)):
+        rd = (_Run * max(1, len(runs)))(*[_Run(_dev(r, "run").data_ptr(), int(r.shape[0])) for r in runs])
+        keep.append(rd)
+        outs.append(out_all[at:at + total])
+        jd[j].runs, jd[j].n_runs, jd[j].flags = rd, len(runs), flags
+        jd[j].out = _Out(out_all.data_ptr() + at * 64, total, n_out.data_ptr() + 8 * j, None, 0)
+        at += total
+    need = int(L.lsm_compact_batch_workspace_bytes(jd, n_jobs)) if n_jobs else 0
+    if n_jobs and need == 0:
+        raise LsmError(-2, "lsm_compact_batch_workspace_bytes")
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    rc = L.lsm_compact_batch(jd, n_jobs, ws.data_ptr(), ws.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_compact_batch")
+    return outs, n_out[:n_jobs]
 
 
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],

@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <mutex>
+#include <vector>
 
 #include "lsm_common.h"
 
@@ -354,11 +355,46 @@ struct MergeShared {
     uint64_t lo[LSM_MAX_RUNS];       // first entry of each run's piece
     const lsm_entry_t* run[LSM_MAX_RUNS];  // copy of the run pointers (indexed per lane)
     uint32_t wave_count[kMergeThreads / kWave];
-    uint32_t tile;
+    uint32_t tile;                   // number of the tile inside its compaction (what the look-back counts in)
     uint32_t n;
     uint32_t failed;
     uint32_t inexact;                // some position has an equal surrogate but a different key tail
     uint64_t base;
+    // batched compactions only: what the single form takes from its kernel arguments
+    uint32_t k, flags, job_tiles;
+    lsm_entry_t* out;
+    uint64_t* n_out;
+    uint64_t* status;
+};
+
+// The tile kernel has three forms.  Single: one compaction, tile = workgroup, pieces from the split table.
+// Range: one tile per key range of a tree - the pieces are the parts of the runs inside the range, found by the
+// tile itself, and the survivors go to a fixed slot of the result (no look-back).  Batch: many independent
+// compactions in one launch - the workgroup looks up its job, and everything the single form takes from kernel
+// arguments comes from the job's descriptor.
+enum : int { kModeSingle = 0, kModeRange = 1, kModeBatch = 2 };
+
+struct JobDesc {       // one compaction of a batch (device memory, written by the host)
+    uint64_t first_tile;   // number of its first tile in the launch
+    uint64_t run_off;      // where its runs start in the run pointer / length arrays
+    uint64_t splits_off;   // where its split table starts (in 64-bit words)
+    lsm_entry_t* out;
+    uint64_t* n_out;
+    uint32_t n_tiles, k, flags, pad;
+};
+static_assert(sizeof(JobDesc) == 56, "descriptor layout");
+
+struct ModeArgs {
+    // range form
+    const uint8_t* lo_keys;   // [n_tiles x 32]
+    const uint8_t* hi_keys;
+    uint32_t* counts;         // [n_tiles]
+    uint32_t max_entries;     // slot pitch of the result
+    // batch form
+    const uint32_t* tile_job;             // [n_tiles] job of every tile
+    const JobDesc* jobs;
+    const lsm_entry_t* const* run_ptr;    // runs of all jobs
+    const uint64_t* run_n;
 };
 
 struct Sur {  // hi = key bytes 0..7, lo = key bytes 8..13 << 16 | index
@@ -464,18 +500,32 @@ __device__ __forceinline__ bool tail_less(const uint4 a0, const uint4 a1, const 
     return __builtin_bswap64(((uint64_t)a1.w << 32) | a1.z) < __builtin_bswap64(((uint64_t)b1.w << 32) | b1.z);
 }
 
+// Lower bound of `key` in run[from, n) for a range that is expected to end soon after `from`: doubling steps from
+// `from` until a record >= key (or the end) is found, then bisection inside the last step.
+__device__ __forceinline__ uint64_t lower_bound_from(const lsm_entry_t* run, uint64_t from, uint64_t n, const Key& key) {
+    uint64_t lo = from, step = 16;
+    while (lo < n) {
+        const uint64_t at = lo + step - 1 < n ? lo + step - 1 : n - 1;  // last record of the step
+        if (!key_less(load_key(run + at), key)) {
+            bool eq;
+            return lower_bound_eq(run, lo, at, key, eq);
+        }
+        lo = at + 1;
+        step <<= 1;
+    }
+    return n;
+}
+
 // two workgroups per compute unit = four waves per SIMD: at most 128 vector registers.
 // kExtras: the output pass also rewrites value pointers and / or writes the fence index (compiled out otherwise).
-template <bool kExtras>
-__global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags,
-                                                               lsm_entry_t* out, uint64_t* n_out, const uint64_t* remap_base,
-                                                               uint32_t remap_files, uint4* fence_out, uint32_t fence_stride) {
+template <bool kExtras, int kMode>
+__global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags_arg,
+                                                               lsm_entry_t* out_arg, uint64_t* n_out_arg, const uint64_t* remap_base,
+                                                               uint32_t remap_files, uint4* fence_out, uint32_t fence_stride, ModeArgs ma) {
     __shared__ MergeShared s;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
-    const uint32_t k = rt.k;
-    const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
     // ---- the tile's k pieces, by wave 0.  Tile number = workgroup number: the look-back below waits only for
     //      tiles with smaller numbers, and workgroups are handed to the compute units in ascending order, so the
@@ -485,16 +535,48 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     //      are bounded in any case.
     if (wave == 0) {
         __builtin_amdgcn_s_setprio(3);  // the other waves wait for this one: let it issue first
-        const uint64_t t = blockIdx.x;
+        uint64_t t = blockIdx.x;        // tile number inside its compaction
+        uint32_t kk = rt.k;
         uint64_t a = 0, b = 0;
-        const bool mine = lane < (int)k;
-        if (mine) {
-            a = ws.splits[t * k + lane];
-            b = ws.splits[(t + 1) * k + lane];
-            s.run[lane] = rt.ptr[lane];
+        if (kMode == kModeSingle) {
+            if (lane < (int)kk) {
+                a = ws.splits[t * kk + lane];
+                b = ws.splits[(t + 1) * kk + lane];
+                s.run[lane] = rt.ptr[lane];
+            }
+        } else if (kMode == kModeRange) {
+            // the part of every run inside [lo_key, hi_key): lane j searches run j
+            const Key lo_key = load_key(ma.lo_keys + t * LSM_KEY_BYTES), hi_key = load_key(ma.hi_keys + t * LSM_KEY_BYTES);
+            if (lane < (int)kk) {
+                const lsm_entry_t* run = rt.ptr[lane];
+                const uint64_t len = rt.n[lane];
+                bool eq;
+                a = len ? lower_bound_eq(run, 0, len, lo_key, eq) : 0;
+                b = key_less(lo_key, hi_key) ? lower_bound_from(run, a, len, hi_key) : a;
+                s.run[lane] = run;
+            }
+        } else {
+            const JobDesc d = ma.jobs[ma.tile_job[t]];  // the same words for every lane
+            kk = d.k;
+            t -= d.first_tile;
+            if (lane < (int)kk) {
+                a = ws.splits[d.splits_off + t * kk + lane];
+                b = ws.splits[d.splits_off + (t + 1) * kk + lane];
+                s.run[lane] = ma.run_ptr[d.run_off + lane];
+            }
+            if (lane == 0) {
+                s.k = kk;
+                s.flags = d.flags;
+                s.job_tiles = d.n_tiles;
+                s.out = d.out;
+                s.n_out = d.n_out;
+                s.status = ws.status + d.first_tile;
+            }
         }
+        const bool mine = lane < (int)kk;
         // piece lengths -> offsets (inclusive scan over the lanes); split rows never exceed the run
         // lengths, and only inputs that break the precondition can make a row pair inconsistent
+        // (a key range may simply hold more than a tile: reported as an overflow of that range)
         const bool bad = mine && (b < a || b - a > (uint64_t)kTileCap);
         uint32_t incl = (mine && !bad) ? (uint32_t)(b - a) : 0;
         for (int off = 1; off < kWave; off <<= 1) {
@@ -518,8 +600,14 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     }
     __syncthreads();
     const uint64_t tile = s.tile;
-    if (tile >= n_tiles) return;  // cannot happen: the grid has exactly n_tiles workgroups
+    if (blockIdx.x >= n_tiles) return;  // cannot happen: the grid has exactly n_tiles workgroups
     const uint32_t n = s.n;
+    const uint32_t k = kMode == kModeBatch ? s.k : rt.k;
+    const uint32_t flags = kMode == kModeBatch ? s.flags : flags_arg;
+    lsm_entry_t* const out = kMode == kModeBatch ? s.out : out_arg;
+    uint64_t* const n_out = kMode == kModeBatch ? s.n_out : n_out_arg;
+    const uint64_t last_tile = kMode == kModeBatch ? (uint64_t)s.job_tiles - 1 : n_tiles - 1;
+    const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
     // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
     // the few instructions of a memory phase should not queue behind the other workgroup's merge arithmetic
@@ -865,7 +953,15 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     if (wave == 0) {
         __builtin_amdgcn_s_setprio(3);  // the stores of the whole tile wait for this wave
         bool failed;
-        uint64_t base = lookback(ws.status, tile, total, s.failed != 0, &failed);
+        uint64_t base;
+        if (kMode == kModeRange) {
+            // a range has its own slot of max_entries entries; one that holds more (or more than a tile) is reported
+            base = tile * (uint64_t)ma.max_entries;
+            failed = s.failed != 0 || total > ma.max_entries;
+            if (lane == 0) ma.counts[tile] = failed ? ~0u : total;
+        } else {
+            base = lookback(kMode == kModeBatch ? s.status : ws.status, tile, total, s.failed != 0, &failed);
+        }
         if (lane == 0) {
             s.base = base;
             if (failed) s.failed = 1;
@@ -900,7 +996,7 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         if (first == 0) {
             const bool failed = s.failed != 0;
             base = s.base;
-            if (tile == n_tiles - 1 && tid == 0) *n_out = failed ? ~0ull : base + total;
+            if (kMode != kModeRange && tile == last_tile && tid == 0) *n_out = failed ? ~0ull : base + total;
             if (failed) return;
         }
         const uint32_t count = min(total - first, (uint32_t)kStageEntries);
@@ -918,6 +1014,32 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
         first += kStageEntries;
         if (first < total) __syncthreads();  // the stage is reused
     } while (first < total);
+}
+
+// ---------------------------------------------------------------------------------------
+// Partition of a batch of independent compactions: one group of lanes per tile of the launch.  The group of a
+// job's tile number t > 0 searches boundary t over the job's whole runs (the jobs of a batch are small); the groups
+// of a job's first and last tile also write the first (all zero) and the last (run lengths) row of its split table,
+// and every group clears its tile's status word.
+// ---------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) partition_batch_kernel(Workspace ws, ModeArgs ma, uint64_t n_tiles, int group) {
+    const GroupLane g = group_lane(group);
+    const bool live = g.slot < n_tiles;
+    JobDesc d = {};
+    if (live) d = ma.jobs[ma.tile_job[g.slot]];
+    const uint64_t t = live ? g.slot - d.first_tile : 0;
+    const bool own = live && g.member < (int)d.k;
+    const lsm_entry_t* run = own ? ma.run_ptr[d.run_off + g.member] : nullptr;
+    const uint64_t len = own ? ma.run_n[d.run_off + g.member] : 0;
+    const bool search = t > 0;  // the same for all lanes of a group
+    const uint64_t best = select_split<false>(run, 0, (own && search) ? len : 0, t * tile_nominal(d.k ? d.k : 1), own && search, g.member,
+                                              group, g.group_base);
+    if (own) {
+        uint64_t* rows = ws.splits + d.splits_off;
+        rows[t * d.k + g.member] = search ? best : 0;
+        if (t + 1 == d.n_tiles) rows[(t + 1) * d.k + g.member] = len;
+    }
+    if (live && g.member == 0) ws.status[g.slot] = 0;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1038,11 +1160,11 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
         uint4* const fence_out = reinterpret_cast<uint4*>(out->fence_keys);
         const uint32_t fence_stride = out->fence_keys ? out->fence_stride : 1u;
         if (remap_files != 0 || fence_out != nullptr)
-            hipLaunchKernelGGL(merge_kernel<true>, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
-                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride);
+            hipLaunchKernelGGL((merge_kernel<true, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride, ModeArgs{});
         else
-            hipLaunchKernelGGL(merge_kernel<false>, dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
-                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride);
+            hipLaunchKernelGGL((merge_kernel<false, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride, ModeArgs{});
     }
     if (ev && ev->after_merge && hipEventRecord(static_cast<hipEvent_t>(ev->after_merge), stream) != hipSuccess)
         return LSM_ERR_HIP;
@@ -1108,6 +1230,173 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
         workspace_bytes < lsm_compact_workspace_bytes(rt.n, n_runs))
         return LSM_ERR_WORKSPACE;
     return launch_compaction(rt, flags, out, workspace, static_cast<hipStream_t>(stream_v), remap_base, remap_files, ev);
+}
+
+// ---------------------------------------------------------------------------------------
+// lsm_range_scan: the live content of many key ranges of a tree, one tile per range.
+// ---------------------------------------------------------------------------------------
+extern "C" int lsm_range_scan(const lsm_ranges_t* ranges, const lsm_tree_t* tree, const lsm_range_out_t* out, void* stream_v) {
+    using namespace lsm;
+    if (ranges == nullptr || tree == nullptr || out == nullptr) return LSM_ERR_NULL;
+    if (ranges->max_entries == 0 || ranges->max_entries > LSM_RANGE_MAX_ENTRIES || tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    if (ranges->n_ranges == 0) return LSM_OK;
+    if (ranges->lo_keys == nullptr || ranges->hi_keys == nullptr || out->entries == nullptr || out->counts == nullptr) return LSM_ERR_NULL;
+    if (((reinterpret_cast<uintptr_t>(ranges->lo_keys) | reinterpret_cast<uintptr_t>(ranges->hi_keys)) & 15) != 0 ||
+        (reinterpret_cast<uintptr_t>(out->entries) & 63) != 0)
+        return LSM_ERR_BAD_ARG;
+    if (tree->n_runs > 0 && tree->runs == nullptr) return LSM_ERR_NULL;
+    RunTable rt;
+    rt.k = tree->n_runs ? tree->n_runs : 1;  // a tree without runs: one empty run
+    rt.n_dev = nullptr;
+    for (uint32_t j = 0; j < LSM_MAX_RUNS; j++) {
+        rt.ptr[j] = nullptr;
+        rt.n[j] = 0;
+    }
+    for (uint32_t j = 0; j < tree->n_runs; j++) {
+        const lsm_run_t& r = tree->runs[j].run;
+        if (r.n > 0 && r.entries == nullptr) return LSM_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(r.entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+        rt.ptr[j] = r.entries;
+        rt.n[j] = r.n;
+    }
+    ModeArgs ma = {};
+    ma.lo_keys = ranges->lo_keys;
+    ma.hi_keys = ranges->hi_keys;
+    ma.counts = out->counts;
+    ma.max_entries = ranges->max_entries;
+    Workspace ws = {};
+    hipLaunchKernelGGL((merge_kernel<false, kModeRange>), dim3(ranges->n_ranges), dim3(kMergeThreads), 0, static_cast<hipStream_t>(stream_v), rt, ws,
+                       (uint64_t)ranges->n_ranges, (uint32_t)LSM_BOTTOMMOST, out->entries, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u,
+                       (uint4*)nullptr, 1u, ma);
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+}
+
+// ---------------------------------------------------------------------------------------
+// lsm_compact_batch: many independent small compactions in two launches.
+// Workspace: tile status words | split tables of all jobs | the table the host builds (job of every tile, job
+// descriptors, run pointers, run lengths).
+// ---------------------------------------------------------------------------------------
+namespace lsm {
+struct BatchLayout {
+    uint64_t tiles, split_words, runs;
+    size_t status, splits, tile_job, jobs, run_ptr, run_n, total;
+    uint32_t k_max;
+};
+static int batch_layout(const lsm_compact_job_t* jobs, uint32_t n_jobs, BatchLayout* l) {
+    l->tiles = l->split_words = l->runs = 0;
+    l->k_max = 1;
+    for (uint32_t j = 0; j < n_jobs; j++) {
+        const lsm_compact_job_t& job = jobs[j];
+        if (job.runs == nullptr) return LSM_ERR_NULL;
+        if (job.n_runs == 0 || job.n_runs > LSM_MAX_RUNS || (job.flags & LSM_VALIDATE) || job.out.fence_keys != nullptr) return LSM_ERR_BAD_ARG;
+        uint64_t total = 0;
+        for (uint32_t r = 0; r < job.n_runs; r++) total += job.runs[r].n;
+        uint64_t nt = tiles_for(total, job.n_runs);
+        if (nt >= kSampledMinTiles) return LSM_ERR_BAD_ARG;  // a large compaction: lsm_compact
+        if (nt == 0) nt = 1;                                  // an empty job keeps one (empty) tile, which writes its count
+        l->tiles += nt;
+        l->split_words += (nt + 1) * job.n_runs;
+        l->runs += job.n_runs;
+        if (job.n_runs > l->k_max) l->k_max = job.n_runs;
+    }
+    if (l->tiles >= (1ull << 31)) return LSM_ERR_BAD_ARG;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align256(bytes);
+        return at;
+    };
+    l->status = take(l->tiles * sizeof(uint64_t));
+    l->splits = take(l->split_words * sizeof(uint64_t));
+    l->tile_job = take(l->tiles * sizeof(uint32_t));  // from here on: written by the host, one copy
+    l->jobs = take((size_t)n_jobs * sizeof(JobDesc));
+    l->run_ptr = take(l->runs * sizeof(void*));
+    l->run_n = take(l->runs * sizeof(uint64_t));
+    l->total = off;
+    return LSM_OK;
+}
+}  // namespace lsm
+
+extern "C" size_t lsm_compact_batch_workspace_bytes(const lsm_compact_job_t* jobs, uint32_t n_jobs) {
+    lsm::BatchLayout l;
+    if (jobs == nullptr || n_jobs == 0 || lsm::batch_layout(jobs, n_jobs, &l) != LSM_OK) return 0;
+    return l.total;
+}
+
+extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs, void* workspace, size_t workspace_bytes, void* stream_v) {
+    using namespace lsm;
+    if (n_jobs == 0) return LSM_OK;
+    if (jobs == nullptr) return LSM_ERR_NULL;
+    BatchLayout l;
+    const int rc = batch_layout(jobs, n_jobs, &l);
+    if (rc != LSM_OK) return rc;
+    for (uint32_t j = 0; j < n_jobs; j++) {
+        const lsm_compact_job_t& job = jobs[j];
+        uint64_t total = 0;
+        for (uint32_t r = 0; r < job.n_runs; r++) {
+            if (job.runs[r].n > 0 && job.runs[r].entries == nullptr) return LSM_ERR_NULL;
+            if ((reinterpret_cast<uintptr_t>(job.runs[r].entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+            total += job.runs[r].n;
+        }
+        if (job.out.n_out == nullptr || (total > 0 && job.out.entries == nullptr)) return LSM_ERR_NULL;
+        if ((reinterpret_cast<uintptr_t>(job.out.entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+        if (job.out.capacity < total) return LSM_ERR_CAPACITY;
+    }
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < l.total) return LSM_ERR_WORKSPACE;
+    // the host's table: kept per thread until the next call, copied in one piece
+    static thread_local std::vector<unsigned char> table;
+    const size_t table_bytes = l.total - l.tile_job;
+    table.assign(table_bytes, 0);
+    uint32_t* tile_job = reinterpret_cast<uint32_t*>(table.data());
+    JobDesc* desc = reinterpret_cast<JobDesc*>(table.data() + (l.jobs - l.tile_job));
+    const lsm_entry_t** run_ptr = reinterpret_cast<const lsm_entry_t**>(table.data() + (l.run_ptr - l.tile_job));
+    uint64_t* run_n = reinterpret_cast<uint64_t*>(table.data() + (l.run_n - l.tile_job));
+    uint64_t tile = 0, split_word = 0, run = 0;
+    for (uint32_t j = 0; j < n_jobs; j++) {
+        const lsm_compact_job_t& job = jobs[j];
+        uint64_t total = 0;
+        for (uint32_t r = 0; r < job.n_runs; r++) {
+            run_ptr[run + r] = job.runs[r].entries;
+            run_n[run + r] = job.runs[r].n;
+            total += job.runs[r].n;
+        }
+        uint64_t nt = tiles_for(total, job.n_runs);
+        if (nt == 0) nt = 1;
+        JobDesc& d = desc[j];
+        d.first_tile = tile;
+        d.run_off = run;
+        d.splits_off = split_word;
+        d.out = job.out.entries;
+        d.n_out = job.out.n_out;
+        d.n_tiles = (uint32_t)nt;
+        d.k = job.n_runs;
+        d.flags = job.flags;
+        d.pad = 0;
+        for (uint64_t t = 0; t < nt; t++) tile_job[tile + t] = j;
+        tile += nt;
+        split_word += (nt + 1) * job.n_runs;
+        run += job.n_runs;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    char* base = static_cast<char*>(workspace);
+    if (hipMemcpyAsync(base + l.tile_job, table.data(), table_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return LSM_ERR_HIP;
+    Workspace ws = {};
+    ws.status = reinterpret_cast<uint64_t*>(base + l.status);
+    ws.splits = reinterpret_cast<uint64_t*>(base + l.splits);
+    ModeArgs ma = {};
+    ma.tile_job = reinterpret_cast<const uint32_t*>(base + l.tile_job);
+    ma.jobs = reinterpret_cast<const JobDesc*>(base + l.jobs);
+    ma.run_ptr = reinterpret_cast<const lsm_entry_t* const*>(base + l.run_ptr);
+    ma.run_n = reinterpret_cast<const uint64_t*>(base + l.run_n);
+    int group = 1;
+    while (group < (int)l.k_max) group <<= 1;
+    const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);
+    hipLaunchKernelGGL(partition_batch_kernel, dim3((uint32_t)((l.tiles + per_block - 1) / per_block)), dim3(256), 0, stream, ws, ma, l.tiles, group);
+    RunTable rt = {};
+    rt.k = 1;
+    hipLaunchKernelGGL((merge_kernel<false, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
+                       (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }
 
 // ---------------------------------------------------------------------------------------

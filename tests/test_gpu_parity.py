@@ -464,3 +464,104 @@ def test_range_scan_equals_filtered_compaction(g, oracle, cfg1):
         got = range_scan(tree, lo, hi)
         torch.cuda.synchronize()
         assert np.array_equal(as_bytes(got).reshape(-1, 64), want)
+
+
+def _keys_tensor(keys):
+    a = np.frombuffer(b"".join(keys), dtype=np.uint8).reshape(-1, 32).copy()
+    return torch.from_numpy(a.view(np.int64).reshape(-1, 4)).to(dev())
+
+
+@pytest.mark.parametrize("which", ["config1", "tiered16"])
+def test_batched_range_scans(g, oracle, cfg1, which):
+    """Many key ranges in one call (appendix B, get_batch): every range's entries equal the checker's last-level
+    compaction of all runs cut to the range - families, ranges between stored keys, single keys, empty and inverted
+    ranges, keys outside the tree; ranges too large for their slot or for a tile are reported as overflow."""
+    from workloads import lsm
+    print("batched range scans", which, flush=True)
+    w = cfg1 if which == "config1" else lsm.config3(device=dev(), scale=256)
+    tree = build_tree(g, w.runs)
+    full = oracle.compact([r.cpu() for r in w.runs], 1)
+    keys = [bytes(k) for k in full[:, :32]]
+    run_keys = [[bytes(k) for k in as_bytes(r).reshape(-1, 64)[:, :32]] for r in w.runs]
+    all_in = sorted({k for rk in run_keys for k in rk})  # every version's key, dead ones too
+    rs = np.random.RandomState(11)
+    ranges = []
+    for i in rs.randint(0, len(keys), size=300):          # the family of a stored key: all keys with the same first 8 bytes
+        fam = keys[i][:8]
+        ranges.append((fam + bytes(24), fam + b"\xff" * 24))
+    for i in rs.randint(0, len(keys) - 300, size=200):    # between two stored keys, a few to a few hundred entries apart
+        ranges.append((keys[i], keys[i + int(rs.randint(0, 300))]))
+    for i in rs.randint(0, len(all_in), size=100):        # exactly one key, live or not
+        k = all_in[i]
+        ranges.append((k, (int.from_bytes(k, "big") + 1).to_bytes(32, "big")))
+    ranges += [(keys[7], keys[7]), (keys[50], keys[10]), (bytes(32), keys[0]), (keys[-1], b"\xff" * 32),
+               (b"\xff" * 32, b"\xff" * 32), (bytes(32), bytes(32))]
+    ranges += [(bytes(32), b"\xff" * 32), (keys[0], keys[len(keys) // 2])]   # far more than a tile: overflow
+    import bisect
+    max_entries = 512
+    ent, cnt = g.lsm_range_scan(tree, _keys_tensor([lo for lo, _ in ranges]), _keys_tensor([hi for _, hi in ranges]), max_entries)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy()
+    got = as_bytes(ent).reshape(len(ranges), max_entries, 64)
+    n_over = 0
+    for i, (lo, hi) in enumerate(ranges):
+        a, b = (bisect.bisect_left(keys, lo), bisect.bisect_left(keys, hi)) if lo < hi else (0, 0)
+        in_pieces = sum(bisect.bisect_left(rk, hi) - bisect.bisect_left(rk, lo) for rk in run_keys) if lo < hi else 0
+        if b - a > max_entries or in_pieces > 2048:   # more results than the slot, or more entries (all versions) than a tile
+            assert cnt[i] == g.binding.LSM_RANGE_OVERFLOW, (i, cnt[i], b - a, in_pieces)
+            n_over += 1
+        else:
+            assert cnt[i] == b - a, (i, cnt[i], b - a)
+            assert np.array_equal(got[i, : b - a], full[a:b]), i
+    assert 2 <= n_over < len(ranges) // 2   # the two huge ranges and the large families
+    # a small slot: ranges with more results than the slot are reported, the others are unchanged
+    ent2, cnt2 = g.lsm_range_scan(tree, _keys_tensor([lo for lo, _ in ranges]), _keys_tensor([hi for _, hi in ranges]), 8)
+    cnt2 = cnt2.cpu().numpy()
+    got2 = as_bytes(ent2).reshape(len(ranges), 8, 64)
+    for i, (lo, hi) in enumerate(ranges):
+        a, b = (bisect.bisect_left(keys, lo), bisect.bisect_left(keys, hi)) if lo < hi else (0, 0)
+        if b - a > 8:
+            assert cnt2[i] == g.binding.LSM_RANGE_OVERFLOW
+        elif cnt[i] != g.binding.LSM_RANGE_OVERFLOW:
+            assert cnt2[i] == b - a and np.array_equal(got2[i, : b - a], full[a:b])
+    # an empty tree and an empty batch
+    e0, c0 = g.lsm_range_scan([], _keys_tensor([bytes(32)]), _keys_tensor([b"\xff" * 32]), 4)
+    assert c0.cpu().tolist() == [0]
+    e1, c1 = g.lsm_range_scan(tree, _keys_tensor([bytes(32)])[:0], _keys_tensor([bytes(32)])[:0], 4)
+    assert c1.numel() == 0
+
+
+def test_batch_of_small_compactions(g, oracle, cfg1):
+    """Many independent compactions in one call: every job's output and count equal the checker's for that job -
+    1 to 9 runs per job, empty runs and empty jobs, both flag values, jobs of one tile and of dozens of tiles."""
+    from workloads import lsm
+    print("batch of small compactions", flush=True)
+    rs = np.random.RandomState(3)
+    src = [r for r in cfg1.runs] + [r for r in lsm.config3(device=dev(), scale=128).runs]
+    jobs = []
+    for j in range(160):
+        k = int(rs.randint(1, 10))
+        runs = []
+        for r in rs.choice(len(src), size=k, replace=False):   # distinct source runs: one version per key per run
+            n = int(src[r].shape[0])
+            lo = int(rs.randint(0, n))
+            ln = int(rs.choice([0, 1, 7, 100, 1000, 3000, 9000]))
+            runs.append(src[r][lo:min(n, lo + ln)].contiguous())
+        jobs.append((runs, int(rs.randint(0, 2))))
+    jobs.append(([src[0][:0].contiguous()], 1))                       # nothing at all
+    jobs.append(([src[0][:0].contiguous(), src[1][:5].contiguous()], 0))
+    jobs.append(([r.contiguous() for r in cfg1.runs], 0))              # configuration 1 as one job of the batch
+    outs, n_out = g.lsm_compact_batch(jobs)
+    torch.cuda.synchronize()
+    n_out = n_out.cpu().numpy()
+    for j, ((runs, flags), out) in enumerate(zip(jobs, outs)):
+        want = oracle.compact([r.cpu() for r in runs], flags)
+        assert int(n_out[j]) == want.shape[0], (j, int(n_out[j]), want.shape[0])
+        assert np.array_equal(as_bytes(out[: want.shape[0]]).reshape(-1, 64), want), j
+    # the same batch again into fresh buffers (the workspace of the first call is gone): same result
+    outs2, n_out2 = g.lsm_compact_batch(jobs)
+    torch.cuda.synchronize()
+    assert np.array_equal(n_out2.cpu().numpy(), n_out)
+    for a, b, m in zip(outs, outs2, n_out):
+        assert torch.equal(a[: int(m)], b[: int(m)])
+    assert g.lsm_compact_batch([])[1].numel() == 0

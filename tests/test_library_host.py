@@ -90,6 +90,25 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     tr[0].run, tr[0].fence = B._Run(64 * 1000, 100), B._Fence(4096, 1, 64)        # needs 2 fences
     q = B._Queries(4096, 8192, 4, 16)
     assert lib.lsm_probe(C.byref(q), C.byref(B._Tree(tr, 1)), C.byref(hits), None) == -2
+    # batched forms: argument errors before any launch
+    rg = B._Ranges(4096, 8192, 3, 4096)
+    ro = B._RangeOut(64 * 1000, 4096)
+    assert lib.lsm_range_scan(C.byref(rg), C.byref(tree), C.byref(ro), None) == -2          # slot larger than a tile
+    assert lib.lsm_range_scan(C.byref(B._Ranges(None, None, 3, 16)), C.byref(tree), C.byref(ro), None) == -1
+    assert lib.lsm_range_scan(C.byref(B._Ranges(4096 + 8, 8192, 3, 16)), C.byref(tree), C.byref(ro), None) == -2
+    assert lib.lsm_range_scan(C.byref(B._Ranges(None, None, 0, 16)), C.byref(tree), C.byref(ro), None) == 0   # no ranges
+    job = (B._CompactJob * 1)()
+    job[0].runs, job[0].n_runs, job[0].flags, job[0].out = C.pointer(fake), 1, 0, big
+    need = lib.lsm_compact_batch_workspace_bytes(job, 1)
+    assert need >= 256 * 6
+    assert lib.lsm_compact_batch(job, 1, 256 * 7, need - 1, None) == -4
+    job[0].flags = 2
+    assert lib.lsm_compact_batch_workspace_bytes(job, 1) == 0 and lib.lsm_compact_batch(job, 1, 256 * 7, 1 << 20, None) == -2
+    job[0].flags, job[0].out = 0, small
+    assert lib.lsm_compact_batch(job, 1, 256 * 7, 1 << 20, None) == -3
+    job[0].out, job[0].runs = big, C.pointer(B._Run(64 * 1000, 1 << 23))
+    assert lib.lsm_compact_batch(job, 1, 256 * 7, 1 << 30, None) == -2                          # too large for the batch
+    assert lib.lsm_compact_batch(None, 0, None, 0, None) == 0
     # the entry point without a workspace argument: same checks, plus its size limit, all before any launch
     assert lib.lsm_compact_static(None, 1, 0, C.byref(out), None) == -1
     assert lib.lsm_compact_static(C.byref(run), 0, 0, C.byref(out), None) == -2
