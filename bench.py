@@ -217,6 +217,55 @@ def mixed_config5(g, lsm, torch, dev, scale: int):
             "final_level_sizes": [[r.n for r in lv] for lv in tree.levels]}
 
 
+def sharded_config5(g, lsm, torch, dev, n_shards: int, scale: int):
+    """Batched small compactions: `n_shards` independent trees (key-range shards of one index, or tenants), each with
+    the mixed workload at 1 / n_shards of its size, written to in step.  The same flush rounds are replayed twice: every
+    tree's compactions on their own (one lsm_compact per compaction), and the compactions of a round in one
+    lsm_compact_batch.  Probe batches are left out of this section (they are the same calls either way)."""
+    from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend, ShardedLsmTrees
+    from workloads import rng
+    traces = [lsm.config5(device=dev, seed=rng.SEED + 1000 * i, tree_total=400_000_000 // scale // n_shards,
+                          buffer_entries=max(36, 3600 // scale), ops_per_phase=(1 << 18) // scale // n_shards) for i in range(n_shards)]
+    rounds = max(int(tr.flush_runs.shape[0]) for tr in traces)
+
+    def build():
+        backend = GpuBackend(bloom_bits=16)
+        trees = [AdaptiveLsmTree(backend, tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests,
+                                 t_grid=(2, 16)) for tr in traces]
+        for tr, tree in zip(traces, trees):
+            for level, r in enumerate(tr.workload.runs):
+                tree.load_level(level, [r])
+        return backend, trees
+
+    def replay(batched: bool):
+        backend, trees = build()
+        sharded = ShardedLsmTrees(trees, backend)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for f in range(rounds):
+            runs = [tr.flush_runs[f] if f < tr.flush_runs.shape[0] else None for tr in traces]
+            if batched:
+                sharded.flush_all(runs)
+            else:
+                for tree, run in zip(trees, runs):
+                    if run is not None:
+                        tree.flush(run)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        comp = [e for t in trees for e in t.trace if e[0] == "compact"]
+        return dt, len(comp), sum(e[3] for e in comp), [[r.n for r in lv] for lv in trees[0].levels]
+
+    dt_one, n_comp, merged, shape_one = replay(False)
+    dt_batch, n_comp_b, merged_b, shape_batch = replay(True)
+    assert (n_comp, merged, shape_one) == (n_comp_b, merged_b, shape_batch), "the batched replay built another tree"
+    return {"workload": "%d independent trees of %d entries, %d flush rounds of %d entries per tree"
+                        % (n_shards, sum(int(r.shape[0]) for r in traces[0].workload.runs), rounds, traces[0].buffer_entries),
+            "compactions": n_comp, "entries_merged": merged,
+            "one_call_per_compaction": {"seconds": dt_one, "merged_entries_per_s_incl_host": merged / dt_one},
+            "batched": {"seconds": dt_batch, "merged_entries_per_s_incl_host": merged / dt_batch},
+            "speedup": dt_one / dt_batch}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -371,6 +420,8 @@ def main() -> int:
         torch.cuda.empty_cache()
     if not args.no_mixed:
         result["mixed_config"] = mixed_config5(g, lsm, torch, dev, args.scale)
+        torch.cuda.empty_cache()
+        result["sharded_mixed_config"] = sharded_config5(g, lsm, torch, dev, 8, args.scale)
         torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cpu_sample, min(16, os.cpu_count() or 1))

@@ -68,6 +68,17 @@ class GpuBackend:
             return fused[2]
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
+    def compact_batch(self, jobs: Sequence[Tuple[Sequence[Any], int]]) -> List[Any]:
+        """Independent compactions (of different trees) in one library call; the counts come back in one copy."""
+        outs, n_out = self._b.lsm_compact_batch([(list(runs), flags) for runs, flags in jobs])
+        counts = n_out.cpu().tolist()
+        merged = []
+        for out, n in zip(outs, counts):
+            if n < 0 or n > out.shape[0]:
+                raise RuntimeError("lsm_compact_batch reported a device-side failure")
+            merged.append(out[:n])
+        return merged
+
     def flush_buffer(self, buffer: Any) -> Any:
         out, n_out = self._b.lsm_flush_buffer(buffer.contiguous())
         return out[: int(n_out.item())]
@@ -147,27 +158,41 @@ class AdaptiveLsmTree:
         self.flush(self.backend.flush_buffer(buffer))
 
     def _arrive(self, level: int, newcomer: LevelRun) -> None:
-        self._ensure_level(level)
-        if (self.level_t[level], self.level_k[level]) != (self.size_ratio, self.runs_per_level):
-            self.trace.append(("adopt", level + 1, self.size_ratio, self.runs_per_level))
-        # lazy transition: the level takes the current parameters when data flows into it
-        self.level_t[level], self.level_k[level] = self.size_ratio, self.runs_per_level
-        lv = self.levels[level]
-        lv.insert(0, newcomer)
-        if len(lv) <= self.level_k[level]:
-            return
-        deeper_empty = all(len(x) == 0 for x in self.levels[level + 1:])
-        flags = LSM_BOTTOMMOST if deeper_empty else 0
-        n_in = sum(r.n for r in lv)
-        merged = self.backend.compact([r.run for r in lv], flags)
-        self.trace.append(("compact", level + 1, len(lv), n_in, int(merged.shape[0]), flags))
-        self.levels[level] = []
-        n_merged = int(merged.shape[0])
-        if n_merged > self.capacity(level):
-            self.trace.append(("move", level + 1, level + 2, n_merged))
-            self._arrive(level + 1, self._index(merged))
-        elif n_merged > 0:
-            self.levels[level] = [self._index(merged)]
+        """A run arrives at a level; the compactions this triggers are run one after the other."""
+        steps = self._arrive_steps(level, newcomer)
+        try:
+            runs, flags = next(steps)
+            while True:
+                runs, flags = steps.send(self.backend.compact(runs, flags))
+        except StopIteration:
+            pass
+
+    def _arrive_steps(self, level: int, newcomer: LevelRun):
+        """The same cascade as a generator: yields (runs, flags) for every compaction it needs and is sent the merged
+        run, so that a caller who steps several trees together can run their compactions as one batch."""
+        while newcomer is not None:
+            self._ensure_level(level)
+            if (self.level_t[level], self.level_k[level]) != (self.size_ratio, self.runs_per_level):
+                self.trace.append(("adopt", level + 1, self.size_ratio, self.runs_per_level))
+            # lazy transition: the level takes the current parameters when data flows into it
+            self.level_t[level], self.level_k[level] = self.size_ratio, self.runs_per_level
+            lv = self.levels[level]
+            lv.insert(0, newcomer)
+            newcomer = None
+            if len(lv) <= self.level_k[level]:
+                return
+            deeper_empty = all(len(x) == 0 for x in self.levels[level + 1:])
+            flags = LSM_BOTTOMMOST if deeper_empty else 0
+            n_in = sum(r.n for r in lv)
+            merged = yield [r.run for r in lv], flags
+            self.trace.append(("compact", level + 1, len(lv), n_in, int(merged.shape[0]), flags))
+            self.levels[level] = []
+            n_merged = int(merged.shape[0])
+            if n_merged > self.capacity(level):
+                self.trace.append(("move", level + 1, level + 2, n_merged))
+                newcomer, level = self._index(merged), level + 1
+            elif n_merged > 0:
+                self.levels[level] = [self._index(merged)]
 
     # ------------------------------------------------------------------ operations and controller
     def _count(self, writes: int, hits: int, empties: int, blocks: float) -> None:
@@ -209,6 +234,37 @@ class AdaptiveLsmTree:
                                           self.t_grid[0], self.t_grid[1], self.page_entries, self.filter_fpr, d)
         self.trace.append(("policy", T, K, tuple(round(x, 6) for x in mix), round(d, 6)))
         self.size_ratio, self.runs_per_level = T, K
+
+
+class ShardedLsmTrees:
+    """Several independent trees (key-range shards of one index, or one index per tenant) stepped together.  The
+    flush / compaction cycles of the small upper levels (section 2.2) of different trees do not depend on each other,
+    so the compactions that one round of flushes triggers are handed to the backend as one batch, and so are the
+    compactions of the next step of their cascades, until every tree is settled.  Each tree keeps its own controller."""
+
+    def __init__(self, trees: Sequence[AdaptiveLsmTree], backend: Any):
+        self.trees, self.backend = list(trees), backend
+
+    def flush_all(self, runs: Sequence[Any]) -> None:
+        """runs[i]: a sorted run from tree i's write buffer, or None if tree i has nothing to flush now."""
+        active = []
+        for tree, run in zip(self.trees, runs):
+            if run is None:
+                continue
+            steps = tree._arrive_steps(0, tree._index(run))
+            try:
+                active.append((steps, next(steps)))
+            except StopIteration:
+                pass
+        while active:
+            merged = self.backend.compact_batch([job for _, job in active])
+            still = []
+            for (steps, _), m in zip(active, merged):
+                try:
+                    still.append((steps, steps.send(m)))
+                except StopIteration:
+                    pass
+            active = still
 
 
 def run_mixed_trace(tree: AdaptiveLsmTree, trace, on_probe=None, on_compaction=None, shuffle_writes=None) -> None:

@@ -97,3 +97,58 @@ def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries,
         assert any(e[0] == "compact" and e[2] > 2 for e in gpu.trace)   # several runs of a level merged at once
     if t_grid[0] != t_grid[1]:
         assert len({t for t, _ in pol}) > 1 or pol[0][0] != tr.size_ratio, pol   # the size ratio moves as well
+
+
+def test_sharded_trees_with_batched_compactions(oracle):
+    """Four independent trees stepped together: the compactions of every round go to the library as one batch
+    (lsm_compact_batch).  Every tree's log, probe results and final runs equal the plain driver's for that tree alone."""
+    from oracle import lsm_driver_oracle as drv
+    from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend, ShardedLsmTrees
+    from workloads import lsm, rng
+    print("sharded trees", flush=True)
+    n_shards, window = 4, 16 * 128
+    traces = [lsm.config5(device=dev(), seed=rng.SEED + 1000 * i, tree_total=200_000 + 50_000 * i, buffer_entries=360,
+                          ops_per_phase=2048, batch_requests=128) for i in range(n_shards)]
+    backend = GpuBackend(bloom_bits=16)
+    batches = []
+    real = backend.compact_batch
+    backend.compact_batch = lambda jobs: (batches.append(len(jobs)), real(jobs))[1]
+    trees = [AdaptiveLsmTree(backend, tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=(2, 16)) for tr in traces]
+    cpus = [drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=(2, 16),
+                             page_entries=64.0, fpr=drv.bloom_fpr(16)) for tr in traces]
+    for tr, tree, cpu in zip(traces, trees, cpus):
+        for level, r in enumerate(tr.workload.runs):
+            tree.load_level(level, [r])
+            cpu.install(level + 1, [r.cpu()])
+    sharded = ShardedLsmTrees(trees, backend)
+    at = [0] * n_shards
+    while any(at[i] < len(traces[i].events) for i in range(n_shards)):
+        runs = [None] * n_shards
+        for i, (tr, tree, cpu) in enumerate(zip(traces, trees, cpus)):
+            if at[i] >= len(tr.events):
+                continue
+            (kind, idx, _phase), n_writes = tr.events[at[i]], tr.write_ops_between[at[i]]
+            at[i] += 1
+            if n_writes:
+                tree.note_writes(n_writes)
+                cpu.writes(n_writes)
+            if kind == "flush":
+                runs[i] = tr.flush_runs[idx]
+                cpu.flush(runs[i].cpu())
+            else:
+                q, nb = tr.probe_batch(idx)
+                ghl, ghits = tree.probe(q, nb)
+                chl, chits = cpu.probe(q.cpu(), nb.cpu())
+                assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl)
+                assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits)
+        sharded.flush_all(runs)
+        for i, (tree, cpu) in enumerate(zip(trees, cpus)):
+            assert tree.trace[-2:] == cpu.log[-2:] and len(tree.trace) == len(cpu.log), (i, tree.trace[-3:], cpu.log[-3:])
+    assert max(batches) == n_shards and sum(batches) == sum(1 for t in trees for e in t.trace if e[0] == "compact")
+    for tree, cpu in zip(trees, cpus):
+        assert tree.trace == cpu.log
+        assert [len(lv) for lv in tree.levels] == [len(lv.runs) for lv in cpu.levels]
+        for glv, clv in zip(tree.levels, cpu.levels):
+            for gr, cr in zip(glv, clv.runs):
+                assert np.array_equal(oracle.as_run(gr.run), cr)
+                assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
