@@ -339,8 +339,8 @@ int lsm_range_scan(const lsm_ranges_t* ranges, const lsm_tree_t* tree, const lsm
  * the small upper levels; with several trees or key-range shards their compactions do not depend on each other).
  * Job j merges jobs[j].runs into jobs[j].out exactly as lsm_compact would with jobs[j].flags; all jobs share two
  * kernel launches (one partition, one tile merge), and every job's count goes to its own out.n_out on the device.
- * Restrictions: LSM_VALIDATE and out.fence_keys are not supported here; a job of 2048 tiles or more (about 4 million
- * entries) is rejected with LSM_ERR_BAD_ARG - use lsm_compact for it.  Inputs and outputs of different jobs must not
+ * out.fence_keys works as in lsm_compact.  Restrictions: LSM_VALIDATE is not supported here; a job of 2048 tiles or
+ * more (about 4 million entries) is rejected with LSM_ERR_BAD_ARG - use lsm_compact for it.  Inputs and outputs of different jobs must not
  * overlap.  jobs, and the run arrays they point to: HOST, read during the call.  workspace: DEVICE, 256-byte
  * aligned, lsm_compact_batch_workspace_bytes(jobs, n_jobs) bytes (0 on bad arguments); the call copies a table of
  * the jobs into it.  Errors as lsm_compact.

@@ -352,10 +352,11 @@ def lsm_range_scan(tree: Sequence[TreeRun], lo_keys: torch.Tensor, hi_keys: torc
     return entries, (raw.to(torch.int64) & 0xFFFFFFFF) if counts is None else raw
 
 
-def lsm_compact_batch(jobs: Sequence[Tuple[Sequence[torch.Tensor], int]], stream=None
-                      ) -> Tuple[List[torch.Tensor], torch.Tensor]:
+def lsm_compact_batch(jobs: Sequence[Tuple[Sequence[torch.Tensor], int]], stream=None, fence_stride: int = 0):
     """Many independent small compactions in one call.  jobs = [(runs, flags), ...].  Returns (outs, n_out): outs[j] is
-    int64 [capacity_j, 8] (a slice of one allocation), n_out int64 [n_jobs] on the device."""
+    int64 [capacity_j, 8] (a slice of one allocation), n_out int64 [n_jobs] on the device.  With fence_stride > 0 the
+    fence index of every output is written in the same pass and (outs, n_out, fences) is returned: fences[j] is int64
+    [ceil(capacity_j / fence_stride), 4], of which the first ceil(n_out[j] / fence_stride) rows are meaningful."""
     L = _load()
     n_jobs = len(jobs)
     dev = next((r.device for runs, _ in jobs for r in runs), torch.device("cuda"))
@@ -363,12 +364,20 @@ def lsm_compact_batch(jobs: Sequence[Tuple[Sequence[torch.Tensor], int]], stream
     out_all = torch.empty((max(sum(totals), 1), 8), dtype=torch.int64, device=dev)
     n_out = torch.empty(max(n_jobs, 1), dtype=torch.int64, device=dev)
     outs, keep, jd, at = [], [], (_CompactJob * max(1, n_jobs))(), 0
+    fences, f_at = [], 0
+    if fence_stride > 0:
+        f_rows = [(t + fence_stride - 1) // fence_stride for t in totals]
+        fence_all = torch.empty((max(sum(f_rows), 1), 4), dtype=torch.int64, device=dev)
     for j, ((runs, flags), total) in enumerate(zip(jobs, totals)):
         rd = (_Run * max(1, len(runs)))(*[_Run(_dev(r, "run").data_ptr(), int(r.shape[0])) for r in runs])
         keep.append(rd)
         outs.append(out_all[at:at + total])
         jd[j].runs, jd[j].n_runs, jd[j].flags = rd, len(runs), flags
         jd[j].out = _Out(out_all.data_ptr() + at * 64, total, n_out.data_ptr() + 8 * j, None, 0)
+        if fence_stride > 0:
+            fences.append(fence_all[f_at:f_at + f_rows[j]])
+            jd[j].out.fence_keys, jd[j].out.fence_stride = fence_all.data_ptr() + f_at * 32, fence_stride
+            f_at += f_rows[j]
         at += total
     need = int(L.lsm_compact_batch_workspace_bytes(jd, n_jobs)) if n_jobs else 0
     if n_jobs and need == 0:
@@ -377,7 +386,7 @@ def lsm_compact_batch(jobs: Sequence[Tuple[Sequence[torch.Tensor], int]], stream
     rc = L.lsm_compact_batch(jd, n_jobs, ws.data_ptr(), ws.numel(), _stream_ptr(stream))
     if rc != 0:
         raise LsmError(rc, "lsm_compact_batch")
-    return outs, n_out[:n_jobs]
+    return (outs, n_out[:n_jobs], fences) if fence_stride > 0 else (outs, n_out[:n_jobs])
 
 
 def lsm_probe(qkeys: torch.Tensor, n_blocks: torch.Tensor, tree: Sequence[TreeRun],

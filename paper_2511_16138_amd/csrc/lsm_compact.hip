@@ -361,10 +361,11 @@ struct MergeShared {
     uint32_t inexact;                // some position has an equal surrogate but a different key tail
     uint64_t base;
     // batched compactions only: what the single form takes from its kernel arguments
-    uint32_t k, flags, job_tiles;
+    uint32_t k, flags, job_tiles, fence_stride;
     lsm_entry_t* out;
     uint64_t* n_out;
     uint64_t* status;
+    uint4* fence_out;
 };
 
 // The tile kernel has three forms.  Single: one compaction, tile = workgroup, pieces from the split table.
@@ -380,9 +381,10 @@ struct JobDesc {       // one compaction of a batch (device memory, written by t
     uint64_t splits_off;   // where its split table starts (in 64-bit words)
     lsm_entry_t* out;
     uint64_t* n_out;
-    uint32_t n_tiles, k, flags, pad;
+    uint4* fence_out;      // optional fence index of the job's output
+    uint32_t n_tiles, k, flags, fence_stride;
 };
-static_assert(sizeof(JobDesc) == 56, "descriptor layout");
+static_assert(sizeof(JobDesc) == 64, "descriptor layout");
 
 struct ModeArgs {
     // range form
@@ -521,7 +523,7 @@ __device__ __forceinline__ uint64_t lower_bound_from(const lsm_entry_t* run, uin
 template <bool kExtras, int kMode>
 __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags_arg,
                                                                lsm_entry_t* out_arg, uint64_t* n_out_arg, const uint64_t* remap_base,
-                                                               uint32_t remap_files, uint4* fence_out, uint32_t fence_stride, ModeArgs ma) {
+                                                               uint32_t remap_files, uint4* fence_out_arg, uint32_t fence_stride_arg, ModeArgs ma) {
     __shared__ MergeShared s;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -571,6 +573,8 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 s.out = d.out;
                 s.n_out = d.n_out;
                 s.status = ws.status + d.first_tile;
+                s.fence_out = d.fence_out;
+                s.fence_stride = d.fence_stride;
             }
         }
         const bool mine = lane < (int)kk;
@@ -607,6 +611,8 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
     lsm_entry_t* const out = kMode == kModeBatch ? s.out : out_arg;
     uint64_t* const n_out = kMode == kModeBatch ? s.n_out : n_out_arg;
     const uint64_t last_tile = kMode == kModeBatch ? (uint64_t)s.job_tiles - 1 : n_tiles - 1;
+    uint4* const fence_out = kMode == kModeBatch ? s.fence_out : fence_out_arg;
+    const uint32_t fence_stride = kMode == kModeBatch ? s.fence_stride : fence_stride_arg;
     const uint32_t top_step = k > 1 ? 1u << (31 - __builtin_clz(k - 1)) : 0;
 
     // ---- load: entry e = tid + i * kMergeThreads stays in this thread's registers until it is stored
@@ -1288,7 +1294,9 @@ static int batch_layout(const lsm_compact_job_t* jobs, uint32_t n_jobs, BatchLay
     for (uint32_t j = 0; j < n_jobs; j++) {
         const lsm_compact_job_t& job = jobs[j];
         if (job.runs == nullptr) return LSM_ERR_NULL;
-        if (job.n_runs == 0 || job.n_runs > LSM_MAX_RUNS || (job.flags & LSM_VALIDATE) || job.out.fence_keys != nullptr) return LSM_ERR_BAD_ARG;
+        if (job.n_runs == 0 || job.n_runs > LSM_MAX_RUNS || (job.flags & LSM_VALIDATE)) return LSM_ERR_BAD_ARG;
+        if (job.out.fence_keys != nullptr && (job.out.fence_stride == 0 || (reinterpret_cast<uintptr_t>(job.out.fence_keys) & 15) != 0))
+            return LSM_ERR_BAD_ARG;
         uint64_t total = 0;
         for (uint32_t r = 0; r < job.n_runs; r++) total += job.runs[r].n;
         uint64_t nt = tiles_for(total, job.n_runs);
@@ -1352,6 +1360,7 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
     const lsm_entry_t** run_ptr = reinterpret_cast<const lsm_entry_t**>(table.data() + (l.run_ptr - l.tile_job));
     uint64_t* run_n = reinterpret_cast<uint64_t*>(table.data() + (l.run_n - l.tile_job));
     uint64_t tile = 0, split_word = 0, run = 0;
+    bool any_fences = false;
     for (uint32_t j = 0; j < n_jobs; j++) {
         const lsm_compact_job_t& job = jobs[j];
         uint64_t total = 0;
@@ -1368,10 +1377,12 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
         d.splits_off = split_word;
         d.out = job.out.entries;
         d.n_out = job.out.n_out;
+        d.fence_out = reinterpret_cast<uint4*>(job.out.fence_keys);
+        d.fence_stride = job.out.fence_keys ? job.out.fence_stride : 1u;
+        any_fences = any_fences || job.out.fence_keys != nullptr;
         d.n_tiles = (uint32_t)nt;
         d.k = job.n_runs;
         d.flags = job.flags;
-        d.pad = 0;
         for (uint64_t t = 0; t < nt; t++) tile_job[tile + t] = j;
         tile += nt;
         split_word += (nt + 1) * job.n_runs;
@@ -1394,8 +1405,12 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
     hipLaunchKernelGGL(partition_batch_kernel, dim3((uint32_t)((l.tiles + per_block - 1) / per_block)), dim3(256), 0, stream, ws, ma, l.tiles, group);
     RunTable rt = {};
     rt.k = 1;
-    hipLaunchKernelGGL((merge_kernel<false, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
-                       (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
+    if (any_fences)  // the form that also writes fence indices (a job without one has a null pointer in its descriptor)
+        hipLaunchKernelGGL((merge_kernel<true, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
+                           (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
+    else
+        hipLaunchKernelGGL((merge_kernel<false, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
+                           (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }
 

@@ -62,6 +62,11 @@ class GpuBackend:
         return merged
 
     def build_fences(self, run: Any) -> Any:
+        batch = getattr(self, "_batch_fences", None)
+        if batch:
+            f = batch.pop((run.data_ptr(), int(run.shape[0])), None)
+            if f is not None:
+                return f
         fused = getattr(self, "_fused", None)
         if fused is not None and fused[0] == run.data_ptr() and fused[1] == int(run.shape[0]) and fused[1] > 0:
             self._fused = None
@@ -70,13 +75,16 @@ class GpuBackend:
 
     def compact_batch(self, jobs: Sequence[Tuple[Sequence[Any], int]]) -> List[Any]:
         """Independent compactions (of different trees) in one library call; the counts come back in one copy."""
-        outs, n_out = self._b.lsm_compact_batch([(list(runs), flags) for runs, flags in jobs])
+        outs, n_out, fences = self._b.lsm_compact_batch([(list(runs), flags) for runs, flags in jobs], fence_stride=self.fence_stride)
         counts = n_out.cpu().tolist()
         merged = []
-        for out, n in zip(outs, counts):
+        self._batch_fences = {}
+        for out, n, f in zip(outs, counts, fences):
             if n < 0 or n > out.shape[0]:
                 raise RuntimeError("lsm_compact_batch reported a device-side failure")
             merged.append(out[:n])
+            if n > 0:  # the fence index written in the same pass: handed out when the driver asks for this run's
+                self._batch_fences[(out.data_ptr(), n)] = f[: (n + self.fence_stride - 1) // self.fence_stride]
         return merged
 
     def flush_buffer(self, buffer: Any) -> Any:

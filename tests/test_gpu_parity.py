@@ -558,10 +558,13 @@ def test_batch_of_small_compactions(g, oracle, cfg1):
         want = oracle.compact([r.cpu() for r in runs], flags)
         assert int(n_out[j]) == want.shape[0], (j, int(n_out[j]), want.shape[0])
         assert np.array_equal(as_bytes(out[: want.shape[0]]).reshape(-1, 64), want), j
-    # the same batch again into fresh buffers (the workspace of the first call is gone): same result
-    outs2, n_out2 = g.lsm_compact_batch(jobs)
+    # the same batch again into fresh buffers (the workspace of the first call is gone), with fence indices: same
+    # result, and every job's fences are the strided keys of its output
+    outs2, n_out2, fences = g.lsm_compact_batch(jobs, fence_stride=64)
     torch.cuda.synchronize()
     assert np.array_equal(n_out2.cpu().numpy(), n_out)
-    for a, b, m in zip(outs, outs2, n_out):
+    for a, b, m, f in zip(outs, outs2, n_out, fences):
         assert torch.equal(a[: int(m)], b[: int(m)])
+        want_f = as_bytes(a[: int(m)]).reshape(-1, 64)[::64, :32]
+        assert np.array_equal(as_bytes(f[: (int(m) + 63) // 64]).reshape(-1, 32), want_f)
     assert g.lsm_compact_batch([])[1].numel() == 0
