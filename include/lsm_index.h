@@ -178,8 +178,13 @@ typedef struct {
  * With LSM_VALIDATE the call synchronises the stream and additionally returns
  * LSM_ERR_UNSORTED / LSM_ERR_BAD_ENTRY (checked before merging; nothing is written then) or
  * LSM_ERR_INTERNAL.  Without it, inputs that violate the precondition give an unspecified
- * (but in-bounds) result.  If a device-side wait ever exceeds its bound, *out->n_out is set
- * to UINT64_MAX instead of a count.
+ * (but in-bounds) result.
+ * The output offset of a tile comes from the counts of the tiles before it; a tile waits for them, and tile numbers
+ * are workgroup numbers, so the wait relies on workgroups being started in ascending order (which holds on this
+ * hardware also when several kernels share the GPU, but is not a documented guarantee).  The wait is bounded: if it
+ * ever ends without the counts, the remaining tiles write nothing, *out->n_out is set to UINT64_MAX instead of a
+ * count, and the output is incomplete - every caller that does not use LSM_VALIDATE should check for that value when
+ * it reads the count.  Two compactions may run at the same time on two streams if each has its own workspace.
  */
 int lsm_compact(const lsm_run_t* runs, uint32_t n_runs, uint32_t flags, const lsm_out_t* out, void* workspace,
                 size_t workspace_bytes, void* stream);

@@ -306,4 +306,25 @@ def range_scan(tree_runs: Sequence[Any], lo_key: bytes, hi_key: bytes) -> Any:
     if not slices:
         return None
     out, n_out = b.lsm_compact(slices, b.LSM_BOTTOMMOST)
-    return out[: int(n_out.item())]
+    n = int(n_out.item())
+    if n < 0 or n > out.shape[0]:
+        raise RuntimeError("lsm_compact reported a device-side failure")
+    return out[:n]
+
+
+def range_scan_batch(tree_runs: Sequence[Any], lo_keys: Any, hi_keys: Any, max_entries: int = 256) -> List[Any]:
+    """The range lookups of a get_batch in one library call (appendix B): for every range [lo_keys[i], hi_keys[i]) the
+    live entries, newest version of each, ascending (their value pointers and lengths are the read list for the tensor
+    files).  lo_keys, hi_keys: int64 [n, 4] key tensors on the GPU.  A range that does not fit its slot is redone alone
+    with range_scan."""
+    from . import binding as b
+    entries, counts = b.lsm_range_scan(tree_runs, lo_keys, hi_keys, max_entries)
+    counts = counts.cpu().tolist()
+    out = []
+    for i, c in enumerate(counts):
+        if c == b.LSM_RANGE_OVERFLOW:
+            lo, hi = (bytes(k.cpu().numpy().tobytes()) for k in (lo_keys[i], hi_keys[i]))
+            out.append(range_scan(tree_runs, lo, hi))
+        else:
+            out.append(entries[i, :c])
+    return out
