@@ -576,3 +576,51 @@ def test_batch_of_small_compactions(g, oracle, cfg1):
         want_f = as_bytes(a[: int(m)]).reshape(-1, 64)[::64, :32]
         assert np.array_equal(as_bytes(f[: (int(m) + 63) // 64]).reshape(-1, 32), want_f)
     assert g.lsm_compact_batch([])[1].numel() == 0
+
+
+def test_get_batch_under_a_shared_prefix_with_ladder_keys(g, oracle):
+    """get_batch (appendix B) on keys in the segment-ladder layout: the cached blocks below a shared prefix of 512 g
+    tokens are one tight key range, fetched for many prefixes in one lsm_range_scan - newest versions, no tombstoned
+    blocks - and nothing that is not below the prefix."""
+    from test_workloads import _prefix_tree_tokens
+    from workloads import keys as K
+    print("get_batch with ladder keys", flush=True)
+    toks = _prefix_tree_tokens(n_seq=120, length=100, seed=21)
+    n, length = toks.shape[0], toks.shape[1]
+    words = K.chain_keys(toks, "ladder")                                  # [n, L, 4]
+    mem = K.key_bytes_words(words.reshape(-1, 4)).numpy().view(np.uint8).reshape(-1, 32)
+    uniq, first_at = np.unique(mem.view("V32").reshape(-1), return_index=True)
+    keys_all = mem[np.sort(first_at)]                                     # distinct keys, one per cached block
+    rs = np.random.RandomState(5)
+    runs, seq = [], 1000
+    for r in range(3):                                                    # three runs: random subsets, some tombstones, newer = earlier run
+        pick = np.sort(rs.choice(keys_all.shape[0], size=keys_all.shape[0] * 2 // 3, replace=False))
+        a = np.zeros((pick.shape[0], 64), dtype=np.uint8)
+        a[:, :32] = keys_all[pick]
+        rec = a.view(oracle.ENTRY_DTYPE).reshape(-1)
+        rec["seqno"] = (3 - r) * 1_000_000 + np.arange(pick.shape[0])
+        rec["type"] = (rs.rand(pick.shape[0]) < 0.1).astype(np.uint8)
+        rec["vptr"] = rec["seqno"] * 16
+        rec["vlen"] = 655360
+        order = np.argsort(a[:, :32].view("V32").reshape(-1), kind="stable")
+        runs.append(a[order])
+    full = oracle.compact(runs, 1)
+    full_keys = [bytes(k) for k in full[:, :32]]
+    tree = build_tree(g, [to_dev(r) for r in runs])
+    kb = [bytes(k) for k in mem]
+    t = toks.numpy()
+    ranges, below = [], []
+    for i in range(0, n, 2):
+        for grp in (1, 2, 3):
+            deep = kb[i * length + 32 * grp]
+            ranges.append((deep[:3 * grp] + bytes(32 - 3 * grp), deep[:3 * grp] + b"\xff" * (32 - 3 * grp)))
+            below.append({kb[j * length + k] for j in range(n) if (t[j, :32 * grp] == t[i, :32 * grp]).all() for k in range(32 * grp, length)})
+    ent, cnt = g.lsm_range_scan(tree, _keys_tensor([lo for lo, _ in ranges]), _keys_tensor([hi for _, hi in ranges]), 1024)
+    torch.cuda.synchronize()
+    cnt = cnt.cpu().numpy()
+    got = as_bytes(ent).reshape(len(ranges), 1024, 64)
+    for i, ((lo, hi), sub) in enumerate(zip(ranges, below)):
+        want = full[[j for j, k in enumerate(full_keys) if k in sub]]     # live newest versions of the blocks below the prefix
+        assert cnt[i] == want.shape[0], (i, cnt[i], want.shape[0])
+        assert np.array_equal(got[i, : cnt[i]], want), i
+    assert max(cnt) > 100 and min(cnt) > 0

@@ -1,5 +1,6 @@
 """Properties of the seeded input generator (CPU only)."""
 import numpy as np
+import pytest
 import torch
 
 from workloads import keys as K
@@ -85,3 +86,68 @@ def test_tree_sizes():
 def test_generator_is_deterministic():
     a, b = lsm.config3(scale=2048), lsm.config3(scale=2048)
     assert all(torch.equal(x, y) for x, y in zip(a.runs, b.runs))
+
+
+def _prefix_tree_tokens(n_seq=60, length=100, seed=9):
+    """Sequences that share prefixes of many lengths: sequence i copies the first cut[i] blocks of an earlier one."""
+    import numpy as np
+    rs = np.random.RandomState(seed)
+    toks = rs.randint(0, 32000, size=(n_seq, length, 16)).astype(np.int64)
+    parent, cut = [-1] * n_seq, [0] * n_seq
+    for i in range(1, n_seq):
+        if rs.rand() < 0.8:
+            parent[i] = int(rs.randint(0, i))
+            cut[i] = int(rs.choice([1, 5, 16, 31, 32, 33, 40, 64, 65, 96, 99]))
+            toks[i, :cut[i]] = toks[parent[i], :cut[i]]
+    return torch.from_numpy(toks)
+
+
+def _as_bytes(words):
+    from workloads import keys as K
+    return [bytes(r) for r in K.key_bytes_words(words.reshape(-1, 4)).numpy().view("u1").reshape(-1, 32)]
+
+
+@pytest.mark.parametrize("layout", ["family", "ladder"])
+def test_both_key_layouts_follow_prefix_order(layout):
+    """Equal block-prefixes give equal keys, different ones different keys, and a prefix sorts before its extensions."""
+    from workloads import keys as K
+    toks = _prefix_tree_tokens()
+    n, length = toks.shape[0], toks.shape[1]
+    kb = _as_bytes(K.chain_keys(toks, layout))
+    key = lambda i, k: kb[i * length + k]
+    for i in range(n):
+        for k in range(length - 1):
+            assert key(i, k) < key(i, k + 1)                       # a block-prefix before its extension
+    t = toks.numpy()
+    for i in range(0, n, 7):
+        for j in range(n):
+            common = 0
+            while common < length and (t[i, common] == t[j, common]).all():
+                common += 1
+            for k in range(0, length, 9):
+                assert (key(i, k) == key(j, k)) == (k < common)    # shared prefixes share their keys, and only those
+
+
+def test_ladder_layout_makes_subtrees_contiguous():
+    """All blocks below a prefix of 32 g blocks (512 g tokens) lie in the key range that the first 3 g bytes of the
+    prefix's ladder span, and nothing else does: a range lookup under a long shared prefix is tight."""
+    from workloads import keys as K
+    toks = _prefix_tree_tokens(n_seq=80, length=100, seed=4)
+    n, length = toks.shape[0], toks.shape[1]
+    kb = _as_bytes(K.chain_keys(toks, "ladder"))
+    t = toks.numpy()
+    all_keys = sorted(set(kb))
+    checked = 0
+    for i in range(0, n, 3):
+        for g in (1, 2, 3):
+            deep = kb[i * length + 32 * g]                          # first block beyond the prefix of 32 g blocks
+            lo, hi = deep[:3 * g] + bytes(32 - 3 * g), deep[:3 * g] + b"\xff" * (32 - 3 * g)
+            inside = {k for k in all_keys if lo <= k <= hi}
+            below = {kb[j * length + k] for j in range(n) if (t[j, :32 * g] == t[i, :32 * g]).all() for k in range(32 * g, length)}
+            assert inside == below
+            checked += 1
+    assert checked > 50
+    # the family layout does not have this property: a family's range also holds the blocks above the prefix
+    fb = _as_bytes(K.chain_keys(toks, "family"))
+    fam = fb[32][:8]
+    assert any(k[:8] == fam and int.from_bytes(k[8:10], "big") < 32 for k in fb)

@@ -15,6 +15,18 @@ Consequences: two sequences that agree on their first k+1 blocks produce the sam
 block k (shared prefixes collide into the same index entries); if P is a proper
 block-prefix of Q then key(P) < key(Q); all keys of one family are contiguous.
 
+A second layout, the segment ladder, trades the family digest for subtree contiguity at a coarser grain (range
+lookups under a long shared prefix then touch one tight key range instead of a family's whole span):
+
+    key(block k) = D_0 D_1 ... D_7 (8 x 3 bytes) | BE16(k) | C_k (6 bytes)
+
+  D_i  24-bit non-zero digest of the chain state after block 32 i + 31 (the end of segment i) if k >= 32 (i + 1),
+       otherwise zero.
+
+A block-prefix still sorts before its extensions (same segment: smaller k; deeper segment: a zero where the
+extension has a digest), equal block-prefixes give equal keys, and all keys below a prefix of 32 g blocks share the
+first 3 g bytes: the subtree is the range [D_0..D_{g-1} 00.., D_0..D_{g-1} ff..].  Sequences are limited to 256 blocks.
+
 A key is held as four int64 "big-endian words" W0..W3 (W0 = bytes 0..7 read as a
 big-endian number, and so on), so unsigned word-by-word comparison is byte-string order.
 """
@@ -83,6 +95,47 @@ def make_key(fam: torch.Tensor, k: torch.Tensor, state: torch.Tensor) -> torch.T
     w2 = (c0 << 48) | rng.lsr(c1, 16)
     w3 = (c1 << 48) | rng.lsr(c2, 16)
     return torch.stack([w0, w1, w2, w3], dim=1)
+
+
+SEGMENT_BLOCKS = 32  # blocks per segment of the ladder layout (512 tokens)
+
+
+def segment_digest(state: torch.Tensor) -> torch.Tensor:
+    """24-bit non-zero digest of a chain state (taken at the end of a segment)."""
+    return rng.lsr(rng.mix64(state[:, 0] ^ rng.rotl(state[:, 2], 13)), 40) | 1
+
+
+def make_ladder_key(ladder: torch.Tensor, k: torch.Tensor, state: torch.Tensor) -> torch.Tensor:
+    """[n, 4] big-endian words of the segment-ladder layout.  ladder: [n, 8] int64, the digests of the segments that
+    block k lies beyond (zero elsewhere); k: block numbers < 256; state: chain state after block k."""
+    d = [ladder[:, i] for i in range(8)]
+    w0 = (d[0] << 40) | (d[1] << 16) | rng.lsr(d[2], 8)
+    w1 = ((d[2] & 0xFF) << 56) | (d[3] << 32) | (d[4] << 8) | rng.lsr(d[5], 16)
+    w2 = ((d[5] & 0xFFFF) << 48) | (d[6] << 24) | d[7]
+    w3 = (k << 48) | rng.lsr(state[:, 0], 16)
+    return torch.stack([w0, w1, w2, w3], dim=1)
+
+
+def chain_keys(token_blocks: torch.Tensor, layout: str = "family") -> torch.Tensor:
+    """Keys of every block of `n` sequences given as tokens [n, L, 16] (L <= 256): [n, L, 4] big-endian words in the
+    family layout (R | k | C_k) or the ladder layout."""
+    n, length = int(token_blocks.shape[0]), int(token_blocks.shape[1])
+    assert length <= 8 * SEGMENT_BLOCKS and layout in ("family", "ladder")
+    dev = token_blocks.device
+    state = initial_state(n, dev)
+    fam = None
+    ladder = torch.zeros((n, 8), dtype=torch.int64, device=dev)
+    out = torch.empty((n, length, 4), dtype=torch.int64, device=dev)
+    for k in range(length):
+        state = absorb(state, token_blocks[:, k])
+        if k == 0:
+            fam = family(state)
+        kk = torch.full((n,), k, dtype=torch.int64, device=dev)
+        out[:, k] = make_key(fam, kk, state) if layout == "family" else make_ladder_key(ladder, kk, state)
+        if (k + 1) % SEGMENT_BLOCKS == 0 and (k + 1) // SEGMENT_BLOCKS <= 8:
+            ladder = ladder.clone()
+            ladder[:, (k + 1) // SEGMENT_BLOCKS - 1] = segment_digest(state)
+    return out
 
 
 def key_bytes_words(be_words: torch.Tensor) -> torch.Tensor:
