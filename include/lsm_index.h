@@ -348,7 +348,8 @@ int lsm_range_scan(const lsm_ranges_t* ranges, const lsm_tree_t* tree, const lsm
  * more (about 4 million entries) is rejected with LSM_ERR_BAD_ARG - use lsm_compact for it.  Inputs and outputs of different jobs must not
  * overlap.  jobs, and the run arrays they point to: HOST, read during the call.  workspace: DEVICE, 256-byte
  * aligned, lsm_compact_batch_workspace_bytes(jobs, n_jobs) bytes (0 on bad arguments); the call copies a table of
- * the jobs into it.  Errors as lsm_compact.
+ * the jobs into it (built in pinned host memory that the library keeps per calling thread; a call waits for the
+ * table copy of the previous call from the same thread, not for its kernels).  Errors as lsm_compact.
  */
 typedef struct {
     const lsm_run_t* runs; /* HOST array of n_runs descriptors */

@@ -23,8 +23,9 @@
 //                     surviving byte written once.
 #include <hip/hip_runtime.h>
 
+#include <string.h>
+
 #include <mutex>
-#include <vector>
 
 #include "lsm_common.h"
 
@@ -1288,6 +1289,37 @@ struct BatchLayout {
     size_t status, splits, tile_job, jobs, run_ptr, run_n, total;
     uint32_t k_max;
 };
+// Pinned host memory for the job table of one thread, with an event that tells when the last copy out of it is done.
+struct BatchStaging {
+    unsigned char* mem = nullptr;
+    size_t capacity = 0;
+    hipEvent_t copied = nullptr;
+    bool pending = false;
+
+    unsigned char* acquire(size_t bytes) {
+        if (pending && hipEventSynchronize(copied) != hipSuccess) return nullptr;
+        pending = false;
+        if (copied == nullptr && hipEventCreateWithFlags(&copied, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (bytes > capacity) {
+            if (mem != nullptr) (void)hipHostFree(mem);
+            mem = nullptr;
+            capacity = 0;
+            const size_t want = bytes < (1u << 16) ? (1u << 16) : bytes + bytes / 2;
+            void* p = nullptr;
+            if (hipHostMalloc(&p, want, hipHostMallocDefault) != hipSuccess) return nullptr;
+            mem = static_cast<unsigned char*>(p);
+            capacity = want;
+        }
+        return mem;
+    }
+    bool copy_enqueued(hipStream_t stream) {
+        if (hipEventRecord(copied, stream) != hipSuccess) return false;
+        pending = true;
+        return true;
+    }
+    // no destructor: at thread or process exit the HIP runtime may already be gone; the memory goes with the process
+};
+
 static int batch_layout(const lsm_compact_job_t* jobs, uint32_t n_jobs, BatchLayout* l) {
     l->tiles = l->split_words = l->runs = 0;
     l->k_max = 1;
@@ -1351,14 +1383,17 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
         if (job.out.capacity < total) return LSM_ERR_CAPACITY;
     }
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < l.total) return LSM_ERR_WORKSPACE;
-    // the host's table: kept per thread until the next call, copied in one piece
-    static thread_local std::vector<unsigned char> table;
+    // the host's table is built in pinned host memory kept per thread (so the copy below really is asynchronous) and
+    // is not written again before the copy of the previous call from this thread has finished
+    static thread_local BatchStaging staging;
     const size_t table_bytes = l.total - l.tile_job;
-    table.assign(table_bytes, 0);
-    uint32_t* tile_job = reinterpret_cast<uint32_t*>(table.data());
-    JobDesc* desc = reinterpret_cast<JobDesc*>(table.data() + (l.jobs - l.tile_job));
-    const lsm_entry_t** run_ptr = reinterpret_cast<const lsm_entry_t**>(table.data() + (l.run_ptr - l.tile_job));
-    uint64_t* run_n = reinterpret_cast<uint64_t*>(table.data() + (l.run_n - l.tile_job));
+    unsigned char* table = staging.acquire(table_bytes);
+    if (table == nullptr) return LSM_ERR_HIP;
+    memset(table, 0, table_bytes);
+    uint32_t* tile_job = reinterpret_cast<uint32_t*>(table);
+    JobDesc* desc = reinterpret_cast<JobDesc*>(table + (l.jobs - l.tile_job));
+    const lsm_entry_t** run_ptr = reinterpret_cast<const lsm_entry_t**>(table + (l.run_ptr - l.tile_job));
+    uint64_t* run_n = reinterpret_cast<uint64_t*>(table + (l.run_n - l.tile_job));
     uint64_t tile = 0, split_word = 0, run = 0;
     bool any_fences = false;
     for (uint32_t j = 0; j < n_jobs; j++) {
@@ -1390,7 +1425,8 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     char* base = static_cast<char*>(workspace);
-    if (hipMemcpyAsync(base + l.tile_job, table.data(), table_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return LSM_ERR_HIP;
+    if (hipMemcpyAsync(base + l.tile_job, table, table_bytes, hipMemcpyHostToDevice, stream) != hipSuccess) return LSM_ERR_HIP;
+    if (!staging.copy_enqueued(stream)) return LSM_ERR_HIP;
     Workspace ws = {};
     ws.status = reinterpret_cast<uint64_t*>(base + l.status);
     ws.splits = reinterpret_cast<uint64_t*>(base + l.splits);
