@@ -273,6 +273,14 @@ uint64_t lsm_bloom_blocks(uint64_t n, uint32_t bits_per_key);
 int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t n_blocks, void* stream);
 
 /*
+ * lsm_build_bloom_batch -- the filters of n_runs runs in two launches per 64 runs (for the outputs of
+ * lsm_compact_batch): filters_out[j] receives the filter of runs[j] with n_blocks[j] blocks, each exactly what
+ * lsm_build_bloom gives.  runs, filters_out, n_blocks: HOST arrays of n_runs elements; the pointers inside are DEVICE.
+ * Errors as lsm_build_bloom.
+ */
+int lsm_build_bloom_batch(const lsm_run_t* runs, void* const* filters_out, const uint64_t* n_blocks, uint32_t n_runs, void* stream);
+
+/*
  * lsm_probe -- batched longest-cached-prefix lookup (appendix B "Probe": find the longest
  * cached prefix of a request; section 2.2 "Point Lookups": levels are checked in order and
  * the first match is the result).

@@ -124,6 +124,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_bloom_blocks.argtypes = [C.c_uint64, C.c_uint32]
     L.lsm_build_bloom.restype = C.c_int
     L.lsm_build_bloom.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_uint64, C.c_void_p]
+    L.lsm_build_bloom_batch.restype = C.c_int
+    L.lsm_build_bloom_batch.argtypes = [C.POINTER(_Run), C.POINTER(C.c_void_p), C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p]
     L.lsm_probe.restype = C.c_int
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
     L.lsm_probe_length.restype = C.c_int
@@ -275,6 +277,27 @@ def lsm_build_bloom(run: torch.Tensor, bits_per_key: int = 16, out: Optional[tor
     if rc != 0:
         raise LsmError(rc, "lsm_build_bloom")
     return out
+
+
+def lsm_build_bloom_batch(runs: Sequence[torch.Tensor], bits_per_key: int = 16, stream=None) -> List[torch.Tensor]:
+    """Bloom filters of several runs in one call; returns one int32 [n_blocks_j, 4] tensor per run (slices of one
+    allocation)."""
+    L = _load()
+    if not runs:
+        return []
+    blocks = [lsm_bloom_blocks(int(_dev(r, "run").shape[0]), bits_per_key) for r in runs]
+    all_f = torch.empty((sum(blocks), 4), dtype=torch.int32, device=runs[0].device)
+    outs, at = [], 0
+    for b in blocks:
+        outs.append(all_f[at:at + b])
+        at += b
+    rd = (_Run * len(runs))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
+    fp = (C.c_void_p * len(runs))(*[o.data_ptr() for o in outs])
+    nb = (C.c_uint64 * len(runs))(*blocks)
+    rc = L.lsm_build_bloom_batch(rd, fp, nb, len(runs), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_build_bloom_batch")
+    return outs
 
 
 @dataclass

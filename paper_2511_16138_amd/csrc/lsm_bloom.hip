@@ -25,6 +25,37 @@ __global__ void bloom_insert_kernel(const lsm_entry_t* entries, uint64_t n, uint
     }
 }
 
+// The same two steps for up to kBloomBatch runs per launch (blockIdx.y = run), for the many small runs that a round of
+// flushes into several trees produces.
+constexpr uint32_t kBloomBatch = 64;
+struct BloomJobs {
+    const lsm_entry_t* entries[kBloomBatch];
+    uint64_t n[kBloomBatch];
+    uint32_t* words[kBloomBatch];
+    uint32_t n_blocks[kBloomBatch];
+};
+
+__global__ void bloom_clear_batch_kernel(BloomJobs jobs) {
+    uint4* blocks = reinterpret_cast<uint4*>(jobs.words[blockIdx.y]);
+    const uint64_t n_blocks = jobs.n_blocks[blockIdx.y], stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_blocks; i += stride) blocks[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void bloom_insert_batch_kernel(BloomJobs jobs) {
+    const lsm_entry_t* entries = jobs.entries[blockIdx.y];
+    uint32_t* words = jobs.words[blockIdx.y];
+    const uint64_t n = jobs.n[blockIdx.y], stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint32_t n_blocks = jobs.n_blocks[blockIdx.y];
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint4 mask;
+        const uint32_t block = bloom_block(bloom_hash(load_key(entries + i), mask), n_blocks);
+        unsigned long long* w = reinterpret_cast<unsigned long long*>(words + (uint64_t)block * 4);
+        const unsigned long long lo = ((unsigned long long)mask.y << 32) | mask.x, hi = ((unsigned long long)mask.w << 32) | mask.z;
+        if (lo) atomicOr(w + 0, lo);
+        if (hi) atomicOr(w + 1, hi);
+    }
+}
+
 }  // namespace lsm
 
 extern "C" uint64_t lsm_bloom_blocks(uint64_t n, uint32_t bits_per_key) {
@@ -50,6 +81,39 @@ extern "C" int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t 
         if (blocks > 16384) blocks = 16384;
         hipLaunchKernelGGL(bloom_insert_kernel, dim3((uint32_t)blocks), dim3(256), 0, stream, run->entries, run->n,
                            static_cast<uint32_t*>(filter_out), (uint32_t)n_blocks);
+    }
+    return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+}
+
+extern "C" int lsm_build_bloom_batch(const lsm_run_t* runs, void* const* filters_out, const uint64_t* n_blocks, uint32_t n_runs,
+                                     void* stream_v) {
+    using namespace lsm;
+    if (n_runs == 0) return LSM_OK;
+    if (runs == nullptr || filters_out == nullptr || n_blocks == nullptr) return LSM_ERR_NULL;
+    for (uint32_t j = 0; j < n_runs; j++) {
+        if (filters_out[j] == nullptr || (runs[j].n > 0 && runs[j].entries == nullptr)) return LSM_ERR_NULL;
+        if (n_blocks[j] == 0 || n_blocks[j] >= (1ull << 32)) return LSM_ERR_BAD_ARG;
+        if ((reinterpret_cast<uintptr_t>(filters_out[j]) & 15) != 0 || (reinterpret_cast<uintptr_t>(runs[j].entries) & 63) != 0)
+            return LSM_ERR_BAD_ARG;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    for (uint32_t first = 0; first < n_runs; first += kBloomBatch) {
+        const uint32_t count = n_runs - first < kBloomBatch ? n_runs - first : kBloomBatch;
+        BloomJobs jobs = {};
+        uint64_t most_blocks = 1, most_entries = 0;
+        for (uint32_t j = 0; j < count; j++) {
+            jobs.entries[j] = runs[first + j].entries;
+            jobs.n[j] = runs[first + j].n;
+            jobs.words[j] = static_cast<uint32_t*>(filters_out[first + j]);
+            jobs.n_blocks[j] = (uint32_t)n_blocks[first + j];
+            most_blocks = n_blocks[first + j] > most_blocks ? n_blocks[first + j] : most_blocks;
+            most_entries = runs[first + j].n > most_entries ? runs[first + j].n : most_entries;
+        }
+        uint64_t cx = (most_blocks + 255) / 256, ix = (most_entries + 255) / 256;
+        if (cx > 1024) cx = 1024;
+        if (ix > 4096) ix = 4096;
+        hipLaunchKernelGGL(bloom_clear_batch_kernel, dim3((uint32_t)cx, count), dim3(256), 0, stream, jobs);
+        if (most_entries > 0) hipLaunchKernelGGL(bloom_insert_batch_kernel, dim3((uint32_t)ix, count), dim3(256), 0, stream, jobs);
     }
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

@@ -62,30 +62,32 @@ class GpuBackend:
         return merged
 
     def build_fences(self, run: Any) -> Any:
-        batch = getattr(self, "_batch_fences", None)
-        if batch:
-            f = batch.pop((run.data_ptr(), int(run.shape[0])), None)
-            if f is not None:
-                return f
         fused = getattr(self, "_fused", None)
         if fused is not None and fused[0] == run.data_ptr() and fused[1] == int(run.shape[0]) and fused[1] > 0:
             self._fused = None
             return fused[2]
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
-    def compact_batch(self, jobs: Sequence[Tuple[Sequence[Any], int]]) -> List[Any]:
-        """Independent compactions (of different trees) in one library call; the counts come back in one copy."""
+    def compact_batch(self, jobs: Sequence[Tuple[Sequence[Any], int]]) -> List[LevelRun]:
+        """Independent compactions (of different trees) in one library call, with the fence indices written in the same
+        pass and the Bloom filters of all outputs built by one more call; the counts come back in one copy."""
         outs, n_out, fences = self._b.lsm_compact_batch([(list(runs), flags) for runs, flags in jobs], fence_stride=self.fence_stride)
         counts = n_out.cpu().tolist()
-        merged = []
-        self._batch_fences = {}
+        merged, fence_of = [], []
         for out, n, f in zip(outs, counts, fences):
             if n < 0 or n > out.shape[0]:
                 raise RuntimeError("lsm_compact_batch reported a device-side failure")
             merged.append(out[:n])
-            if n > 0:  # the fence index written in the same pass: handed out when the driver asks for this run's
-                self._batch_fences[(out.data_ptr(), n)] = f[: (n + self.fence_stride - 1) // self.fence_stride]
-        return merged
+            fence_of.append(f[: (n + self.fence_stride - 1) // self.fence_stride])
+        live = [i for i, m in enumerate(merged) if int(m.shape[0]) > 0]
+        blooms = dict(zip(live, self._b.lsm_build_bloom_batch([merged[i] for i in live], self.bloom_bits))) if self.bloom_bits else {}
+        return [LevelRun(m, fence_of[i] if int(m.shape[0]) > 0 else None, blooms.get(i)) for i, m in enumerate(merged)]
+
+    def index_batch(self, runs: Sequence[Any]) -> List[LevelRun]:
+        """Fence indices and Bloom filters of several new runs, the filters in one library call."""
+        fences = [self._b.lsm_build_fences(r.contiguous(), self.fence_stride) for r in runs]
+        blooms = self._b.lsm_build_bloom_batch([r.contiguous() for r in runs], self.bloom_bits) if self.bloom_bits else [None] * len(runs)
+        return [LevelRun(r, f, b) for r, f, b in zip(runs, fences, blooms)]
 
     def flush_buffer(self, buffer: Any) -> Any:
         out, n_out = self._b.lsm_flush_buffer(buffer.contiguous())
@@ -171,13 +173,15 @@ class AdaptiveLsmTree:
         try:
             runs, flags = next(steps)
             while True:
-                runs, flags = steps.send(self.backend.compact(runs, flags))
+                merged = self.backend.compact(runs, flags)
+                runs, flags = steps.send(self._index(merged) if int(merged.shape[0]) > 0 else LevelRun(merged, None))
         except StopIteration:
             pass
 
     def _arrive_steps(self, level: int, newcomer: LevelRun):
         """The same cascade as a generator: yields (runs, flags) for every compaction it needs and is sent the merged
-        run, so that a caller who steps several trees together can run their compactions as one batch."""
+        run with its lookup structures (a LevelRun), so that a caller who steps several trees together can run their
+        compactions - and build their indices - as one batch."""
         while newcomer is not None:
             self._ensure_level(level)
             if (self.level_t[level], self.level_k[level]) != (self.size_ratio, self.runs_per_level):
@@ -193,14 +197,13 @@ class AdaptiveLsmTree:
             flags = LSM_BOTTOMMOST if deeper_empty else 0
             n_in = sum(r.n for r in lv)
             merged = yield [r.run for r in lv], flags
-            self.trace.append(("compact", level + 1, len(lv), n_in, int(merged.shape[0]), flags))
+            self.trace.append(("compact", level + 1, len(lv), n_in, merged.n, flags))
             self.levels[level] = []
-            n_merged = int(merged.shape[0])
-            if n_merged > self.capacity(level):
-                self.trace.append(("move", level + 1, level + 2, n_merged))
-                newcomer, level = self._index(merged), level + 1
-            elif n_merged > 0:
-                self.levels[level] = [self._index(merged)]
+            if merged.n > self.capacity(level):
+                self.trace.append(("move", level + 1, level + 2, merged.n))
+                newcomer, level = merged, level + 1
+            elif merged.n > 0:
+                self.levels[level] = [merged]
 
     # ------------------------------------------------------------------ operations and controller
     def _count(self, writes: int, hits: int, empties: int, blocks: float) -> None:
@@ -256,16 +259,17 @@ class ShardedLsmTrees:
     def flush_all(self, runs: Sequence[Any]) -> None:
         """runs[i]: a sorted run from tree i's write buffer, or None if tree i has nothing to flush now."""
         active = []
-        for tree, run in zip(self.trees, runs):
-            if run is None:
-                continue
-            steps = tree._arrive_steps(0, tree._index(run))
+        arriving = [(tree, run) for tree, run in zip(self.trees, runs) if run is not None]
+        index_batch = getattr(self.backend, "index_batch", None)
+        indexed = index_batch([run for _, run in arriving]) if index_batch else [tree._index(run) for tree, run in arriving]
+        for (tree, _), newcomer in zip(arriving, indexed):
+            steps = tree._arrive_steps(0, newcomer)
             try:
                 active.append((steps, next(steps)))
             except StopIteration:
                 pass
         while active:
-            merged = self.backend.compact_batch([job for _, job in active])
+            merged = self.backend.compact_batch([job for _, job in active])  # LevelRuns: merged run, fences, filter
             still = []
             for (steps, _), m in zip(active, merged):
                 try:

@@ -152,3 +152,4 @@ def test_sharded_trees_with_batched_compactions(oracle):
             for gr, cr in zip(glv, clv.runs):
                 assert np.array_equal(oracle.as_run(gr.run), cr)
                 assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
+                assert np.array_equal(gr.bloom.cpu().numpy().view(np.uint8).reshape(-1, 16), oracle.build_bloom(cr, int(gr.bloom.shape[0])))

@@ -624,3 +624,24 @@ def test_get_batch_under_a_shared_prefix_with_ladder_keys(g, oracle):
         assert cnt[i] == want.shape[0], (i, cnt[i], want.shape[0])
         assert np.array_equal(got[i, : cnt[i]], want), i
     assert max(cnt) > 100 and min(cnt) > 0
+
+
+def test_bloom_filters_of_many_runs_in_one_call(g, oracle, cfg1):
+    """lsm_build_bloom_batch: every filter is byte for byte the checker's filter of that run (and so lsm_build_bloom's)."""
+    print("bloom batch", flush=True)
+    rs = np.random.RandomState(8)
+    src = [r for r in cfg1.runs]
+    runs = []
+    for j in range(70):                      # more than one launch's worth of runs, sizes 0 .. 16,384
+        r = src[j % len(src)]
+        lo = int(rs.randint(0, r.shape[0]))
+        runs.append(r[lo:lo + int(rs.choice([0, 1, 9, 300, 5000, 16384]))].contiguous())
+    for bits in (16, 5):
+        filters = g.lsm_build_bloom_batch(runs, bits)
+        torch.cuda.synchronize()
+        for r, f in zip(runs, filters):
+            assert int(f.shape[0]) == oracle.bloom_blocks(int(r.shape[0]), bits)
+            assert np.array_equal(as_bytes(f).reshape(-1, 16), oracle.build_bloom(r.cpu(), int(f.shape[0])))
+    one = g.lsm_build_bloom(runs[5], 16)
+    assert torch.equal(one, g.lsm_build_bloom_batch(runs, 16)[5])
+    assert g.lsm_build_bloom_batch([], 16) == []

@@ -90,6 +90,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     tr[0].run, tr[0].fence = B._Run(64 * 1000, 100), B._Fence(4096, 1, 64)        # needs 2 fences
     q = B._Queries(4096, 8192, 4, 16)
     assert lib.lsm_probe(C.byref(q), C.byref(B._Tree(tr, 1)), C.byref(hits), None) == -2
+    ptrs, nbs = (C.c_void_p * 2)(64, 128), (C.c_uint64 * 2)(4, 0)
+    two = (B._Run * 2)(fake, fake)
+    assert lib.lsm_build_bloom_batch(two, ptrs, nbs, 2, None) == -2      # a filter of zero blocks
+    assert lib.lsm_build_bloom_batch(None, ptrs, nbs, 2, None) == -1 and lib.lsm_build_bloom_batch(None, None, None, 0, None) == 0
     # batched forms: argument errors before any launch
     rg = B._Ranges(4096, 8192, 3, 4096)
     ro = B._RangeOut(64 * 1000, 4096)
