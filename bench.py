@@ -280,7 +280,7 @@ def main() -> int:
                          "whose HBM bytes are known; it scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the index shards by key range without any exchange); "
+        print("bench.py: the library runs on one GPU only (the index shards by key range without any exchange); "
               "run with --gpus 1", file=sys.stderr)
         return 2
 

@@ -19,7 +19,7 @@ K larger than before: the run already there stays as it is and the newcomer sits
 the level holds more runs than allowed after the arrival, so they are all merged then - the same rule that bounds
 the run count in steady state.  A merged run that exceeds the level's capacity moves down, where the same happens.
 
-Readings (the paper fixes no constants; the same ones are listed in the repository's design notes):
+Readings (the paper fixes no constants):
   * an operation is one inserted sequence (write) or one probe request (read); a probe request that finds no live
     first block is an empty probe; d = mean number of blocks a successful request found;
   * statistics arrive in batches (the writes since the last event, or one probe batch); the window is the shortest
