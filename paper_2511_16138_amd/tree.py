@@ -52,20 +52,26 @@ class GpuBackend:
         import torch
         total = sum(int(r.shape[0]) for r in runs)
         fences = torch.empty(((total + self.fence_stride - 1) // self.fence_stride, 4), dtype=torch.int64, device=runs[0].device)
-        out, n_out = self._b.lsm_compact(list(runs), flags, fences=fences, fence_stride=self.fence_stride)
+        # one workspace for all compactions of this backend (they follow each other on one stream), grown when needed
+        need = self._b.lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs])
+        ws = getattr(self, "_workspace", None)
+        if ws is None or ws.numel() < need or ws.device != runs[0].device:
+            ws = self._workspace = torch.empty(max(2 * need, 1 << 20), dtype=torch.uint8, device=runs[0].device)
+        out, n_out = self._b.lsm_compact(list(runs), flags, fences=fences, fence_stride=self.fence_stride, workspace=ws)
         n = int(n_out.item())
         if n < 0 or n > out.shape[0]:
             raise RuntimeError("lsm_compact reported a device-side failure")
         merged = out[:n]
-        # the compaction wrote the fence index of its output in the same pass: hand it out when asked for this run
-        self._fused = (merged.data_ptr(), n, fences[: (n + self.fence_stride - 1) // self.fence_stride])
+        # the compaction wrote the fence index of its output in the same pass: the driver takes it right after this call
+        self._fused = (merged, fences[: (n + self.fence_stride - 1) // self.fence_stride]) if n > 0 else None
         return merged
 
+    def pop_fused_fences(self, merged: Any) -> Any:
+        """The fence index that the last compact() wrote for its output `merged` (None if it is not that output)."""
+        fused, self._fused = getattr(self, "_fused", None), None
+        return fused[1] if fused is not None and fused[0] is merged else None
+
     def build_fences(self, run: Any) -> Any:
-        fused = getattr(self, "_fused", None)
-        if fused is not None and fused[0] == run.data_ptr() and fused[1] == int(run.shape[0]) and fused[1] > 0:
-            self._fused = None
-            return fused[2]
         return self._b.lsm_build_fences(run.contiguous(), self.fence_stride)
 
     def compact_batch(self, jobs: Sequence[Tuple[Sequence[Any], int]]) -> List[LevelRun]:
@@ -82,12 +88,6 @@ class GpuBackend:
         live = [i for i, m in enumerate(merged) if int(m.shape[0]) > 0]
         blooms = dict(zip(live, self._b.lsm_build_bloom_batch([merged[i] for i in live], self.bloom_bits))) if self.bloom_bits else {}
         return [LevelRun(m, fence_of[i] if int(m.shape[0]) > 0 else None, blooms.get(i)) for i, m in enumerate(merged)]
-
-    def index_batch(self, runs: Sequence[Any]) -> List[LevelRun]:
-        """Fence indices and Bloom filters of several new runs, the filters in one library call."""
-        fences = [self._b.lsm_build_fences(r.contiguous(), self.fence_stride) for r in runs]
-        blooms = self._b.lsm_build_bloom_batch([r.contiguous() for r in runs], self.bloom_bits) if self.bloom_bits else [None] * len(runs)
-        return [LevelRun(r, f, b) for r, f, b in zip(runs, fences, blooms)]
 
     def flush_buffer(self, buffer: Any) -> Any:
         out, n_out = self._b.lsm_flush_buffer(buffer.contiguous())
@@ -159,9 +159,21 @@ class AdaptiveLsmTree:
     def tree_runs(self) -> List[LevelRun]:
         return [r for lv in self.levels for r in lv]
 
+    def _settle(self, lr: LevelRun) -> LevelRun:
+        """A run that comes to rest in a level gets whatever lookup structure it still lacks.  (Runs that are merged
+        away at once - a flushed run arriving at a full level, a run moved down onto another - never get any.)"""
+        if lr.n == 0:
+            return lr
+        if lr.fences is None:
+            lr.fences = self.backend.build_fences(lr.run)
+        build_bloom = getattr(self.backend, "build_bloom", None)
+        if lr.bloom is None and build_bloom:
+            lr.bloom = build_bloom(lr.run)
+        return lr
+
     def flush(self, run: Any) -> None:
         """A sorted run from the write buffer enters level 1."""
-        self._arrive(0, self._index(run))
+        self._arrive(0, LevelRun(run, None))
 
     def flush_unsorted(self, buffer: Any) -> None:
         """The write buffer as it was filled (any order, repeated keys): sorted and deduplicated by the backend first."""
@@ -174,7 +186,8 @@ class AdaptiveLsmTree:
             runs, flags = next(steps)
             while True:
                 merged = self.backend.compact(runs, flags)
-                runs, flags = steps.send(self._index(merged) if int(merged.shape[0]) > 0 else LevelRun(merged, None))
+                pop = getattr(self.backend, "pop_fused_fences", None)
+                runs, flags = steps.send(LevelRun(merged, pop(merged) if pop else None))
         except StopIteration:
             pass
 
@@ -192,6 +205,7 @@ class AdaptiveLsmTree:
             lv.insert(0, newcomer)
             newcomer = None
             if len(lv) <= self.level_k[level]:
+                lv[0] = self._settle(lv[0])
                 return
             deeper_empty = all(len(x) == 0 for x in self.levels[level + 1:])
             flags = LSM_BOTTOMMOST if deeper_empty else 0
@@ -203,7 +217,7 @@ class AdaptiveLsmTree:
                 self.trace.append(("move", level + 1, level + 2, merged.n))
                 newcomer, level = merged, level + 1
             elif merged.n > 0:
-                self.levels[level] = [merged]
+                self.levels[level] = [self._settle(merged)]
 
     # ------------------------------------------------------------------ operations and controller
     def _count(self, writes: int, hits: int, empties: int, blocks: float) -> None:
@@ -259,11 +273,10 @@ class ShardedLsmTrees:
     def flush_all(self, runs: Sequence[Any]) -> None:
         """runs[i]: a sorted run from tree i's write buffer, or None if tree i has nothing to flush now."""
         active = []
-        arriving = [(tree, run) for tree, run in zip(self.trees, runs) if run is not None]
-        index_batch = getattr(self.backend, "index_batch", None)
-        indexed = index_batch([run for _, run in arriving]) if index_batch else [tree._index(run) for tree, run in arriving]
-        for (tree, _), newcomer in zip(arriving, indexed):
-            steps = tree._arrive_steps(0, newcomer)
+        for tree, run in zip(self.trees, runs):
+            if run is None:
+                continue
+            steps = tree._arrive_steps(0, LevelRun(run, None))  # indexed only if it comes to rest (level 1 empty)
             try:
                 active.append((steps, next(steps)))
             except StopIteration:
