@@ -160,8 +160,13 @@ def _dev(t: torch.Tensor, what: str) -> torch.Tensor:
     return t
 
 
+_raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+
+
 def _stream_ptr(stream) -> int:
     if stream is None:
+        if _raw_current_stream is not None:   # the handle alone: building a Stream object costs more than a small launch
+            return int(_raw_current_stream(torch.cuda.current_device()))
         stream = torch.cuda.current_stream()
     return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
 

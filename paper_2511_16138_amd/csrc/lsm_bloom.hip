@@ -56,6 +56,31 @@ __global__ void bloom_insert_batch_kernel(BloomJobs jobs) {
     }
 }
 
+// A filter of at most kBloomSmallBlocks blocks (64 KiB) is built by one workgroup in LDS and written out once: one
+// launch and no global atomics, for the short runs of a tree's upper levels.  blockIdx.y = run.
+constexpr uint32_t kBloomSmallBlocks = 4096;
+constexpr int kBloomSmallThreads = 1024;
+__global__ void __launch_bounds__(kBloomSmallThreads) bloom_small_kernel(BloomJobs jobs) {
+    __shared__ uint32_t f[kBloomSmallBlocks * 4];
+    const lsm_entry_t* entries = jobs.entries[blockIdx.y];
+    const uint64_t n = jobs.n[blockIdx.y];
+    const uint32_t n_blocks = jobs.n_blocks[blockIdx.y];  // <= kBloomSmallBlocks (checked by the host)
+    for (uint32_t w = threadIdx.x; w < n_blocks * 4; w += kBloomSmallThreads) f[w] = 0;
+    __syncthreads();
+    for (uint64_t i = threadIdx.x; i < n; i += kBloomSmallThreads) {
+        uint4 mask;
+        const uint32_t block = bloom_block(bloom_hash(load_key(entries + i), mask), n_blocks);
+        if (mask.x) atomicOr(&f[block * 4 + 0], mask.x);
+        if (mask.y) atomicOr(&f[block * 4 + 1], mask.y);
+        if (mask.z) atomicOr(&f[block * 4 + 2], mask.z);
+        if (mask.w) atomicOr(&f[block * 4 + 3], mask.w);
+    }
+    __syncthreads();
+    uint4* out = reinterpret_cast<uint4*>(jobs.words[blockIdx.y]);
+    const uint4* src = reinterpret_cast<const uint4*>(f);
+    for (uint32_t b = threadIdx.x; b < n_blocks; b += kBloomSmallThreads) out[b] = src[b];
+}
+
 }  // namespace lsm
 
 extern "C" uint64_t lsm_bloom_blocks(uint64_t n, uint32_t bits_per_key) {
@@ -73,6 +98,15 @@ extern "C" int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t 
     if ((reinterpret_cast<uintptr_t>(filter_out) & 15) != 0 || (reinterpret_cast<uintptr_t>(run->entries) & 63) != 0)
         return LSM_ERR_BAD_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    if (n_blocks <= kBloomSmallBlocks) {
+        BloomJobs jobs = {};
+        jobs.entries[0] = run->entries;
+        jobs.n[0] = run->n;
+        jobs.words[0] = static_cast<uint32_t*>(filter_out);
+        jobs.n_blocks[0] = (uint32_t)n_blocks;
+        hipLaunchKernelGGL(bloom_small_kernel, dim3(1, 1), dim3(kBloomSmallThreads), 0, stream, jobs);
+        return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+    }
     uint64_t clear_blocks = (n_blocks + 255) / 256;
     if (clear_blocks > 4096) clear_blocks = 4096;
     hipLaunchKernelGGL(bloom_clear_kernel, dim3((uint32_t)clear_blocks), dim3(256), 0, stream, static_cast<uint4*>(filter_out), n_blocks);
@@ -108,6 +142,10 @@ extern "C" int lsm_build_bloom_batch(const lsm_run_t* runs, void* const* filters
             jobs.n_blocks[j] = (uint32_t)n_blocks[first + j];
             most_blocks = n_blocks[first + j] > most_blocks ? n_blocks[first + j] : most_blocks;
             most_entries = runs[first + j].n > most_entries ? runs[first + j].n : most_entries;
+        }
+        if (most_blocks <= kBloomSmallBlocks) {
+            hipLaunchKernelGGL(bloom_small_kernel, dim3(1, count), dim3(kBloomSmallThreads), 0, stream, jobs);
+            continue;
         }
         uint64_t cx = (most_blocks + 255) / 256, ix = (most_entries + 255) / 256;
         if (cx > 1024) cx = 1024;

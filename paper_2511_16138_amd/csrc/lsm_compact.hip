@@ -2,7 +2,8 @@
 //
 // Kernels, on one stream:
 //   init_kernel       clears the per-call scratch (tile status words) and writes the
-//                     first and last partition rows.
+//                     first and last partition rows (inputs of a few tiles: done by the
+//                     partition launch instead).
 //   partition         one group of lanes per interior tile boundary: multi-sequence selection
 //                     over the k runs.  For target rank r it finds the key x with the largest
 //                     L(x) = sum_j |{e in run j : e.key < x}| that is still <= r, and stores
@@ -40,6 +41,7 @@ constexpr int kRoundItems = 4;                         // outputs per thread in 
 __host__ __device__ inline uint64_t tile_nominal(uint32_t k) { return (uint64_t)kTileCap - k; }
 constexpr uint64_t kCoarseStride = 16;                 // every 16th boundary is searched over whole sequences first
 constexpr uint64_t kSampleStride = 32;                 // one key in 32 is copied for the sampled partition
+constexpr uint64_t kShortRunsTotal = 262144;           // inputs of at most this many entries (16 MiB) are searched as cached data
 constexpr uint64_t kSampledMinTiles = 2048;            // inputs of fewer tiles search the runs directly (measured crossover)
 constexpr uint32_t kSpinLimit = 1u << 22;              // polls of one look-back window before giving up
 
@@ -235,12 +237,24 @@ __device__ __forceinline__ GroupLane group_lane(int group) {
 }
 
 // Direct search over whole runs, for inputs of a few dozen tiles: one launch, one group per interior boundary.
+// kInit: the launch also clears the tile status words and writes the first and last split rows, which saves the
+// separate init launch (a small compaction is then two launches: this one and the merge).  kShort: the runs are
+// short enough to stay in cache, where four-way search steps (half the dependent round trips) are the faster ones.
+template <bool kInit, bool kShort>
 __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, int group) {
+    if (kInit) {
+        const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (uint64_t)gridDim.x * blockDim.x;
+        for (uint64_t t = i; t < n_tiles; t += stride) ws.status[t] = 0;
+        if (i < rt.k) {
+            ws.splits[i] = 0;
+            ws.splits[n_tiles * rt.k + i] = run_len(rt, (uint32_t)i);
+        }
+    }
     const GroupLane g = group_lane(group);
     const uint64_t b = g.slot + 1;
     const bool own = b < n_tiles && g.member < (int)rt.k;
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
-    const uint64_t best = select_split<false>(run, 0, own ? run_len(rt, g.member) : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
+    const uint64_t best = select_split<kShort>(run, 0, own ? run_len(rt, g.member) : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
 }
 
@@ -1125,10 +1139,15 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
     carve(workspace, rt.n, n_runs, &ws);
     const uint64_t n_coarse = coarse_rows(n_tiles);  // boundaries kCoarseStride, 2 * kCoarseStride, ... < n_tiles
 
-    uint32_t init_blocks = (uint32_t)((n_tiles + 255) / 256);
-    if (init_blocks == 0) init_blocks = 1;
-    if (init_blocks > 1024) init_blocks = 1024;
-    hipLaunchKernelGGL(init_kernel, dim3(init_blocks), dim3(256), 0, stream, rt, ws, n_tiles, n_coarse, out->n_out);
+    // a compaction of a few tiles that is not validated: the partition launch does the clearing as well
+    const bool direct = n_tiles > 1 && n_tiles < kSampledMinTiles;
+    const bool fused_init = direct && !(flags & LSM_VALIDATE);
+    if (!fused_init) {
+        uint32_t init_blocks = (uint32_t)((n_tiles + 255) / 256);
+        if (init_blocks == 0) init_blocks = 1;
+        if (init_blocks > 1024) init_blocks = 1024;
+        hipLaunchKernelGGL(init_kernel, dim3(init_blocks), dim3(256), 0, stream, rt, ws, n_tiles, n_coarse, out->n_out);
+    }
 
     if (flags & LSM_VALIDATE) {
         hipLaunchKernelGGL(validate_kernel, dim3(256, n_runs), dim3(256), 0, stream, rt, ws);
@@ -1149,7 +1168,11 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
         if (n_tiles < kSampledMinTiles) {
             // a few dozen boundaries: every one searched over whole runs (a coarse pass first would be a second
             // dependent launch, which costs more than the longer searches)
-            hipLaunchKernelGGL(partition_kernel, blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
+            const bool brief = total <= kShortRunsTotal;
+            if (fused_init && brief) hipLaunchKernelGGL((partition_kernel<true, true>), blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
+            else if (fused_init) hipLaunchKernelGGL((partition_kernel<true, false>), blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
+            else if (brief) hipLaunchKernelGGL((partition_kernel<false, true>), blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
+            else hipLaunchKernelGGL((partition_kernel<false, false>), blocks(n_tiles - 1), dim3(256), 0, stream, rt, ws, n_tiles, group);
         } else {
             uint64_t m_max = 0;
             for (uint32_t j = 0; j < n_runs; j++) m_max = ws.st.m[j] > m_max ? ws.st.m[j] : m_max;
@@ -1486,7 +1509,7 @@ extern "C" int lsm_compact_static(const lsm_run_t* runs, uint32_t n_runs, uint32
     void* ws = nullptr;
     const int rc = lsm::scratch_address(&ws);
     if (rc != LSM_OK) return rc;
-    // every word of the scratch that a call reads is written by that call's own kernels first (init_kernel clears the
-    // tile status words), so what the previous call left behind does not matter
+    // every word of the scratch that a call reads is written by that call's own kernels first (the tile status words are
+    // cleared before the merge), so what the previous call left behind does not matter
     return lsm_compact_remap(runs, n_runs, flags, out, ws, LSM_STATIC_SCRATCH_BYTES, stream, nullptr, nullptr);
 }
