@@ -121,6 +121,46 @@ def probe_useful_bytes(nb, hit_len, hits, n_runs: int, filtered: bool, stride: i
     return keys * 48 + (searched_for_found + int(first_miss) * n_runs) * per_search
 
 
+def filter_pipeline(g, torch, dev, runs, out, n_out_d, ws, fences, n_out: int):
+    """What a compaction costs when the new run also gets its fence index and its Bloom filter (16 bits per key): the
+    merge writes the fence keys and the keys' filter hashes in its own pass and the filter is built from the hashes;
+    beside it the two separate builds from the finished run (from hashes computed by a pass over the run; by atomic
+    operations on the filter).  Medians of five runs each."""
+    import statistics
+    n_in = int(out.shape[0])
+    hashes = torch.empty(n_in, dtype=torch.int64, device=dev)
+    n_blocks = g.lsm_bloom_blocks(n_out, 16)
+    bws = torch.empty(max(g.lsm_bloom_workspace_bytes(n_out, n_blocks), 256), dtype=torch.uint8, device=dev)
+    f_hashed = torch.empty((n_blocks, 4), dtype=torch.int32, device=dev)
+    f_atomic = torch.empty((n_blocks, 4), dtype=torch.int32, device=dev)
+    h2 = torch.empty(n_out, dtype=torch.int64, device=dev)
+
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return statistics.median(ts)
+
+    ms_compact = timed(lambda: g.lsm_compact(runs, g.LSM_BOTTOMMOST, out=out, n_out=n_out_d, workspace=ws, fences=fences, fence_stride=64,
+                                             key_hashes=hashes))
+    assert int(n_out_d.item()) == n_out
+    ms_hashed = timed(lambda: g.lsm_build_bloom_hashed(hashes[:n_out], n_blocks, out=f_hashed, workspace=bws))
+    ms_hash_keys = timed(lambda: g.lsm_hash_keys(out[:n_out], out=h2))
+    ms_atomic = timed(lambda: g.lsm_build_bloom(out[:n_out], 16, out=f_atomic))
+    assert torch.equal(f_hashed, f_atomic) and torch.equal(h2, hashes[:n_out]), "the two filter builds disagree"
+    return {"workload": "the same compaction, new run with fence index and Bloom filter (16 bits per key, %d blocks)" % n_blocks,
+            "compact_writing_fences_and_key_hashes_ms": ms_compact, "filter_from_hashes_ms": ms_hashed,
+            "total_ms": ms_compact + ms_hashed, "merged_entries_per_s": n_in / ((ms_compact + ms_hashed) * 1e-3),
+            "separate_builds": {"hash_keys_pass_over_the_run_ms": ms_hash_keys, "filter_by_atomics_ms": ms_atomic}}
+
+
 def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     """Lookup-heavy configuration: batches of 4,096 longest-prefix requests (Zipf(0.99) prefixes, 30 % misses,
     up to 256 block keys each) against the 5-level, 100M-entry tree.  Returns probes/s and key lookups/s (medians over
@@ -130,7 +170,13 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     plain = [g.TreeRun(r, g.lsm_build_fences(r, 64), 64, i + 1) for i, r in enumerate(w.runs)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    filtered = [g.TreeRun(t.run, t.fences, 64, t.level, g.lsm_build_bloom(t.run, 16)) for t in plain]
+    filtered = []
+    for t in plain:   # long runs: from the keys' hashes; short ones: one workgroup
+        n = int(t.run.shape[0])
+        n_blocks = g.lsm_bloom_blocks(n, 16)
+        bloom = (g.lsm_build_bloom_hashed(g.lsm_hash_keys(t.run), n_blocks) if n >= (1 << 20) and g.lsm_bloom_workspace_bytes(n, n_blocks)
+                 else g.lsm_build_bloom(t.run, 16))
+        filtered.append(g.TreeRun(t.run, t.fences, 64, t.level, bloom))
     torch.cuda.synchronize()
     bloom_build_ms = (time.perf_counter() - t0) * 1e3
     batches = [lsm.queries_config4(w, 4096, stream=b) for b in range(n_batches)]
@@ -412,6 +458,7 @@ def main() -> int:
     result["copy_ceiling_gbps"] = copy_gbps
     result["compact_frac_of_copy_ceiling"] = result["compact_hbm_gbps"] / copy_gbps
     del src, dst
+    result["filter_pipeline"] = filter_pipeline(g, torch, dev, runs, out, n_out_d, ws, fences, n_out)
     cpu_sample = None if args.no_cpu_baseline else [r.cpu() for r in runs]  # the whole workload: a few seconds for the checker
     del runs, out, fences, q, hits, w
     torch.cuda.empty_cache()

@@ -100,6 +100,12 @@ typedef struct {
      * keys of 32 bytes, of which the first ceil(*n_out / fence_stride) are written; NULL = none. */
     uint8_t* fence_keys;
     uint32_t fence_stride; /* > 0 if fence_keys is given */
+    /* Optional: key_hashes[i] = the filter hash h (see lsm_bloom_t) of output entry i, written in the same
+     * pass, so that the filter of the new run can be built by lsm_build_bloom_hashed without reading the
+     * run again.  DEVICE, 8-byte aligned, room for `capacity` values; NULL = none.  Honoured by lsm_compact,
+     * lsm_compact_timed, lsm_compact_remap and lsm_compact_static; lsm_flush_buffer and lsm_compact_batch
+     * reject a request for it (LSM_ERR_BAD_ARG): their outputs are short. */
+    uint64_t* key_hashes;
 } lsm_out_t;
 
 /* Fence index of a run: fence i is the key of entry i*stride. */
@@ -279,6 +285,23 @@ int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t n_blocks, v
  * Errors as lsm_build_bloom.
  */
 int lsm_build_bloom_batch(const lsm_run_t* runs, void* const* filters_out, const uint64_t* n_blocks, uint32_t n_runs, void* stream);
+
+/*
+ * lsm_hash_keys, lsm_build_bloom_hashed -- the same filter for a long run, built from the keys' hashes without
+ * read-modify-write traffic on the filter (section 2.2 has every new run carry a filter, so the build is part
+ * of every compaction's cost).  lsm_hash_keys writes hashes_out[i] = h of entry i's key (the h of lsm_bloom_t;
+ * DEVICE, 8-byte aligned, run->n values); lsm_compact can write the same values for its output in its own
+ * pass (lsm_out_t.key_hashes).  lsm_build_bloom_hashed sorts the n hashes into ranges of 4,096 filter blocks
+ * inside the workspace, builds each range in on-chip memory and writes it once; filter_out as for
+ * lsm_build_bloom and with the same bytes as its result.  The hashes are only read.
+ * lsm_bloom_workspace_bytes(n, n_blocks): bytes the build needs (DEVICE, 256-byte aligned, about 8 n), or 0
+ * when it does not apply (n >= 2^32, n_blocks == 0 or more than 2^25 blocks: use lsm_build_bloom).
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (as lsm_build_bloom; not applicable), LSM_ERR_WORKSPACE, LSM_ERR_HIP.
+ */
+size_t lsm_bloom_workspace_bytes(uint64_t n, uint64_t n_blocks);
+int lsm_hash_keys(const lsm_run_t* run, uint64_t* hashes_out, void* stream);
+int lsm_build_bloom_hashed(const uint64_t* hashes, uint64_t n, void* filter_out, uint64_t n_blocks, void* workspace,
+                           size_t workspace_bytes, void* stream);
 
 /*
  * lsm_probe -- batched longest-cached-prefix lookup (appendix B "Probe": find the longest

@@ -41,7 +41,7 @@ class _Run(C.Structure):
 
 class _Out(C.Structure):
     _fields_ = [("entries", C.c_void_p), ("capacity", C.c_uint64), ("n_out", C.c_void_p), ("fence_keys", C.c_void_p),
-                ("fence_stride", C.c_uint32)]
+                ("fence_stride", C.c_uint32), ("key_hashes", C.c_void_p)]
 
 
 class _Fence(C.Structure):
@@ -126,6 +126,12 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_build_bloom.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_uint64, C.c_void_p]
     L.lsm_build_bloom_batch.restype = C.c_int
     L.lsm_build_bloom_batch.argtypes = [C.POINTER(_Run), C.POINTER(C.c_void_p), C.POINTER(C.c_uint64), C.c_uint32, C.c_void_p]
+    L.lsm_bloom_workspace_bytes.restype = C.c_size_t
+    L.lsm_bloom_workspace_bytes.argtypes = [C.c_uint64, C.c_uint64]
+    L.lsm_hash_keys.restype = C.c_int
+    L.lsm_hash_keys.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_void_p]
+    L.lsm_build_bloom_hashed.restype = C.c_int
+    L.lsm_build_bloom_hashed.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]
     L.lsm_probe.restype = C.c_int
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
     L.lsm_probe_length.restype = C.c_int
@@ -183,12 +189,14 @@ def lsm_compact_workspace_bytes(run_lens: Sequence[int]) -> int:
 def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torch.Tensor] = None,
                 n_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None,
                 events: Optional[Tuple[int, int, int]] = None, remap: Optional[torch.Tensor] = None,
-                fences: Optional[torch.Tensor] = None, fence_stride: int = 64) -> Tuple[torch.Tensor, torch.Tensor]:
+                fences: Optional[torch.Tensor] = None, fence_stride: int = 64,
+                key_hashes: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """Merge sorted runs (runs[0] newest).  Returns (out, n_out): out is int64 [capacity, 8]
     whose first n_out rows are the result, n_out a one-element int64 tensor on the device.
     `events` = three raw hipEvent_t handles (or 0) for lsm_compact_timed; `remap` = int64 [n_files]
     table of new pointer bases for lsm_compact_remap; `fences` = int64 [>= ceil(capacity / fence_stride), 4]
-    that receives the fence index of the result (its first ceil(n_out / fence_stride) rows)."""
+    that receives the fence index of the result (its first ceil(n_out / fence_stride) rows); `key_hashes` = int64
+    [>= capacity] that receives the filter hash of every output key (for lsm_build_bloom_hashed)."""
     L = _load()
     runs = [_dev(r, "run") for r in runs]
     total = sum(int(r.shape[0]) for r in runs)
@@ -202,7 +210,10 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
     od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
-              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0)
+              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0,
+              _dev(key_hashes, "key hashes").data_ptr() if key_hashes is not None else None)
+    if key_hashes is not None and key_hashes.numel() < out.shape[0]:
+        raise ValueError("key_hashes is too short for the output capacity")
     if fences is not None and fence_stride > 0 and fences.shape[0] * fence_stride < out.shape[0]:
         raise ValueError("fences is too short for the output capacity")
     ws_ptr, ws_bytes = _dev(workspace, "workspace").data_ptr(), workspace.numel() * workspace.element_size()
@@ -222,13 +233,15 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
 
 
 def lsm_compact_static(runs: Sequence[torch.Tensor], flags: int, out: torch.Tensor, n_out: torch.Tensor, stream=None,
-                       fences: Optional[torch.Tensor] = None, fence_stride: int = 64) -> Tuple[torch.Tensor, torch.Tensor]:
+                       fences: Optional[torch.Tensor] = None, fence_stride: int = 64,
+                       key_hashes: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """lsm_compact on the library's own static scratch: nothing is allocated, here or in the library, so the caller
     passes every buffer (out int64 [capacity, 8], n_out int64 [1])."""
     runs = [_dev(r, "run") for r in runs]
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
     od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
-              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0)
+              _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0,
+              _dev(key_hashes, "key hashes").data_ptr() if key_hashes is not None else None)
     rc = _load().lsm_compact_static(rd, len(runs), flags, C.byref(od), _stream_ptr(stream))
     if rc != 0:
         raise LsmError(rc, "lsm_compact_static")
@@ -281,6 +294,40 @@ def lsm_build_bloom(run: torch.Tensor, bits_per_key: int = 16, out: Optional[tor
     rc = L.lsm_build_bloom(C.byref(rd), _dev(out, "bloom filter").data_ptr(), int(out.shape[0]), _stream_ptr(stream))
     if rc != 0:
         raise LsmError(rc, "lsm_build_bloom")
+    return out
+
+
+def lsm_bloom_workspace_bytes(n: int, n_blocks: int) -> int:
+    return int(_load().lsm_bloom_workspace_bytes(n, n_blocks))
+
+
+def lsm_hash_keys(run: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """The filter hash of every key of a run; returns int64 [n]."""
+    n = int(_dev(run, "run").shape[0])
+    if out is None:
+        out = torch.empty(n, dtype=torch.int64, device=run.device)
+    rd = _Run(run.data_ptr(), n)
+    rc = _load().lsm_hash_keys(C.byref(rd), _dev(out, "key hashes").data_ptr(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_hash_keys")
+    return out
+
+
+def lsm_build_bloom_hashed(hashes: torch.Tensor, n_blocks: int, out: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Bloom filter of the keys whose hashes are given (int64 [n], from lsm_hash_keys or lsm_compact's key_hashes);
+    returns int32 [n_blocks, 4], the same bytes as lsm_build_bloom on the run."""
+    L = _load()
+    n = int(_dev(hashes, "key hashes").shape[0])
+    if out is None:
+        out = torch.empty((n_blocks, 4), dtype=torch.int32, device=hashes.device)
+    need = int(L.lsm_bloom_workspace_bytes(n, int(out.shape[0])))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=hashes.device)
+    rc = L.lsm_build_bloom_hashed(hashes.data_ptr(), n, _dev(out, "bloom filter").data_ptr(), int(out.shape[0]),
+                                  _dev(workspace, "workspace").data_ptr(), workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_build_bloom_hashed")
     return out
 
 

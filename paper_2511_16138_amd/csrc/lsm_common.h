@@ -155,9 +155,13 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x) {
     return x;
 }
 // the hash h of a key (its top half picks the block) and the six bits as four 32-bit masks
-__device__ __forceinline__ uint64_t bloom_hash(const Key& k, uint4& mask) {
+// h of a key, and the six bits (as a 128-bit mask) that h selects inside its block
+__device__ __forceinline__ uint64_t bloom_key_hash(const Key& k) {
     uint64_t h = 0x5EED251116138ull;
     for (int i = 0; i < 4; i++) h = mix64(h ^ k.w[i]);
+    return h;
+}
+__device__ __forceinline__ uint4 bloom_mask(uint64_t h) {
     const uint64_t g = mix64(h ^ 0x9E3779B97F4A7C15ull);
     uint32_t m[4] = {0, 0, 0, 0};
 #pragma unroll
@@ -166,7 +170,11 @@ __device__ __forceinline__ uint64_t bloom_hash(const Key& k, uint4& mask) {
 #pragma unroll
         for (int w = 0; w < 4; w++) m[w] |= (b >> 5) == (uint32_t)w ? 1u << (b & 31) : 0u;
     }
-    mask = make_uint4(m[0], m[1], m[2], m[3]);
+    return make_uint4(m[0], m[1], m[2], m[3]);
+}
+__device__ __forceinline__ uint64_t bloom_hash(const Key& k, uint4& mask) {
+    const uint64_t h = bloom_key_hash(k);
+    mask = bloom_mask(h);
     return h;
 }
 __device__ __forceinline__ uint32_t bloom_block(uint64_t h, uint32_t n_blocks) { return (uint32_t)(((h >> 32) * (uint64_t)n_blocks) >> 32); }

@@ -402,6 +402,8 @@ struct JobDesc {       // one compaction of a batch (device memory, written by t
 static_assert(sizeof(JobDesc) == 64, "descriptor layout");
 
 struct ModeArgs {
+    // single form: optional filter hashes of the output's keys (kExtras = 2)
+    uint64_t* key_hashes;
     // range form
     const uint8_t* lo_keys;   // [n_tiles x 32]
     const uint8_t* hi_keys;
@@ -534,12 +536,16 @@ __device__ __forceinline__ uint64_t lower_bound_from(const lsm_entry_t* run, uin
 }
 
 // two workgroups per compute unit = four waves per SIMD: at most 128 vector registers.
-// kExtras: the output pass also rewrites value pointers and / or writes the fence index (compiled out otherwise).
-template <bool kExtras, int kMode>
+// kExtras: what else the output pass does (compiled out otherwise).  1: rewrites value pointers and / or writes the fence
+// index; 2: also writes the filter hash of every survivor's key.
+template <int kExtras, int kMode>
 __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) merge_kernel(RunTable rt, Workspace ws, uint64_t n_tiles, uint32_t flags_arg,
                                                                lsm_entry_t* out_arg, uint64_t* n_out_arg, const uint64_t* remap_base,
                                                                uint32_t remap_files, uint4* fence_out_arg, uint32_t fence_stride_arg, ModeArgs ma) {
     __shared__ MergeShared s;
+    // staging of the survivors' filter hashes (kExtras = 2): the first half lives in s.rank, which is dead by then
+    __shared__ uint64_t hash_stage_upper[kExtras == 2 ? kStageEntries / 2 : 1];
+    static_assert(sizeof(s.rank) == sizeof(uint64_t) * (kStageEntries / 2), "s.rank holds half a pass of hashes");
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -1010,6 +1016,13 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 if (slot < (uint32_t)kStageEntries) {
 #pragma unroll
                     for (int part = 0; part < 4; part++) stage[slot * 4 + (part ^ (slot & 3))] = ent[i][part];
+                    // the filter hash of the survivor's key travels with it (paper section 2.2: a new run gets its Bloom
+                    // filter; the filter is then built from these 8-byte values, not from the run)
+                    if (kExtras == 2 && kMode == kModeSingle && ma.key_hashes != nullptr) {
+                        const uint64_t h = bloom_key_hash(key_from_raw(ent[i][0], ent[i][1]));
+                        if (slot < (uint32_t)kStageEntries / 2) reinterpret_cast<uint64_t*>(s.rank)[slot] = h;
+                        else hash_stage_upper[slot - kStageEntries / 2] = h;
+                    }
                 }
             }
         }
@@ -1031,6 +1044,11 @@ __global__ void __launch_bounds__(kMergeThreads) __attribute__((amdgpu_waves_per
                 const uint64_t at = base + first + (c >> 2);
                 if (at % fence_stride == 0) fence_out[(at / fence_stride) * 2 + part] = v;
             }
+        }
+        if (kExtras == 2 && kMode == kModeSingle && ma.key_hashes != nullptr) {
+            for (uint32_t c = tid; c < count; c += kMergeThreads)
+                ma.key_hashes[base + first + c] = c < (uint32_t)kStageEntries / 2 ? reinterpret_cast<const uint64_t*>(s.rank)[c]
+                                                                                  : hash_stage_upper[c - kStageEntries / 2];
         }
         first += kStageEntries;
         if (first < total) __syncthreads();  // the stage is reused
@@ -1189,11 +1207,16 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
     if (n_tiles > 0) {
         uint4* const fence_out = reinterpret_cast<uint4*>(out->fence_keys);
         const uint32_t fence_stride = out->fence_keys ? out->fence_stride : 1u;
-        if (remap_files != 0 || fence_out != nullptr)
-            hipLaunchKernelGGL((merge_kernel<true, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+        ModeArgs extras = {};
+        extras.key_hashes = out->key_hashes;
+        if (out->key_hashes != nullptr)
+            hipLaunchKernelGGL((merge_kernel<2, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+                               out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride, extras);
+        else if (remap_files != 0 || fence_out != nullptr)
+            hipLaunchKernelGGL((merge_kernel<1, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
                                out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride, ModeArgs{});
         else
-            hipLaunchKernelGGL((merge_kernel<false, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
+            hipLaunchKernelGGL((merge_kernel<0, kModeSingle>), dim3((uint32_t)n_tiles), dim3(kMergeThreads), 0, stream, rt, ws, n_tiles, flags,
                                out->entries, out->n_out, remap_base, remap_files, fence_out, fence_stride, ModeArgs{});
     }
     if (ev && ev->after_merge && hipEventRecord(static_cast<hipEvent_t>(ev->after_merge), stream) != hipSuccess)
@@ -1256,6 +1279,7 @@ extern "C" int lsm_compact_remap(const lsm_run_t* runs, uint32_t n_runs, uint32_
     if (out->capacity < total) return LSM_ERR_CAPACITY;
     if (out->fence_keys != nullptr && (out->fence_stride == 0 || (reinterpret_cast<uintptr_t>(out->fence_keys) & 15) != 0))
         return LSM_ERR_BAD_ARG;
+    if ((reinterpret_cast<uintptr_t>(out->key_hashes) & 7) != 0) return LSM_ERR_BAD_ARG;
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 ||
         workspace_bytes < lsm_compact_workspace_bytes(rt.n, n_runs))
         return LSM_ERR_WORKSPACE;
@@ -1295,7 +1319,7 @@ extern "C" int lsm_range_scan(const lsm_ranges_t* ranges, const lsm_tree_t* tree
     ma.counts = out->counts;
     ma.max_entries = ranges->max_entries;
     Workspace ws = {};
-    hipLaunchKernelGGL((merge_kernel<false, kModeRange>), dim3(ranges->n_ranges), dim3(kMergeThreads), 0, static_cast<hipStream_t>(stream_v), rt, ws,
+    hipLaunchKernelGGL((merge_kernel<0, kModeRange>), dim3(ranges->n_ranges), dim3(kMergeThreads), 0, static_cast<hipStream_t>(stream_v), rt, ws,
                        (uint64_t)ranges->n_ranges, (uint32_t)LSM_BOTTOMMOST, out->entries, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u,
                        (uint4*)nullptr, 1u, ma);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
@@ -1352,6 +1376,7 @@ static int batch_layout(const lsm_compact_job_t* jobs, uint32_t n_jobs, BatchLay
         if (job.n_runs == 0 || job.n_runs > LSM_MAX_RUNS || (job.flags & LSM_VALIDATE)) return LSM_ERR_BAD_ARG;
         if (job.out.fence_keys != nullptr && (job.out.fence_stride == 0 || (reinterpret_cast<uintptr_t>(job.out.fence_keys) & 15) != 0))
             return LSM_ERR_BAD_ARG;
+        if (job.out.key_hashes != nullptr) return LSM_ERR_BAD_ARG;  // filters of a batch: lsm_build_bloom_batch
         uint64_t total = 0;
         for (uint32_t r = 0; r < job.n_runs; r++) total += job.runs[r].n;
         uint64_t nt = tiles_for(total, job.n_runs);
@@ -1465,10 +1490,10 @@ extern "C" int lsm_compact_batch(const lsm_compact_job_t* jobs, uint32_t n_jobs,
     RunTable rt = {};
     rt.k = 1;
     if (any_fences)  // the form that also writes fence indices (a job without one has a null pointer in its descriptor)
-        hipLaunchKernelGGL((merge_kernel<true, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
+        hipLaunchKernelGGL((merge_kernel<1, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
                            (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
     else
-        hipLaunchKernelGGL((merge_kernel<false, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
+        hipLaunchKernelGGL((merge_kernel<0, kModeBatch>), dim3((uint32_t)l.tiles), dim3(kMergeThreads), 0, stream, rt, ws, l.tiles, 0u,
                            (lsm_entry_t*)nullptr, (uint64_t*)nullptr, (const uint64_t*)nullptr, 0u, (uint4*)nullptr, 1u, ma);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

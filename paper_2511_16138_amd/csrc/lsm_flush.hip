@@ -140,6 +140,7 @@ extern "C" int lsm_flush_buffer(const lsm_entry_t* buffer, uint64_t n, const lsm
     if ((reinterpret_cast<uintptr_t>(buffer) & 63) != 0 || (reinterpret_cast<uintptr_t>(out->entries) & 63) != 0) return LSM_ERR_BAD_ARG;
     if (out->fence_keys != nullptr && (out->fence_stride == 0 || (reinterpret_cast<uintptr_t>(out->fence_keys) & 15) != 0))
         return LSM_ERR_BAD_ARG;
+    if (out->key_hashes != nullptr) return LSM_ERR_BAD_ARG;  // the filter of a flushed run: lsm_build_bloom
     if (out->capacity < n) return LSM_ERR_CAPACITY;
     const bool direct = n <= kFlushDirect;
     if (n > 0 && (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & (direct ? 3 : 255)) != 0 ||

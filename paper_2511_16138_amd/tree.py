@@ -94,7 +94,15 @@ class GpuBackend:
         return out[: int(n_out.item())]
 
     def build_bloom(self, run: Any) -> Any:
-        return self._b.lsm_build_bloom(run.contiguous(), self.bloom_bits) if self.bloom_bits else None
+        if not self.bloom_bits:
+            return None
+        run = run.contiguous()
+        n = int(run.shape[0])
+        n_blocks = self._b.lsm_bloom_blocks(n, self.bloom_bits)
+        # a long run: the filter is built from the keys' hashes, sorted by block range (no atomic traffic on the filter)
+        if n >= (1 << 20) and self._b.lsm_bloom_workspace_bytes(n, n_blocks):
+            return self._b.lsm_build_bloom_hashed(self._b.lsm_hash_keys(run), n_blocks)
+        return self._b.lsm_build_bloom(run, self.bloom_bits)
 
     def probe(self, qkeys: Any, n_blocks: Any, tree: Sequence[LevelRun]) -> Tuple[Any, Any]:
         tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i, t.bloom) for i, t in enumerate(tree)]

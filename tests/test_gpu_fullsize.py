@@ -72,6 +72,8 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
     torch.cuda.synchronize()
     for t, r in zip(filtered, runs_cpu):
         assert np.array_equal(as_bytes(t.bloom).reshape(-1, 16), oracle.build_bloom(r, int(t.bloom.shape[0])))
+        # the build from the keys' hashes (thousands of block ranges on the 90M-entry level) gives the same bytes
+        assert torch.equal(g.lsm_build_bloom_hashed(g.lsm_hash_keys(t.run), int(t.bloom.shape[0])), t.bloom)
     t0, misses, requests = time.time(), 0, 0
     for stream in range(256):
         q, nb = lsm.queries_config4(w, 4096, stream=stream)

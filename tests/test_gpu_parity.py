@@ -362,6 +362,67 @@ def test_fence_index_written_by_the_compaction(g, oracle, cfg1, stride):
         assert bool((fences[n_f:] == -1).all())  # nothing written past the end
 
 
+@pytest.mark.parametrize("case", ["cfg1", "one_tile", "empty", "sampled"])
+def test_filter_hashes_written_by_the_compaction(g, oracle, cfg1, case):
+    """The key hashes lsm_compact writes along with the run are those lsm_hash_keys gives for the merged run, and the
+    filter lsm_build_bloom_hashed builds from them is byte for byte the checker's filter of the merged run (so also
+    lsm_build_bloom's); fences asked for in the same call are written as well."""
+    from workloads import lsm
+    print("key hashes from the compaction", case, flush=True)
+    if case == "cfg1":
+        runs = list(cfg1.runs)
+    elif case == "one_tile":
+        runs = [cfg1.runs[0][:700].contiguous(), cfg1.runs[1][:300].contiguous()]
+    elif case == "empty":
+        runs = [cfg1.runs[0][:0].contiguous()]
+    else:
+        runs = lsm.config3(device=dev(), scale=12).runs   # 5.6M entries: the sampled partition, thousands of tiles
+    total = sum(int(r.shape[0]) for r in runs)
+    for flags, bits in ((1, 16), (0, 7)):
+        hashes = torch.full((max(total, 1),), -1, dtype=torch.int64, device=dev())
+        fences = torch.full(((max(total, 1) + 63) // 64, 4), -1, dtype=torch.int64, device=dev()) if flags else None
+        out, n_out = g.lsm_compact(runs, flags, key_hashes=hashes, fences=fences, fence_stride=64)
+        torch.cuda.synchronize()
+        n = int(n_out.item())
+        want = oracle.compact([r.cpu() for r in runs], flags & 1)
+        assert n == want.shape[0] and np.array_equal(as_bytes(out[:n]).reshape(-1, 64), want)
+        assert torch.equal(hashes[:n], g.lsm_hash_keys(out[:n]))
+        assert bool((hashes[n:] == -1).all())   # nothing written past the end
+        n_blocks = g.lsm_bloom_blocks(n, bits)
+        assert n_blocks == oracle.bloom_blocks(n, bits)
+        bloom = g.lsm_build_bloom_hashed(hashes[:n], n_blocks, out=torch.full((n_blocks, 4), -1, dtype=torch.int32, device=dev()))
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(bloom).reshape(-1, 16), oracle.build_bloom(want, n_blocks))
+        assert torch.equal(bloom, g.lsm_build_bloom(out[:n], bits))
+        if fences is not None:
+            assert np.array_equal(as_bytes(fences[:(n + 63) // 64]).reshape(-1, 32), oracle.build_fences(want, 64))
+    if case == "cfg1":   # the entry point that allocates nothing takes the same request
+        out = torch.empty((total, 8), dtype=torch.int64, device=dev())
+        n_out = torch.zeros(1, dtype=torch.int64, device=dev())
+        hashes = torch.full((total,), -1, dtype=torch.int64, device=dev())
+        g.lsm_compact_static(runs, 1, out, n_out, key_hashes=hashes)
+        torch.cuda.synchronize()
+        n = int(n_out.item())
+        assert torch.equal(hashes[:n], g.lsm_hash_keys(out[:n]))
+
+
+@pytest.mark.parametrize("n,bits", [(0, 16), (1, 16), (5000, 16), (40_000, 16), (300_000, 16), (300_000, 3), (65_536 * 3 + 17, 10)])
+def test_filter_built_from_hashes_equals_the_checker(g, oracle, n, bits):
+    """lsm_hash_keys + lsm_build_bloom_hashed on runs from one bucket's worth to several chunks and dozens of buckets:
+    the same bytes as the checker's filter, whatever the buffers held before; a filter with more blocks than the key
+    count asks for (as a caller who sizes it from an upper bound would pass) as well."""
+    from workloads import lsm
+    print("hashed bloom", n, bits, flush=True)
+    w = lsm.config3(device=dev(), scale=64)      # 16 runs x 65,536 entries
+    run = torch.cat([r for r in w.runs])[:n].contiguous()   # not sorted across runs: a filter does not care
+    for n_blocks in (g.lsm_bloom_blocks(n, bits), g.lsm_bloom_blocks(n, bits) * 3 + 5):
+        hashes = g.lsm_hash_keys(run)
+        ws = torch.full((max(g.lsm_bloom_workspace_bytes(n, n_blocks), 256),), 0xA5, dtype=torch.uint8, device=dev())
+        got = g.lsm_build_bloom_hashed(hashes, n_blocks, out=torch.full((n_blocks, 4), -1, dtype=torch.int32, device=dev()), workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(got).reshape(-1, 16), oracle.build_bloom(run.cpu(), n_blocks))
+
+
 # ------------------------------------------------------------------ prefix length by search (appendix B)
 def test_probe_length_equals_probe_on_prefix_closed_data(g, oracle, cfg1):
     """The generator evicts leaf first, so its trees are prefix-closed: the search over the prefix length gives the

@@ -36,7 +36,7 @@ def test_every_declared_entry_point_is_exported(lib):
 
 def test_struct_sizes_match_the_header():
     import paper_2511_16138_amd.binding as B
-    assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 40 and C.sizeof(B._Fence) == 24
+    assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 48 and C.sizeof(B._Fence) == 24
     assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 64 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
     assert C.sizeof(B._PolicyInput) == 72
 
@@ -65,6 +65,20 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(fenced), 256 * 7, 1 << 20, None) == -2     # fence stride 0
     odd = B._Out(64 * 2000, 10, C.addressof(n_out), 16 * 5 + 4, 64)
     assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(odd), 256 * 7, 1 << 20, None) == -2        # fence keys misaligned
+    hashed = B._Out(64 * 2000, 10, C.addressof(n_out), None, 0, 8 * 7 + 4)
+    assert lib.lsm_compact(C.byref(fake), 1, 0, C.byref(hashed), 256 * 7, 1 << 20, None) == -2     # key hashes misaligned
+    hashed = B._Out(64 * 2000, 10, C.addressof(n_out), None, 0, 8 * 7)
+    assert lib.lsm_flush_buffer(64 * 10, 10, C.byref(hashed), 256, 1 << 20, None) == -2            # a flush writes no hashes
+    assert lib.lsm_bloom_workspace_bytes(0, 1) > 0 and lib.lsm_bloom_workspace_bytes(10, 0) == 0
+    assert lib.lsm_bloom_workspace_bytes(1 << 32, 1 << 20) == 0 and lib.lsm_bloom_workspace_bytes(10, (1 << 25) + 1) == 0
+    assert 8 * 1_000_000 <= lib.lsm_bloom_workspace_bytes(1_000_000, 125_000) < 8 * 1_000_000 + 4096
+    assert lib.lsm_build_bloom_hashed(None, 5, 16 * 9, 4, 256 * 3, 1 << 20, None) == -1            # no hashes
+    assert lib.lsm_build_bloom_hashed(8 * 3, 5, 16 * 9, 0, 256 * 3, 1 << 20, None) == -2           # no blocks
+    assert lib.lsm_build_bloom_hashed(8 * 3, 5, 16 * 9 + 8, 4, 256 * 3, 1 << 20, None) == -2       # filter misaligned
+    assert lib.lsm_build_bloom_hashed(8 * 3, 5, 16 * 9, 4, 256 * 3, 16, None) == -4                # workspace too small
+    assert lib.lsm_build_bloom_hashed(8 * 3, 5, 16 * 9, 4, 256 * 3 + 8, 1 << 20, None) == -4       # workspace misaligned
+    assert lib.lsm_hash_keys(C.byref(fake), None, None) == -1
+    assert lib.lsm_hash_keys(C.byref(fake), 8 * 5 + 1, None) == -2
     table = B._Remap(None, 3)
     assert lib.lsm_compact_remap(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 1 << 20, None, C.byref(table), None) == -1
     assert lib.lsm_flush_workspace_bytes(3600) == 14400 and lib.lsm_flush_workspace_bytes(1 << 20) == 0
