@@ -205,6 +205,20 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
     ms_len = timed(lambda q, nb: g.lsm_probe_length(q, nb, filtered, hit_len=hit_len))
     assert bool((plain_len == hit_len).all()), "the search over the prefix length gave another length"
     ms_len_plain = timed(lambda q, nb: g.lsm_probe_length(q, nb, plain, hit_len=hit_len))
+    # hash indices on every run (one 64-byte read finds or rules out a key): with the filters, and in their place
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    indices = [g.lsm_build_hash_index(g.lsm_hash_keys(t.run)) for t in plain]
+    torch.cuda.synchronize()
+    index_build_ms = (time.perf_counter() - t0) * 1e3
+    both = [g.TreeRun(t.run, t.fences, 64, t.level, t.bloom, ix) for t, ix in zip(filtered, indices)]
+    ms_ix = timed(lambda q, nb: g.lsm_probe(q, nb, both, hit_len=hit_len, hits=hits))
+    assert bool((plain_len == hit_len).all()), "hash indices changed a probe result"
+    only_ix = [g.TreeRun(t.run, t.fences, 64, t.level, None, ix) for t, ix in zip(plain, indices)]
+    ms_ix_plain = timed(lambda q, nb: g.lsm_probe(q, nb, only_ix, hit_len=hit_len, hits=hits))
+    assert bool((plain_len == hit_len).all()), "hash indices changed a probe result"
+    ms_ix_len = timed(lambda q, nb: g.lsm_probe_length(q, nb, both, hit_len=hit_len))
+    assert bool((plain_len == hit_len).all()), "hash indices changed a prefix length"
     keys = sum(int(nb.sum().item()) for _, nb in batches) / n_batches
     traffic = measured_traffic("probe_kernel_cfg4_filtered", os.path.join(ROOT, "paper_2511_16138_amd", "csrc", "lsm_probe.hip"))
     return {"workload": "configs[3]: 5-level tree of %d entries, batches of 4096 requests, Bloom filters of 16 bits per key on every run"
@@ -219,6 +233,10 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
                                 "useful_gbps": useful_plain / (ms_plain * 1e-3) / 1e9},
             "length_only": {"ms_per_batch": ms_len, "probes_per_s": 4096 / (ms_len * 1e-3),
                             "without_filters_ms_per_batch": ms_len_plain},
+            "with_hash_indices": {"ms_per_batch": ms_ix, "probes_per_s": 4096 / (ms_ix * 1e-3),
+                                  "requested_keys_per_s": keys / (ms_ix * 1e-3),
+                                  "without_filters_ms_per_batch": ms_ix_plain, "length_only_ms_per_batch": ms_ix_len,
+                                  "index_bytes": sum(int(ix.numel()) * 8 for ix in indices), "build_ms_all_runs": index_build_ms},
             "bloom_build_ms_all_runs": bloom_build_ms}
 
 

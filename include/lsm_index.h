@@ -132,11 +132,34 @@ typedef struct {
     uint64_t n_blocks;  /* < 2^32 */
 } lsm_bloom_t;
 
+/*
+ * Hash index of a run (optional; built by lsm_build_hash_index).  Section 2.2 has a point lookup consult a run's
+ * Bloom filter and then its fence pointers; with the run in device memory the fence search is a dozen dependent
+ * reads.  The hash index answers both questions - can the key be in this run, and where - from one 64-byte line:
+ *   n_buckets = lsm_hash_index_buckets(n) = max(1, ceil(n / 4)) buckets of 64 bytes, eight slots each
+ *   a key with filter hash h (the h of lsm_bloom_t) belongs to bucket ((h >> 32) * n_buckets) >> 32; tag = h & 0x7FFF
+ *   bytes  0..15  the slots' tag fields, 16 bits each (little-endian): low 15 bits = tag of the key in the slot
+ *                 (0 for an empty slot); bit 15 is set in the first field only, and only when more than eight
+ *                 keys of the run fall into the bucket ("crowded": it then holds eight of them)
+ *   bytes 16..47  the slots' positions in the run, 32 bits each; 0xFFFFFFFF = empty slot
+ *   bytes 48..63  zero
+ * A key whose tag is in no slot of its uncrowded bucket is not in the run, so a lookup reads the 16 tag bytes where
+ * it would read a filter block, and the index does what the filter does; a lookup that does not find its key in a
+ * crowded bucket searches the fence index instead.  Which eight keys a crowded bucket keeps and the order of the
+ * slots inside a bucket are not defined; lookups give the same answers for every table of this form.  Runs of at
+ * most 2^27 entries.
+ */
+typedef struct {
+    const void* buckets; /* DEVICE, 64-byte aligned, n_buckets x 64 bytes; NULL = none */
+    uint64_t n_buckets;  /* = lsm_hash_index_buckets(run.n) if buckets is given */
+} lsm_hash_index_t;
+
 typedef struct {
     lsm_run_t run;
     lsm_fence_t fence;
     lsm_bloom_t bloom; /* optional: lsm_probe skips the run for keys the filter excludes */
     uint32_t level;    /* informational */
+    lsm_hash_index_t index; /* optional: lsm_probe finds (or rules out) a key in the run without the fence search */
 } lsm_tree_run_t;
 
 /* A tree = its runs ordered NEWEST -> OLDEST (shallow level first; within a level, the most
@@ -302,6 +325,19 @@ size_t lsm_bloom_workspace_bytes(uint64_t n, uint64_t n_blocks);
 int lsm_hash_keys(const lsm_run_t* run, uint64_t* hashes_out, void* stream);
 int lsm_build_bloom_hashed(const uint64_t* hashes, uint64_t n, void* filter_out, uint64_t n_blocks, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/*
+ * lsm_build_hash_index -- the hash index of a run (see lsm_hash_index_t) from the filter hashes of its keys in
+ * run order (hashes[i] belongs to entry i: from lsm_hash_keys, or from lsm_compact's key_hashes).  buckets_out:
+ * DEVICE, 64-byte aligned, lsm_hash_index_buckets(n) x 64 bytes, every byte written.  The hashes are sorted by
+ * ranges of 4,096 buckets inside the workspace and every range is filled by one workgroup (no atomic traffic
+ * on the table).  lsm_hash_index_workspace_bytes(n): DEVICE, 256-byte aligned, about 12 n bytes; 0 when the
+ * build does not apply (n > 2^27).
+ * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (misaligned pointers, n too large), LSM_ERR_WORKSPACE, LSM_ERR_HIP.
+ */
+uint64_t lsm_hash_index_buckets(uint64_t n);
+size_t lsm_hash_index_workspace_bytes(uint64_t n);
+int lsm_build_hash_index(const uint64_t* hashes, uint64_t n, void* buckets_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * lsm_probe -- batched longest-cached-prefix lookup (appendix B "Probe": find the longest

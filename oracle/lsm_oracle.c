@@ -223,6 +223,72 @@ int oracle_bloom_may_contain(const uint8_t* filter, uint64_t n_blocks, const uin
 }
 
 /* ------------------------------------------------------------------------------------
+ * Hash index of a run (the library's own in-memory index beside the filter and the fence pointers of section 2.2;
+ * its format is stated with lsm_hash_index_t in the library's header).  The index is not unique - which eight keys
+ * a crowded bucket keeps and the order of the slots are left open - so the checker does not build one: it decides
+ * whether a given table is a valid index of a given run.
+ *   h(key) as for the filter above; bucket = ((h >> 32) * n_buckets) >> 32; tag = h & 0x7FFF
+ *   n_buckets = max(1, ceil(n / 4)); a bucket is 64 bytes with eight slots:
+ *   bytes 0..15 tag fields (16 bits each, little-endian; bit 15 of the first = crowded, 0 for an empty slot),
+ *   bytes 16..47 positions (32 bits each, all ones = empty), bytes 48..63 zero
+ *   more than 8 keys in a bucket: 8 of them and the crowded bit
+ * Returns 0 for a valid table, else the number of the rule that is broken.
+ * ------------------------------------------------------------------------------------ */
+static uint64_t key_hash(const uint8_t* key) {
+    uint64_t h = 0x5EED251116138ULL;
+    for (int i = 0; i < 4; i++) {
+        uint64_t k = 0;
+        for (int b = 0; b < 8; b++) k = (k << 8) | key[8 * i + b];
+        h = splitmix_out(h ^ k);
+    }
+    return h;
+}
+
+void oracle_key_hashes(const entry_t* run, uint64_t n, uint64_t* out) {
+    for (uint64_t e = 0; e < n; e++) out[e] = key_hash(run[e].key);
+}
+
+uint64_t oracle_hash_index_buckets(uint64_t n) { return n ? (n + 3) / 4 : 1; }
+
+int oracle_hash_index_check(const entry_t* run, uint64_t n, const uint8_t* table, uint64_t n_buckets) {
+    if (n_buckets != oracle_hash_index_buckets(n)) return 1;
+    uint32_t* keys_of = calloc(n_buckets, sizeof(uint32_t)); /* how many keys of the run belong to each bucket */
+    uint8_t* listed = calloc(n ? n : 1, 1);                  /* entry e appears in the table */
+    int rc = 0;
+    for (uint64_t e = 0; e < n; e++) keys_of[((key_hash(run[e].key) >> 32) * n_buckets) >> 32]++;
+    for (uint64_t b = 0; b < n_buckets && rc == 0; b++) {
+        const uint8_t* bucket = table + 64 * b;
+        uint32_t held = 0;
+        const int crowded = (bucket[1] & 0x80) != 0;
+        for (int k = 0; k < 8 && rc == 0; k++) {
+            const uint32_t field = (uint32_t)bucket[2 * k] | (uint32_t)bucket[2 * k + 1] << 8;
+            uint32_t pos = 0;
+            for (int i = 3; i >= 0; i--) pos = pos << 8 | bucket[16 + 4 * k + i];
+            if (k > 0 && (field & 0x8000)) rc = 8; /* bit 15 belongs to the first field only */
+            else if (pos == 0xFFFFFFFFu) {
+                if (field & 0x7FFF) rc = 9; /* an empty slot has tag 0 */
+            } else if (pos >= n) rc = 2;     /* points outside the run */
+            else {
+                const uint64_t h = key_hash(run[pos].key);
+                if ((((h >> 32) * n_buckets) >> 32) != b || (h & 0x7FFF) != (field & 0x7FFF)) rc = 3; /* wrong bucket or wrong tag */
+                else if (listed[pos]) rc = 4;                                                           /* listed twice */
+                else listed[pos] = 1, held++;
+            }
+        }
+        for (int i = 48; i < 64 && rc == 0; i++)
+            if (bucket[i]) rc = 10; /* the rest of the bucket is zero */
+        if (rc) break;
+        if (keys_of[b] <= 8) {
+            if (crowded) rc = 5;                 /* marked crowded without need */
+            else if (held != keys_of[b]) rc = 6; /* a key is missing: a lookup would not find it */
+        } else if (!crowded || held != 8) rc = 7;
+    }
+    free(keys_of);
+    free(listed);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------
  * Cost model of the adaptive controller.
  *   levels   L = smallest integer >= 1 with M * T^L >= N   (L = log_T(N*e/M), in entries)
  *   update   W = T*L / (B*K)

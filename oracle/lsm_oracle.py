@@ -54,6 +54,12 @@ def lib() -> C.CDLL:
         L.oracle_build_bloom.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.oracle_bloom_may_contain.restype = C.c_int
         L.oracle_bloom_may_contain.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+        L.oracle_key_hashes.restype = None
+        L.oracle_key_hashes.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p]
+        L.oracle_hash_index_buckets.restype = C.c_uint64
+        L.oracle_hash_index_buckets.argtypes = [C.c_uint64]
+        L.oracle_hash_index_check.restype = C.c_int
+        L.oracle_hash_index_check.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64]
         L.oracle_levels.restype = C.c_uint32
         L.oracle_levels.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32]
         L.oracle_cost.restype = C.c_double
@@ -150,6 +156,25 @@ def remap_pointers(run, base) -> np.ndarray:
         if int(rec["type"][i]) == 0 and file_id < base.shape[0]:
             rec["vptr"][i] = (int(base[file_id]) + offset) & 0xFFFFFFFFFFFFFFFF
     return out
+
+
+def key_hashes(run) -> np.ndarray:
+    """The filter hash h of every key of a run (uint64 [n]); see the C source."""
+    run = as_run(run)
+    out = np.zeros(run.shape[0], dtype=np.uint64)
+    lib().oracle_key_hashes(run.ctypes.data, run.shape[0], out.ctypes.data)
+    return out
+
+
+def hash_index_buckets(n: int) -> int:
+    return int(lib().oracle_hash_index_buckets(n))
+
+
+def hash_index_check(run, table) -> int:
+    """0 if `table` (bytes, n_buckets x 64) is a valid hash index of the run, else the number of the broken rule."""
+    run = as_run(run)
+    table = np.ascontiguousarray(table).view(np.uint8).reshape(-1, 64)
+    return int(lib().oracle_hash_index_check(run.ctypes.data, run.shape[0], table.ctypes.data, table.shape[0]))
 
 
 def bloom_blocks(n: int, bits_per_key: int) -> int:

@@ -52,8 +52,12 @@ class _Bloom(C.Structure):
     _fields_ = [("blocks", C.c_void_p), ("n_blocks", C.c_uint64)]
 
 
+class _HashIndex(C.Structure):
+    _fields_ = [("buckets", C.c_void_p), ("n_buckets", C.c_uint64)]
+
+
 class _TreeRun(C.Structure):
-    _fields_ = [("run", _Run), ("fence", _Fence), ("bloom", _Bloom), ("level", C.c_uint32)]
+    _fields_ = [("run", _Run), ("fence", _Fence), ("bloom", _Bloom), ("level", C.c_uint32), ("index", _HashIndex)]
 
 
 class _Tree(C.Structure):
@@ -132,6 +136,12 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_hash_keys.argtypes = [C.POINTER(_Run), C.c_void_p, C.c_void_p]
     L.lsm_build_bloom_hashed.restype = C.c_int
     L.lsm_build_bloom_hashed.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.lsm_hash_index_buckets.restype = C.c_uint64
+    L.lsm_hash_index_buckets.argtypes = [C.c_uint64]
+    L.lsm_hash_index_workspace_bytes.restype = C.c_size_t
+    L.lsm_hash_index_workspace_bytes.argtypes = [C.c_uint64]
+    L.lsm_build_hash_index.restype = C.c_int
+    L.lsm_build_hash_index.argtypes = [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     L.lsm_probe.restype = C.c_int
     L.lsm_probe.argtypes = [C.POINTER(_Queries), C.POINTER(_Tree), C.POINTER(_Hits), C.c_void_p]
     L.lsm_probe_length.restype = C.c_int
@@ -331,6 +341,27 @@ def lsm_build_bloom_hashed(hashes: torch.Tensor, n_blocks: int, out: Optional[to
     return out
 
 
+def lsm_hash_index_buckets(n: int) -> int:
+    return int(_load().lsm_hash_index_buckets(n))
+
+
+def lsm_build_hash_index(hashes: torch.Tensor, out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                         stream=None) -> torch.Tensor:
+    """Hash index of the run whose keys' hashes are given in run order (int64 [n], from lsm_hash_keys or lsm_compact's
+    key_hashes); returns int64 [n_buckets, 8]."""
+    L = _load()
+    n = int(_dev(hashes, "key hashes").shape[0])
+    if out is None:
+        out = torch.empty((int(L.lsm_hash_index_buckets(n)), 8), dtype=torch.int64, device=hashes.device)
+    if workspace is None:
+        workspace = torch.empty(max(int(L.lsm_hash_index_workspace_bytes(n)), 256), dtype=torch.uint8, device=hashes.device)
+    rc = L.lsm_build_hash_index(hashes.data_ptr(), n, _dev(out, "hash index").data_ptr(), _dev(workspace, "workspace").data_ptr(),
+                                workspace.numel(), _stream_ptr(stream))
+    if rc != 0:
+        raise LsmError(rc, "lsm_build_hash_index")
+    return out
+
+
 def lsm_build_bloom_batch(runs: Sequence[torch.Tensor], bits_per_key: int = 16, stream=None) -> List[torch.Tensor]:
     """Bloom filters of several runs in one call; returns one int32 [n_blocks_j, 4] tensor per run (slices of one
     allocation)."""
@@ -359,6 +390,7 @@ class TreeRun:
     stride: int = 64
     level: int = 0
     bloom: Optional[torch.Tensor] = None  # int32 [n_blocks, 4] from lsm_build_bloom, or None
+    index: Optional[torch.Tensor] = None  # int64 [n_buckets, 8] from lsm_build_hash_index, or None
 
 
 def _tree_descriptor(tree: Sequence[TreeRun]):
@@ -369,6 +401,8 @@ def _tree_descriptor(tree: Sequence[TreeRun]):
         if t.bloom is not None:
             tr[i].bloom = _Bloom(_dev(t.bloom, "bloom filter").data_ptr(), int(t.bloom.shape[0]))
         tr[i].level = t.level
+        if t.index is not None:
+            tr[i].index = _HashIndex(_dev(t.index, "hash index").data_ptr(), int(t.index.shape[0]))
     return _Tree(tr, len(tree)), tr  # tr must outlive the call
 
 

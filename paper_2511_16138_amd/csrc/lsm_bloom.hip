@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include "lsm_common.h"
+#include "lsm_partition.h"
 
 namespace lsm {
 
@@ -83,82 +84,16 @@ __global__ void __launch_bounds__(kBloomSmallThreads) bloom_small_kernel(BloomJo
 
 // ---------------------------------------------------------------------------------------
 // Filter of a long run without global atomics.  The atomic build above is bound by the rate of read-modify-write
-// operations on scattered 8-byte words (two per key); this one moves the keys' 8-byte hashes instead:
-//   count     every workgroup counts, in LDS, how many hashes of its chunk fall into each bucket (a bucket is a range
-//             of kBucketBlocks consecutive filter blocks, 64 KiB) and adds its counts to the bucket totals
-//   offsets   exclusive prefix sum over the bucket totals
-//   scatter   every workgroup counts its chunk again, reserves its share of each bucket with one atomic per bucket, and
-//             copies each hash to its bucket's part of the workspace
-//   fill      one workgroup per bucket builds the bucket's 64 KiB of filter in LDS from the bucket's hashes and writes
-//             it out once
-// A hash's block grows with the hash's top half, so a bucket is a contiguous range of hash values.  The order of the
-// hashes inside a bucket does not matter: bits are only ever set.
+// operations on scattered 8-byte words (two per key); this one moves the keys' 8-byte hashes instead: they are sorted
+// by ranges of kBucketBlocks consecutive filter blocks ("buckets", 64 KiB; the passes of lsm_partition.h), then one
+// workgroup per bucket builds the bucket's 64 KiB of filter in LDS from the bucket's hashes and writes it out once.
+// The order of the hashes inside a bucket does not matter: bits are only ever set.
 // ---------------------------------------------------------------------------------------
-constexpr uint32_t kBucketBlocks = 4096;   // filter blocks per bucket (64 KiB of LDS)
-constexpr uint32_t kMaxBuckets = 8192;     // bucket counters of a workgroup (32 KiB of LDS)
-constexpr uint32_t kChunkHashes = 65536;   // hashes per workgroup of the count and scatter passes
-constexpr int kPartThreads = 1024;
+constexpr uint32_t kBucketBlocks = kRangeUnits;  // filter blocks per bucket (64 KiB of LDS)
 
 __global__ void hash_keys_kernel(const lsm_entry_t* entries, uint64_t n, uint64_t* hashes) {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) hashes[i] = bloom_key_hash(load_key(entries + i));
-}
-
-__global__ void bucket_clear_kernel(uint64_t* totals, uint32_t n_buckets) {
-    for (uint32_t b = blockIdx.x * blockDim.x + threadIdx.x; b < n_buckets; b += gridDim.x * blockDim.x) totals[b] = 0;
-}
-
-// kScatter = false: count.  kScatter = true: count, reserve, copy.
-template <bool kScatter>
-__global__ void __launch_bounds__(kPartThreads) bucket_pass_kernel(const uint64_t* hashes, uint64_t n, uint32_t n_blocks, uint32_t n_buckets,
-                                                                  unsigned long long* totals, unsigned long long* cursors, uint64_t* bucketed) {
-    __shared__ uint32_t count[kMaxBuckets];
-    const uint64_t first = (uint64_t)blockIdx.x * kChunkHashes;
-    const uint64_t last = first + kChunkHashes < n ? first + kChunkHashes : n;
-    for (uint32_t b = threadIdx.x; b < n_buckets; b += kPartThreads) count[b] = 0;
-    __syncthreads();
-    for (uint64_t i = first + threadIdx.x; i < last; i += kPartThreads) atomicAdd(&count[bloom_block(hashes[i], n_blocks) / kBucketBlocks], 1u);
-    __syncthreads();
-    if (!kScatter) {
-        for (uint32_t b = threadIdx.x; b < n_buckets; b += kPartThreads)
-            if (count[b]) atomicAdd(&totals[b], (unsigned long long)count[b]);
-        return;
-    }
-    // count[b] becomes where this workgroup's next hash of bucket b goes (the workspace holds fewer than 2^32 hashes)
-    for (uint32_t b = threadIdx.x; b < n_buckets; b += kPartThreads)
-        if (count[b]) count[b] = (uint32_t)atomicAdd(&cursors[b], (unsigned long long)count[b]);
-    __syncthreads();
-    for (uint64_t i = first + threadIdx.x; i < last; i += kPartThreads) {
-        const uint64_t h = hashes[i];
-        bucketed[atomicAdd(&count[bloom_block(h, n_blocks) / kBucketBlocks], 1u)] = h;
-    }
-}
-
-// cursors[b] = number of hashes in the buckets before b (one workgroup); totals[b] keeps the bucket's own count
-__global__ void __launch_bounds__(kPartThreads) bucket_offsets_kernel(const unsigned long long* totals, unsigned long long* cursors, uint32_t n_buckets) {
-    __shared__ unsigned long long wave_sum[kPartThreads / kWave];
-    constexpr uint32_t kPer = kMaxBuckets / kPartThreads;  // consecutive buckets per thread
-    unsigned long long v[kPer], mine = 0;
-    for (uint32_t i = 0; i < kPer; i++) {
-        const uint32_t b = threadIdx.x * kPer + i;
-        v[i] = b < n_buckets ? totals[b] : 0;
-        mine += v[i];
-    }
-    unsigned long long incl = mine;
-    const int lane = threadIdx.x & (kWave - 1);
-    for (int off = 1; off < kWave; off <<= 1) {
-        const unsigned long long o = __shfl_up(incl, off, kWave);
-        if (lane >= off) incl += o;
-    }
-    if (lane == kWave - 1) wave_sum[threadIdx.x / kWave] = incl;
-    __syncthreads();
-    unsigned long long before = incl - mine;
-    for (uint32_t w = 0; w < threadIdx.x / kWave; w++) before += wave_sum[w];
-    for (uint32_t i = 0; i < kPer; i++) {
-        const uint32_t b = threadIdx.x * kPer + i;
-        if (b < n_buckets) cursors[b] = before;
-        before += v[i];
-    }
 }
 
 // one workgroup per bucket; after the scatter pass cursors[b] is the END of bucket b's hashes, totals[b] their number
@@ -184,28 +119,11 @@ __global__ void __launch_bounds__(kPartThreads) bucket_fill_kernel(const uint64_
     for (uint32_t b = threadIdx.x; b < blocks; b += kPartThreads) filter[first_block + b] = src[b];
 }
 
-struct PartLayout {
-    uint32_t n_buckets;
-    size_t totals, cursors, bucketed, total;
-};
-static PartLayout part_layout(uint64_t n, uint64_t n_blocks) {
-    PartLayout l;
-    l.n_buckets = (uint32_t)((n_blocks + kBucketBlocks - 1) / kBucketBlocks);
-    l.totals = 0;
-    l.cursors = l.totals + (((size_t)l.n_buckets * 8 + 255) & ~size_t(255));
-    l.bucketed = l.cursors + (((size_t)l.n_buckets * 8 + 255) & ~size_t(255));
-    l.total = l.bucketed + (((size_t)n * 8 + 255) & ~size_t(255));
-    return l;
-}
-static bool part_applicable(uint64_t n, uint64_t n_blocks) {
-    return n_blocks > 0 && n < (1ull << 32) && (n_blocks + kBucketBlocks - 1) / kBucketBlocks <= kMaxBuckets;
-}
-
 }  // namespace lsm
 
 extern "C" size_t lsm_bloom_workspace_bytes(uint64_t n, uint64_t n_blocks) {
-    if (!lsm::part_applicable(n, n_blocks)) return 0;
-    return lsm::part_layout(n, n_blocks).total;
+    if (!lsm::range_partition_applies(n, n_blocks)) return 0;
+    return lsm::range_layout(n, n_blocks, false).total;
 }
 
 extern "C" int lsm_hash_keys(const lsm_run_t* run, uint64_t* hashes_out, void* stream_v) {
@@ -226,26 +144,16 @@ extern "C" int lsm_build_bloom_hashed(const uint64_t* hashes, uint64_t n, void* 
     if (filter_out == nullptr || (n > 0 && hashes == nullptr)) return LSM_ERR_NULL;
     if (n_blocks == 0 || n_blocks >= (1ull << 32)) return LSM_ERR_BAD_ARG;
     if ((reinterpret_cast<uintptr_t>(filter_out) & 15) != 0 || (reinterpret_cast<uintptr_t>(hashes) & 7) != 0) return LSM_ERR_BAD_ARG;
-    if (!part_applicable(n, n_blocks)) return LSM_ERR_BAD_ARG;
-    const PartLayout l = part_layout(n, n_blocks);
+    if (!range_partition_applies(n, n_blocks)) return LSM_ERR_BAD_ARG;
+    const RangeLayout l = range_layout(n, n_blocks, false);
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) & 255) != 0 || workspace_bytes < l.total) return LSM_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    launch_range_partition<false>(hashes, n, n_blocks, l, workspace, stream);
     char* base = static_cast<char*>(workspace);
-    unsigned long long* totals = reinterpret_cast<unsigned long long*>(base + l.totals);
-    unsigned long long* cursors = reinterpret_cast<unsigned long long*>(base + l.cursors);
-    uint64_t* bucketed = reinterpret_cast<uint64_t*>(base + l.bucketed);
-    const uint32_t chunks = (uint32_t)((n + kChunkHashes - 1) / kChunkHashes);
-    hipLaunchKernelGGL(bucket_clear_kernel, dim3((l.n_buckets + 255) / 256), dim3(256), 0, stream, reinterpret_cast<uint64_t*>(totals), l.n_buckets);
-    if (chunks > 0) {
-        hipLaunchKernelGGL(bucket_pass_kernel<false>, dim3(chunks), dim3(kPartThreads), 0, stream, hashes, n, (uint32_t)n_blocks, l.n_buckets, totals,
-                           cursors, bucketed);
-    }
-    hipLaunchKernelGGL(bucket_offsets_kernel, dim3(1), dim3(kPartThreads), 0, stream, totals, cursors, l.n_buckets);
-    if (chunks > 0) {
-        hipLaunchKernelGGL(bucket_pass_kernel<true>, dim3(chunks), dim3(kPartThreads), 0, stream, hashes, n, (uint32_t)n_blocks, l.n_buckets, totals,
-                           cursors, bucketed);
-    }
-    hipLaunchKernelGGL(bucket_fill_kernel, dim3(l.n_buckets), dim3(kPartThreads), 0, stream, bucketed, totals, cursors, (uint32_t)n_blocks,
+    const unsigned long long* totals = reinterpret_cast<const unsigned long long*>(base + l.totals);
+    const unsigned long long* cursors = reinterpret_cast<const unsigned long long*>(base + l.cursors);
+    const uint64_t* bucketed = reinterpret_cast<const uint64_t*>(base + l.ranged);
+    hipLaunchKernelGGL(bucket_fill_kernel, dim3(l.n_ranges), dim3(kPartThreads), 0, stream, bucketed, totals, cursors, (uint32_t)n_blocks,
                        static_cast<uint4*>(filter_out));
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

@@ -182,6 +182,14 @@ __device__ __forceinline__ bool bloom_excludes(const uint4 w, const uint4 mask) 
     return (((w.x & mask.x) ^ mask.x) | ((w.y & mask.y) ^ mask.y) | ((w.z & mask.z) ^ mask.z) | ((w.w & mask.w) ^ mask.w)) != 0;
 }
 
+// Hash index of a run: 64-byte buckets of kIndexSlots slots.  Bytes 0..15: the slots' 16-bit tag fields (low 15 bits
+// = tag; bit 15 of the first field = more keys fall into the bucket than it has slots); bytes 16..47: the slots' 32-bit
+// positions, all ones = empty slot; bytes 48..63: zero.
+constexpr uint32_t kIndexSlots = 8;
+constexpr uint32_t kIndexNoEntry = 0xFFFFFFFFu;
+constexpr uint32_t kIndexTagMask = 0x7FFFu;
+__host__ __device__ inline uint64_t index_buckets(uint64_t n) { return n ? (n + 3) / 4 : 1; }
+
 // Run descriptors passed to kernels by value.
 struct RunTable {
     const lsm_entry_t* ptr[LSM_MAX_RUNS];

@@ -18,13 +18,14 @@ namespace lsm {
 
 struct TreeRun {
     const lsm_entry_t* entries;
-    const uint8_t* fences;
+    const uint8_t* fences;  // ceil(n / stride) keys
     uint64_t n;
-    uint64_t n_fences;
+    const uint64_t* index;  // hash index of index_buckets(n) buckets, or null
     uint32_t stride;
     uint32_t bloom_blocks;  // 0 = no filter
     const uint4* bloom;
 };
+static_assert(sizeof(TreeRun) == 48, "64 of these travel as a kernel argument");
 
 struct TreeTable {
     TreeRun run[LSM_MAX_RUNS];
@@ -47,6 +48,7 @@ struct ProbeShared {
     uint64_t n[LSM_MAX_RUNS];
     uint64_t n_fences[LSM_MAX_RUNS];
     uint32_t stride[LSM_MAX_RUNS];
+    const uint64_t* index[LSM_MAX_RUNS];  // hash index of the run, or null
 };
 
 // -1 / 0 / +1 for q < / == / > the 32-byte key whose halves are (lo, hi); hi is only fetched on a tie
@@ -64,13 +66,17 @@ __device__ __forceinline__ int compare_key(const Key& q, uint4 lo, LoadHi load_h
     return 0;
 }
 
-// Copies the run descriptors and the top-level fence table into LDS (all threads of the workgroup call this).
+// Copies the run descriptors and, with kTop, the top-level fence table into LDS (all threads of the workgroup call this).
+// Without the table (every run has a hash index, so the fences are only searched for keys of crowded buckets) a fence
+// search starts from the whole fence array.
+template <bool kTop>
 __device__ __forceinline__ void probe_setup(ProbeShared& s, const TreeTable& tree, const int tid) {
     const uint32_t n_runs = tree.n_runs;
     // ---- top-level fence table: an equal share of the slots for every run
-    const uint32_t share = n_runs ? kTopSlots / n_runs : 0;
+    const uint32_t share = (kTop && n_runs) ? kTopSlots / n_runs : 0;
     if (tid < (int)n_runs) {
-        const uint64_t nf = tree.run[tid].n_fences;
+        const uint32_t stride = tree.run[tid].stride;  // >= 1 (checked by the host)
+        const uint64_t nf = (tree.run[tid].n + stride - 1) / stride;
         const uint32_t ts = share ? (uint32_t)((nf + share - 1) / share) : 1;
         s.first_slot[tid] = tid * share;
         s.top_stride[tid] = ts ? ts : 1;
@@ -79,44 +85,69 @@ __device__ __forceinline__ void probe_setup(ProbeShared& s, const TreeTable& tre
         s.entries[tid] = tree.run[tid].entries;
         s.n[tid] = tree.run[tid].n;
         s.n_fences[tid] = nf;
-        s.stride[tid] = tree.run[tid].stride;
+        s.stride[tid] = stride;
+        s.index[tid] = tree.run[tid].index;
     }
     __syncthreads();
-    for (uint32_t slot = tid; slot < share * n_runs; slot += kProbeThreads) {
-        const uint32_t r = slot / share, i = slot - r * share;
-        if (i < s.n_top[r]) {
-            const uint4* f = reinterpret_cast<const uint4*>(tree.run[r].fences + (uint64_t)i * s.top_stride[r] * LSM_KEY_BYTES);
-            s.top_lo[slot] = f[0];
-            s.top_hi[slot] = f[1];
+    if (kTop) {
+        for (uint32_t slot = tid; slot < share * n_runs; slot += kProbeThreads) {
+            const uint32_t r = slot / share, i = slot - r * share;
+            if (i < s.n_top[r]) {
+                const uint4* f = reinterpret_cast<const uint4*>(tree.run[r].fences + (uint64_t)i * s.top_stride[r] * LSM_KEY_BYTES);
+                s.top_lo[slot] = f[0];
+                s.top_hi[slot] = f[1];
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
+}
 
+// Whether a key with this tag can be in the bucket whose tag fields are w: some field carries the tag, or the bucket is crowded
+__device__ __forceinline__ bool index_admits(const uint4 w, const uint32_t tag) {
+    const uint32_t x[4] = {w.x, w.y, w.z, w.w};
+    bool any = (w.x & 0x8000u) != 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) any = any || (x[i] & kIndexTagMask) == tag || ((x[i] >> 16) & kIndexTagMask) == tag;
+    return any;
 }
 
 // Looks one block key per lane up in the tree (every lane of the wave calls this; lanes with mine == false idle).
 // Returns whether the key's newest version is a live PUT (true for idle lanes) and sets h to its hit record.
+template <bool kTop>
 __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTable& tree, const uint32_t n_runs,
-                                             const uint64_t run_mask, const bool any_bloom, const bool mine, const Key& q, uint4& h) {
+                                             const uint64_t run_mask, const bool any_filter, const bool mine, const Key& q, uint4& h) {
     bool live = !mine, found = !mine;
     // (0) Bloom filters of the runs that have one: one 16-byte read per run, all runs of a group of
     //     eight requested together, decides which runs this key is searched in
     uint64_t maybe = ~0ull;
-    if (mine && any_bloom) {
-        uint4 mask;
-        const uint64_t bh = bloom_hash(q, mask);
+    const uint64_t bh = mine ? bloom_key_hash(q) : 0;
+    const uint32_t tag = (uint32_t)bh & kIndexTagMask;
+    if (mine && any_filter) {
+        // one 16-byte read per run: the tags of the key's bucket in the run's hash index, else the key's filter block
+        const uint4 mask = bloom_mask(bh);
         for (uint32_t rb = 0; rb < n_runs; rb += 8) {
             uint4 w[8];
 #pragma unroll
             for (int g = 0; g < 8; g++) {
                 const uint32_t r = rb + g;
-                const uint32_t blocks = r < n_runs ? tree.run[r].bloom_blocks : 0;
                 w[g] = make_uint4(~0u, ~0u, ~0u, ~0u);
-                if (blocks) w[g] = tree.run[r].bloom[bloom_block(bh, blocks)];
+                if (r < n_runs) {
+                    // a run that has both is asked through its filter: an eighth of the index's size, so far more of it
+                    // stays in the caches
+                    if (tree.run[r].bloom_blocks != 0)
+                        w[g] = tree.run[r].bloom[bloom_block(bh, tree.run[r].bloom_blocks)];
+                    else if (tree.run[r].index != nullptr)
+                        w[g] = reinterpret_cast<const uint4*>(tree.run[r].index)[(uint64_t)bloom_block(bh, (uint32_t)index_buckets(tree.run[r].n)) * 4];
+                }
             }
 #pragma unroll
-            for (int g = 0; g < 8; g++)
-                if (bloom_excludes(w[g], mask)) maybe &= ~(1ull << (rb + g));
+            for (int g = 0; g < 8; g++) {
+                const uint32_t r = rb + g;
+                bool out;
+                if (r < n_runs && tree.run[r].bloom_blocks == 0 && tree.run[r].index != nullptr) out = !index_admits(w[g], tag);
+                else out = bloom_excludes(w[g], mask);
+                if (out) maybe &= ~(1ull << r);
+            }
         }
     }
     maybe &= run_mask;
@@ -126,8 +157,43 @@ __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTab
         const bool act = !found && maybe != 0;
         const uint32_t r = act ? (uint32_t)__builtin_ctzll(maybe) : 0;
         maybe &= maybe - 1;  // 0 stays 0
+        // (0b) a run with a hash index: the key's bucket holds its tag and position (the line was read in step 0, so
+        //      this read stays in the caches); only a key of a crowded bucket that is not among the bucket's eight goes
+        //      on to the fences
+        bool via_fences = act;
+        const uint64_t* index = act ? s.index[r] : nullptr;
+        if (index != nullptr) {
+            const uint64_t n = s.n[r];
+            const uint4* bucket = reinterpret_cast<const uint4*>(index) + (uint64_t)bloom_block(bh, (uint32_t)index_buckets(n)) * 4;
+            const uint4 t = bucket[0], p0 = bucket[1], p1 = bucket[2];
+            const uint32_t pos[kIndexSlots] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+            const uint32_t field[kIndexSlots] = {t.x & 0xFFFF, t.x >> 16, t.y & 0xFFFF, t.y >> 16, t.z & 0xFFFF, t.z >> 16, t.w & 0xFFFF, t.w >> 16};
+            via_fences = (t.x & 0x8000u) != 0;  // crowded
+            uint32_t same = 0;
+#pragma unroll
+            for (int k = 0; k < (int)kIndexSlots; k++) same |= (pos[k] != kIndexNoEntry && (field[k] & kIndexTagMask) == tag) ? 1u << k : 0u;
+            while (same != 0) {  // nearly always one candidate at most: another needs a second key with the same tag
+                const int k = __builtin_ctz(same);
+                same &= same - 1;
+                uint32_t at = pos[0];
+#pragma unroll
+                for (int j = 1; j < (int)kIndexSlots; j++) at = k == j ? pos[j] : at;
+                if (at >= n) continue;  // a table that does not belong to the run must not send a read outside it
+                const uint4* e = reinterpret_cast<const uint4*>(s.entries[r] + at);
+                const uint4 k0 = e[0], k1 = e[1], meta = e[2], val = e[3];
+                if (compare_key(q, k0, [&] { return k1; }) == 0) {
+                    found = true;
+                    via_fences = false;
+                    same = 0;
+                    if ((meta.z & 0xFF) == LSM_PUT) {
+                        live = true;
+                        h = make_uint4(val.x, val.y, val.z, r);
+                    }
+                }
+            }
+        }
         // (1) top-level fences in LDS: number of top keys <= q
-        uint32_t lo = 0, hi = act ? s.n_top[r] : 0;
+        uint32_t lo = 0, hi = (kTop && via_fences) ? s.n_top[r] : 0;
         const uint32_t first_slot = s.first_slot[r];
         while (__ballot(lo < hi) != 0) {
             if (lo < hi) {
@@ -139,7 +205,10 @@ __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTab
         }
         // (2) the fences between two top keys, in global memory: number of fences <= q
         const uint8_t* fences = s.fences[r];
-        if (lo > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the lane is idle)
+        if (!kTop) {  // no table: the whole fence array
+            lo = 0;
+            hi = via_fences ? (uint32_t)s.n_fences[r] : 0;
+        } else if (lo > 0) {  // lo = top keys <= q; 0 means q is below the run's first key (or the lane is idle)
             const uint32_t ts = s.top_stride[r];
             const uint64_t nf = s.n_fences[r], end = (uint64_t)lo * ts;
             hi = (uint32_t)(end < nf ? end : nf);
@@ -223,6 +292,7 @@ __device__ __forceinline__ bool probe_lookup(const ProbeShared& s, const TreeTab
     return live;
 }
 
+template <bool kTop>
 __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
                                                                uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len,
                                                                lsm_hit_t* hits) {
@@ -230,10 +300,10 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const uint32_t n_runs = tree.n_runs;
-    probe_setup(s, tree, tid);
+    probe_setup<kTop>(s, tree, tid);
     const uint64_t run_mask = n_runs >= 64 ? ~0ull : (1ull << n_runs) - 1;
-    bool any_bloom = false;
-    for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
+    bool any_filter = false;  // a Bloom filter or a hash index
+    for (uint32_t r = 0; r < n_runs; r++) any_filter = any_filter || tree.run[r].bloom_blocks != 0 || tree.run[r].index != nullptr;
     const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
     for (uint32_t req = blockIdx.x * (kProbeThreads / kWave) + tid / kWave; req < n_req; req += waves) {
         uint32_t nb = n_blocks[req];
@@ -249,7 +319,7 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
                 const bool mine = j < nb;  // lanes past the request's length do not end the prefix
                 Key q = {{0, 0, 0, 0}};
                 if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
-                const bool live = probe_lookup(s, tree, n_runs, run_mask, any_bloom, mine, q, h);
+                const bool live = probe_lookup<kTop>(s, tree, n_runs, run_mask, any_filter, mine, q, h);
                 const uint64_t dead = __ballot(!live);
                 if (dead) {
                     const uint32_t first = (uint32_t)__ffsll((unsigned long long)dead) - 1;
@@ -268,16 +338,17 @@ __global__ void __launch_bounds__(kProbeThreads) probe_kernel(TreeTable tree, co
 // lookup of every block key: valid when the tree is prefix-closed (block j of a request live => blocks 0..j-1
 // live).  One wave per request, two rounds: 64 evenly spaced blocks, then the blocks between the last live and the
 // first dead one of those.
+template <bool kTop>
 __global__ void __launch_bounds__(kProbeThreads) probe_length_kernel(TreeTable tree, const uint8_t* qkeys, const uint32_t* n_blocks,
                                                                       uint32_t n_req, uint32_t max_blocks, uint32_t* hit_len) {
     __shared__ ProbeShared s;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const uint32_t n_runs = tree.n_runs;
-    probe_setup(s, tree, tid);
+    probe_setup<kTop>(s, tree, tid);
     const uint64_t run_mask = n_runs >= 64 ? ~0ull : (1ull << n_runs) - 1;
-    bool any_bloom = false;
-    for (uint32_t r = 0; r < n_runs; r++) any_bloom = any_bloom || tree.run[r].bloom_blocks != 0;
+    bool any_filter = false;  // a Bloom filter or a hash index
+    for (uint32_t r = 0; r < n_runs; r++) any_filter = any_filter || tree.run[r].bloom_blocks != 0 || tree.run[r].index != nullptr;
     const uint32_t waves = gridDim.x * (kProbeThreads / kWave);
     for (uint32_t req = blockIdx.x * (kProbeThreads / kWave) + tid / kWave; req < n_req; req += waves) {
         uint32_t nb = n_blocks[req];
@@ -293,7 +364,7 @@ __global__ void __launch_bounds__(kProbeThreads) probe_length_kernel(TreeTable t
             Key q = {{0, 0, 0, 0}};
             if (mine) q = load_key(qrow + (uint64_t)j * LSM_KEY_BYTES);
             uint4 h;
-            const bool live = probe_lookup(s, tree, n_runs, run_mask, any_bloom, mine, q, h);
+            const bool live = probe_lookup<kTop>(s, tree, n_runs, run_mask, any_filter, mine, q, h);
             const uint64_t dead = __ballot(!live);
             if (dead == 0) {
                 lo = hi;  // block hi - 1 is live: so is everything below it
@@ -321,6 +392,17 @@ __global__ void range_bounds_kernel(TreeTable tree, Key lo_key, Key hi_key, uint
 }  // namespace lsm
 
 // Checks a tree descriptor and copies it into the by-value table the kernels take.
+// Whether the kernels can do without the top-level fence table: every run that holds entries has a hash index.
+static bool all_indexed(const lsm::TreeTable& tt) {
+    bool any = false;
+    for (uint32_t r = 0; r < tt.n_runs; r++) {
+        if (tt.run[r].n == 0) continue;
+        if (tt.run[r].index == nullptr) return false;
+        any = true;
+    }
+    return any;
+}
+
 static int make_tree_table(const lsm_tree_t* tree, lsm::TreeTable& tt) {
     using namespace lsm;
     if (tree->n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
@@ -332,8 +414,13 @@ static int make_tree_table(const lsm_tree_t* tree, lsm::TreeTable& tt) {
         d.entries = tr.run.entries;
         d.n = tr.run.n;
         d.fences = tr.fence.keys;
-        d.n_fences = tr.fence.n;
         d.stride = tr.fence.stride;
+        d.index = static_cast<const uint64_t*>(tr.index.buckets);
+        if (tr.index.buckets != nullptr) {
+            if ((reinterpret_cast<uintptr_t>(tr.index.buckets) & 63) != 0 || tr.index.n_buckets != index_buckets(tr.run.n) || tr.run.n >= 0xFFFFFFFFull)
+                return LSM_ERR_BAD_ARG;
+            if (tr.run.n == 0) d.index = nullptr;
+        }
         d.bloom = static_cast<const uint4*>(tr.bloom.blocks);
         d.bloom_blocks = tr.bloom.blocks ? (uint32_t)tr.bloom.n_blocks : 0;
         if (tr.bloom.blocks != nullptr &&
@@ -346,12 +433,11 @@ static int make_tree_table(const lsm_tree_t* tree, lsm::TreeTable& tt) {
             if ((reinterpret_cast<uintptr_t>(tr.run.entries) & 63) != 0 || (reinterpret_cast<uintptr_t>(tr.fence.keys) & 15) != 0)
                 return LSM_ERR_BAD_ARG;
         } else {
-            d.n_fences = 0;  // an empty run is never searched
-            d.stride = 1;
+            d.stride = 1;  // an empty run has no fences and is never searched
         }
     }
     tt.n_runs = tree->n_runs;
-    for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, 0, 1, 0, nullptr};
+    for (uint32_t r = tree->n_runs; r < LSM_MAX_RUNS; r++) tt.run[r] = TreeRun{nullptr, nullptr, 0, nullptr, 1, 0, nullptr};
     return LSM_OK;
 }
 
@@ -381,8 +467,12 @@ extern "C" int lsm_probe(const lsm_queries_t* queries, const lsm_tree_t* tree, c
     int rc = make_tree_table(tree, tt);
     if (rc == LSM_OK) rc = probe_grid(queries->n_req, blocks);
     if (rc != LSM_OK) return rc;
-    hipLaunchKernelGGL(probe_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
-                       queries->n_blocks, queries->n_req, queries->max_blocks, out_hits->hit_len, out_hits->hits);
+    if (all_indexed(tt))
+        hipLaunchKernelGGL(probe_kernel<false>, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
+                           queries->n_blocks, queries->n_req, queries->max_blocks, out_hits->hit_len, out_hits->hits);
+    else
+        hipLaunchKernelGGL(probe_kernel<true>, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
+                           queries->n_blocks, queries->n_req, queries->max_blocks, out_hits->hit_len, out_hits->hits);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }
 
@@ -398,8 +488,12 @@ extern "C" int lsm_probe_length(const lsm_queries_t* queries, const lsm_tree_t* 
     int rc = make_tree_table(tree, tt);
     if (rc == LSM_OK) rc = probe_grid(queries->n_req, blocks);
     if (rc != LSM_OK) return rc;
-    hipLaunchKernelGGL(probe_length_kernel, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
-                       queries->n_blocks, queries->n_req, queries->max_blocks, hit_len);
+    if (all_indexed(tt))
+        hipLaunchKernelGGL(probe_length_kernel<false>, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
+                           queries->n_blocks, queries->n_req, queries->max_blocks, hit_len);
+    else
+        hipLaunchKernelGGL(probe_length_kernel<true>, dim3(blocks), dim3(kProbeThreads), 0, static_cast<hipStream_t>(stream), tt, queries->keys,
+                           queries->n_blocks, queries->n_req, queries->max_blocks, hit_len);
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }
 

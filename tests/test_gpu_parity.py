@@ -319,6 +319,71 @@ def test_probe_with_bloom_filters_gives_the_same_answers(g, oracle, cfg1):
         assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)
 
 
+# ------------------------------------------------------------------ hash index (section 2.2: in-memory indices of a run)
+@pytest.mark.parametrize("n", [0, 1, 3, 9, 4096, 16384, 300_000, 65_536 * 5 + 123])
+def test_hash_index_is_a_valid_index_of_the_run(g, oracle, n):
+    """lsm_build_hash_index: the table passes the checker's validity check (every key in its bucket with its tag and
+    position, or its bucket marked crowded and holding seven; nothing else in the table), whatever the buffers held
+    before; the key hashes equal the checker's.  The table itself is not unique, so its bytes are not compared."""
+    from workloads import lsm
+    print("hash index", n, flush=True)
+    w = lsm.config3(device=dev(), scale=64)      # 16 runs x 65,536 entries
+    run = w.runs[0][:n].contiguous() if n <= 65_536 else torch.cat(list(w.runs))[:n].contiguous()
+    if n > 65_536:   # several runs put together are not sorted and hold a key more than once: one sorted run
+        cpu = oracle.compact([r.cpu() for r in w.runs], 0)[:n]
+        run = torch.from_numpy(cpu.view(np.int64).reshape(-1, 8).copy()).to(dev())
+    n = int(run.shape[0])
+    hashes = g.lsm_hash_keys(run)
+    torch.cuda.synchronize()
+    assert np.array_equal(hashes.cpu().numpy().view(np.uint64), oracle.key_hashes(run.cpu()))
+    n_buckets = g.lsm_hash_index_buckets(n)
+    assert n_buckets == oracle.hash_index_buckets(n)
+    table = g.lsm_build_hash_index(hashes, out=torch.full((n_buckets, 8), 0x5A5A5A5A, dtype=torch.int64, device=dev()))
+    torch.cuda.synchronize()
+    assert oracle.hash_index_check(run.cpu(), table.cpu().numpy()) == 0
+    if n >= 4096:
+        marks = int(((table[:, 0] >> 15) & 1).sum().item())   # bit 15 of the first tag field
+        assert 0 < marks < n_buckets // 10          # some buckets are crowded, most are not
+
+
+def test_probe_with_hash_indices_gives_the_same_answers(g, oracle, cfg1):
+    """A hash index only tells the probe where to look: results equal the checker's (which has none) with an index on
+    every run (no fence table in the kernel) or on some, with and without filters, and for the search over the prefix
+    length.  Requests made of a run's own keys reach every key of every crowded bucket (the fence path behind the
+    mark)."""
+    from workloads import lsm
+    print("probe with hash indices", flush=True)
+    q, nb = lsm.queries_config1(cfg1, 2048)
+    runs_cpu = [r.cpu() for r in cfg1.runs]
+    want = oracle.probe(q, nb, runs_cpu)
+    plain = build_tree(g, cfg1.runs)
+    indices = [g.lsm_build_hash_index(g.lsm_hash_keys(t.run)) for t in plain]
+    for choice in ("all", "some", "all+filters", "some+filters"):
+        tree = []
+        for i, t in enumerate(plain):
+            index = indices[i] if (not choice.startswith("some") or i % 2 == 0) else None
+            bloom = g.lsm_build_bloom(t.run, 16) if choice.endswith("filters") else None
+            tree.append(g.TreeRun(t.run, t.fences, t.stride, t.level, bloom, index))
+        assert_probe_equal(oracle, probe_gpu(g, q, nb, tree), want)
+        got_len = g.lsm_probe_length(q, nb, tree)
+        torch.cuda.synchronize()
+        assert np.array_equal(got_len.cpu().numpy().astype(np.uint32), want[0])
+    # every key of the oldest run as a request of its own row of keys
+    run = cfg1.runs[-1]
+    n = int(run.shape[0]) // 256 * 256
+    own_q = run[:n, :4].reshape(-1, 256, 4).contiguous()
+    own_nb = torch.full((own_q.shape[0],), 256, dtype=torch.int32, device=dev())
+    want_own = oracle.probe(own_q, own_nb, runs_cpu)
+    for tree in ([g.TreeRun(t.run, t.fences, t.stride, t.level, None, ix) for t, ix in zip(plain, indices)],
+                 [g.TreeRun(t.run, t.fences, t.stride, t.level, None, ix if i != 1 else None) for i, (t, ix) in enumerate(zip(plain, indices))]):
+        assert_probe_equal(oracle, probe_gpu(g, own_q, own_nb, tree), want_own)
+    # a table that does not belong to the run (positions far beyond it) must not send a read outside the run
+    wrong = torch.full_like(indices[0], (2_000_000_000 << 32) | 2_000_000_000)   # every tag field set, positions beyond the run
+    tree = [g.TreeRun(t.run, t.fences, t.stride, t.level, None, wrong if t.run.shape[0] == plain[0].run.shape[0] else None) for t in plain]
+    hl, _ = probe_gpu(g, q, nb, tree)
+    assert hl.shape == want[0].shape   # the answers are meaningless, the call must simply stay inside the runs
+
+
 # ------------------------------------------------------------------ pointer rewrite during compaction (section 3.4)
 def test_compaction_with_pointer_rewrite(g, oracle, cfg1):
     """lsm_compact_remap = compaction followed by the checker's pointer rewrite: several tensor files folded into

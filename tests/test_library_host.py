@@ -37,7 +37,7 @@ def test_every_declared_entry_point_is_exported(lib):
 def test_struct_sizes_match_the_header():
     import paper_2511_16138_amd.binding as B
     assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 48 and C.sizeof(B._Fence) == 24
-    assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 64 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
+    assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 80 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
     assert C.sizeof(B._PolicyInput) == 72
 
 
@@ -79,6 +79,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert lib.lsm_build_bloom_hashed(8 * 3, 5, 16 * 9, 4, 256 * 3 + 8, 1 << 20, None) == -4       # workspace misaligned
     assert lib.lsm_hash_keys(C.byref(fake), None, None) == -1
     assert lib.lsm_hash_keys(C.byref(fake), 8 * 5 + 1, None) == -2
+    assert [lib.lsm_hash_index_buckets(n) for n in (0, 1, 4, 5, 1 << 20)] == [1, 1, 1, 2, 1 << 18]
+    assert lib.lsm_hash_index_workspace_bytes((1 << 27) + 1) == 0 and lib.lsm_hash_index_workspace_bytes(0) > 0
+    assert 12 * 1_000_000 <= lib.lsm_hash_index_workspace_bytes(1_000_000) < 12 * 1_000_000 + 8192
+    assert lib.lsm_build_hash_index(None, 5, 64 * 9, 256 * 3, 1 << 20, None) == -1                 # no hashes
+    assert lib.lsm_build_hash_index(8 * 3, 5, 64 * 9 + 8, 256 * 3, 1 << 20, None) == -2            # table misaligned
+    assert lib.lsm_build_hash_index(8 * 3, (1 << 27) + 1, 64 * 9, 256 * 3, 1 << 40, None) == -2    # run too long
+    assert lib.lsm_build_hash_index(8 * 3, 5, 64 * 9, 256 * 3, 16, None) == -4                     # workspace too small
     table = B._Remap(None, 3)
     assert lib.lsm_compact_remap(C.byref(fake), 1, 0, C.byref(big), 256 * 7, 1 << 20, None, C.byref(table), None) == -1
     assert lib.lsm_flush_workspace_bytes(3600) == 14400 and lib.lsm_flush_workspace_bytes(1 << 20) == 0
