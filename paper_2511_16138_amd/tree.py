@@ -33,6 +33,7 @@ class LevelRun:
     run: Any      # backend handle of the entries (has .shape[0] = number of entries)
     fences: Any   # backend handle of its fence index
     bloom: Any = None  # backend handle of its Bloom filter, if the backend builds them
+    index: Any = None  # backend handle of its hash index, if the backend builds them
 
     @property
     def n(self) -> int:
@@ -42,11 +43,12 @@ class LevelRun:
 class GpuBackend:
     """The library calls the driver needs, on torch CUDA tensors."""
 
-    def __init__(self, fence_stride: int = 64, bloom_bits: int = 0):
+    def __init__(self, fence_stride: int = 64, bloom_bits: int = 0, hash_index_from: int = 0):
         from . import binding
         self._b = binding
         self.fence_stride = fence_stride
         self.bloom_bits = bloom_bits  # bits per key of the per-run Bloom filters; 0 = none
+        self.hash_index_from = hash_index_from  # runs of at least this many entries get a hash index; 0 = none
 
     def compact(self, runs: Sequence[Any], flags: int) -> Any:
         import torch
@@ -93,19 +95,26 @@ class GpuBackend:
         out, n_out = self._b.lsm_flush_buffer(buffer.contiguous())
         return out[: int(n_out.item())]
 
-    def build_bloom(self, run: Any) -> Any:
+    def build_bloom(self, run: Any, hashes: Any = None) -> Any:
         if not self.bloom_bits:
             return None
         run = run.contiguous()
         n = int(run.shape[0])
         n_blocks = self._b.lsm_bloom_blocks(n, self.bloom_bits)
         # a long run: the filter is built from the keys' hashes, sorted by block range (no atomic traffic on the filter)
-        if n >= (1 << 20) and self._b.lsm_bloom_workspace_bytes(n, n_blocks):
-            return self._b.lsm_build_bloom_hashed(self._b.lsm_hash_keys(run), n_blocks)
+        if (hashes is not None or n >= (1 << 20)) and self._b.lsm_bloom_workspace_bytes(n, n_blocks):
+            return self._b.lsm_build_bloom_hashed(hashes if hashes is not None else self._b.lsm_hash_keys(run), n_blocks)
         return self._b.lsm_build_bloom(run, self.bloom_bits)
 
+    def build_lookup(self, run: Any) -> Tuple[Any, Any]:
+        """Filter and hash index of a run that has come to rest (either may be None); the keys are hashed once for both."""
+        n = int(run.shape[0])
+        indexed = self.hash_index_from and n >= self.hash_index_from and n <= (1 << 27)
+        hashes = self._b.lsm_hash_keys(run.contiguous()) if indexed else None
+        return self.build_bloom(run, hashes), (self._b.lsm_build_hash_index(hashes) if indexed else None)
+
     def probe(self, qkeys: Any, n_blocks: Any, tree: Sequence[LevelRun]) -> Tuple[Any, Any]:
-        tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i, t.bloom) for i, t in enumerate(tree)]
+        tr = [self._b.TreeRun(t.run, t.fences, self.fence_stride, i, t.bloom, t.index) for i, t in enumerate(tree)]
         return self._b.lsm_probe(qkeys, n_blocks, tr)
 
     def hit_len_to_host(self, hit_len: Any) -> List[int]:
@@ -154,9 +163,8 @@ class AdaptiveLsmTree:
         self.levels[level] = [self._index(r) for r in runs_newest_first]
 
     def _index(self, run: Any) -> LevelRun:
-        """A run with the lookup structures the backend builds for it (fence index, optional Bloom filter)."""
-        build_bloom = getattr(self.backend, "build_bloom", None)
-        return LevelRun(run, self.backend.build_fences(run), build_bloom(run) if build_bloom else None)
+        """A run with the lookup structures the backend builds for it (fence index, optional Bloom filter and hash index)."""
+        return self._settle(LevelRun(run, None if int(run.shape[0]) else self.backend.build_fences(run)))
 
     def capacity(self, level: int) -> int:
         return self.buffer_entries * self.level_t[level] ** (level + 1)
@@ -174,9 +182,11 @@ class AdaptiveLsmTree:
             return lr
         if lr.fences is None:
             lr.fences = self.backend.build_fences(lr.run)
-        build_bloom = getattr(self.backend, "build_bloom", None)
-        if lr.bloom is None and build_bloom:
-            lr.bloom = build_bloom(lr.run)
+        build_lookup = getattr(self.backend, "build_lookup", None)
+        if lr.bloom is None and lr.index is None and build_lookup:
+            lr.bloom, lr.index = build_lookup(lr.run)
+        elif lr.index is None and build_lookup and getattr(self.backend, "hash_index_from", 0):
+            lr.index = build_lookup(lr.run)[1]   # a run of a batch already has its filter
         return lr
 
     def flush(self, run: Any) -> None:

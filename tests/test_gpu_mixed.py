@@ -11,7 +11,7 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, progress=None):
+def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, progress=None, hash_index_from=0):
     """Run the trace through both drivers in step: every compaction output and every probe batch is compared as it is
     produced (so that no more than one of each is alive at a time), the logs after every event."""
     from gpu_util import oracle_probe_threads
@@ -26,7 +26,7 @@ def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, pr
             gpu_out.append(merged)
             return merged
 
-    gpu = AdaptiveLsmTree(Recording(bloom_bits=bloom_bits), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window,
+    gpu = AdaptiveLsmTree(Recording(bloom_bits=bloom_bits, hash_index_from=hash_index_from), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window,
                           t_grid=t_grid)
     cpu = drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=t_grid,
                            page_entries=64.0, fpr=drv.bloom_fpr(bloom_bits), on_compact=cpu_out.append,
@@ -69,23 +69,28 @@ def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, pr
             assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
             if bloom_bits:
                 assert np.array_equal(gr.bloom.cpu().numpy().view(np.uint8).reshape(-1, 16), oracle.build_bloom(cr, int(gr.bloom.shape[0])))
+            if hash_index_from and cr.shape[0] >= hash_index_from:
+                assert oracle.hash_index_check(cr, gr.index.cpu().numpy()) == 0
+            else:
+                assert gr.index is None
     assert [(t, k) for t, k in zip(gpu.level_t, gpu.level_k)] == [(lv.T, lv.K) for lv in cpu.levels]
     return gpu, n_probe
 
 
-@pytest.mark.parametrize("tree_total,buffer_entries,ops,bloom_bits,t_grid,shuffled", [
-    (400_000, 360, 4096, 16, (2, 16), False),    # filters on: p = 0.0022, the full (T, K) grid
-    (2_000_000, 900, 8192, 16, (10, 10), False),  # T fixed at 10: only K moves
-    (400_000, 360, 4096, 0, (2, 16), False),     # no filters: p = 1
-    (400_000, 360, 4096, 16, (2, 16), True),     # write buffers handed over unsorted (lsm_flush_buffer)
+@pytest.mark.parametrize("tree_total,buffer_entries,ops,bloom_bits,t_grid,shuffled,hash_index_from", [
+    (400_000, 360, 4096, 16, (2, 16), False, 0),    # filters on: p = 0.0022, the full (T, K) grid
+    (2_000_000, 900, 8192, 16, (10, 10), False, 0),  # T fixed at 10: only K moves
+    (400_000, 360, 4096, 0, (2, 16), False, 0),     # no filters: p = 1
+    (400_000, 360, 4096, 16, (2, 16), True, 0),     # write buffers handed over unsorted (lsm_flush_buffer)
+    (400_000, 360, 4096, 16, (2, 16), False, 2000),  # runs of 2,000 entries and more also get a hash index
 ])
-def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled):
+def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, hash_index_from):
     from workloads import lsm
-    print("mixed trace", tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, flush=True)
+    print("mixed trace", tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, hash_index_from, flush=True)
     tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=128)
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
     shuffle = (lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())) if shuffled else None
-    gpu, n_probe = replay_both(oracle, tr, bloom_bits, t_grid, 16, shuffle)
+    gpu, n_probe = replay_both(oracle, tr, bloom_bits, t_grid, 16, shuffle, hash_index_from=hash_index_from)
     kinds = {e[0] for e in gpu.trace}
     assert {"compact", "probe", "policy", "move"} <= kinds and n_probe >= 6
     pol = [(e[1], e[2]) for e in gpu.trace if e[0] == "policy"]
