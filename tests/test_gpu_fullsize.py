@@ -74,6 +74,15 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
         assert np.array_equal(as_bytes(t.bloom).reshape(-1, 16), oracle.build_bloom(r, int(t.bloom.shape[0])))
         # the build from the keys' hashes (thousands of block ranges on the 90M-entry level) gives the same bytes
         assert torch.equal(g.lsm_build_bloom_hashed(g.lsm_hash_keys(t.run), int(t.bloom.shape[0])), t.bloom)
+    # hash indices of every level: valid tables (the 90M-entry level: 22.5M buckets, thousands of bucket ranges)
+    indexed, both = [], []
+    for t, f, r in zip(tree, filtered, runs_cpu):
+        index = g.lsm_build_hash_index(g.lsm_hash_keys(t.run))
+        torch.cuda.synchronize()
+        assert oracle.hash_index_check(r, index.cpu().numpy()) == 0
+        indexed.append(g.TreeRun(t.run, t.fences, t.stride, t.level, None, index))
+        both.append(g.TreeRun(t.run, t.fences, t.stride, t.level, f.bloom, index))
+    print("  filters and hash indices ok", flush=True)
     t0, misses, requests = time.time(), 0, 0
     for stream in range(256):
         q, nb = lsm.queries_config4(w, 4096, stream=stream)
@@ -85,7 +94,9 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
         if stream % 16 == 0:
             print(f"  batch {stream} ok ({time.time() - t0:.0f} s)", flush=True)
             assert_probe_equal(oracle, probe_gpu(g, q, nb, filtered), want)
-            for t in (tree, filtered):  # the generator's data is prefix-closed: the search over the length agrees
+            assert_probe_equal(oracle, probe_gpu(g, q, nb, indexed), want)
+            assert_probe_equal(oracle, probe_gpu(g, q, nb, both), want)
+            for t in (tree, filtered, both):  # the generator's data is prefix-closed: the search over the length agrees
                 assert np.array_equal(g.lsm_probe_length(q, nb, t).cpu().numpy().astype(np.uint32), want[0])
             assert want[0].max() >= 32
     assert requests == 1 << 20 and 0.25 < misses / requests < 0.45
