@@ -331,7 +331,7 @@ int lsm_build_bloom_hashed(const uint64_t* hashes, uint64_t n, void* filter_out,
  * run order (hashes[i] belongs to entry i: from lsm_hash_keys, or from lsm_compact's key_hashes).  buckets_out:
  * DEVICE, 64-byte aligned, lsm_hash_index_buckets(n) x 64 bytes, every byte written.  The hashes are sorted by
  * ranges of 4,096 buckets inside the workspace and every range is filled by one workgroup (no atomic traffic
- * on the table).  lsm_hash_index_workspace_bytes(n): DEVICE, 256-byte aligned, about 12 n bytes; 0 when the
+ * on the table).  lsm_hash_index_workspace_bytes(n): DEVICE, 256-byte aligned, about 16 n bytes; 0 when the
  * build does not apply (n > 2^27).
  * Errors: LSM_ERR_NULL, LSM_ERR_BAD_ARG (misaligned pointers, n too large), LSM_ERR_WORKSPACE, LSM_ERR_HIP.
  */

@@ -11,7 +11,8 @@
 // first tag field set, which sends a lookup that finds nothing among the eight to the fence index.
 //
 // Build: the hashes and their positions are sorted by ranges of 4,096 buckets (lsm_partition.h); one workgroup per
-// range hands out the slots of its buckets with counters in LDS and writes every byte of its range exactly once.
+// range hands out the slots of its buckets with counters in LDS, assembles the buckets there, and writes every byte of
+// its range exactly once.
 // Which keys of a crowded bucket are kept, and the order of the slots in a bucket, depend on the order the
 // workgroup happens to see the hashes in: lookups give the same answers for every such table.
 #include <hip/hip_runtime.h>
@@ -21,37 +22,44 @@
 
 namespace lsm {
 
-// one workgroup per range of kRangeUnits buckets
-__global__ void __launch_bounds__(kPartThreads) index_fill_kernel(const uint64_t* ranged, const uint32_t* ranged_pos, const unsigned long long* totals,
-                                                                 const unsigned long long* cursors, uint32_t n_buckets, uint8_t* table) {
-    __shared__ uint32_t count[kRangeUnits];
-    __shared__ uint16_t first_tag[kRangeUnits];  // the first slot's tag waits here: its field also carries the crowded bit
-    const uint32_t first_bucket = blockIdx.x * kRangeUnits;
-    const uint32_t buckets = n_buckets - first_bucket < kRangeUnits ? n_buckets - first_bucket : kRangeUnits;
-    for (uint32_t b = threadIdx.x; b < buckets; b += kPartThreads) count[b] = 0;
-    __syncthreads();
+// One workgroup per range of kRangeUnits buckets.  The range is built a quarter at a time in LDS (1,024 buckets = 64 KiB)
+// and each quarter leaves with contiguous 16-byte stores: scattered 2- and 4-byte stores straight into the table cost
+// 4.6 bytes of HBM writes per byte of table.  Every pass reads the range's hashes again (they stay in the caches).
+constexpr uint32_t kFillBuckets = 1024;
+__global__ void __launch_bounds__(kPartThreads) index_fill_kernel(const uint4* ranged, const unsigned long long* totals,
+                                                                 const unsigned long long* cursors, uint32_t n_buckets, uint4* table) {
+    __shared__ uint4 part[kFillBuckets * 4];  // the buckets of this pass
+    __shared__ uint32_t count[kFillBuckets];
+    const uint32_t range_first = blockIdx.x * kRangeUnits;
     const uint64_t end = cursors[blockIdx.x], begin = end - totals[blockIdx.x];
-    for (uint64_t i = begin + threadIdx.x; i < end; i += kPartThreads) {
-        const uint64_t h = ranged[i];
-        const uint32_t b = bloom_block(h, n_buckets) - first_bucket;  // inside this range by construction
-        const uint32_t k = atomicAdd(&count[b], 1u);
-        if (k >= kIndexSlots) continue;  // a crowded bucket keeps the first eight keys that arrive
-        uint8_t* bucket = table + (uint64_t)(first_bucket + b) * 64;
-        const uint16_t tag = (uint16_t)(h & kIndexTagMask);
-        if (k == 0) first_tag[b] = tag;
-        else reinterpret_cast<uint16_t*>(bucket)[k] = tag;
-        reinterpret_cast<uint32_t*>(bucket + 16)[k] = ranged_pos[i];
-    }
-    __syncthreads();
-    for (uint32_t b = threadIdx.x; b < buckets; b += kPartThreads) {
-        const uint32_t c = count[b];
-        uint8_t* bucket = table + (uint64_t)(first_bucket + b) * 64;
-        uint16_t* tags = reinterpret_cast<uint16_t*>(bucket);
-        uint32_t* pos = reinterpret_cast<uint32_t*>(bucket + 16);
-        tags[0] = (uint16_t)((c > 0 ? first_tag[b] : 0) | (c > kIndexSlots ? 0x8000u : 0u));
-        for (uint32_t k = c > 0 ? c : 1; k < kIndexSlots; k++) tags[k] = 0;
-        for (uint32_t k = c; k < kIndexSlots; k++) pos[k] = kIndexNoEntry;
-        reinterpret_cast<uint4*>(bucket)[3] = make_uint4(0, 0, 0, 0);
+    for (uint32_t first_bucket = range_first; first_bucket < range_first + kRangeUnits && first_bucket < n_buckets; first_bucket += kFillBuckets) {
+        const uint32_t buckets = n_buckets - first_bucket < kFillBuckets ? n_buckets - first_bucket : kFillBuckets;
+        // every bucket starts empty: tag fields 0, positions all ones, the rest 0
+        for (uint32_t i = threadIdx.x; i < buckets * 4; i += kPartThreads) {
+            const uint32_t fill = ((i & 3) == 1 || (i & 3) == 2) ? kIndexNoEntry : 0u;
+            part[i] = make_uint4(fill, fill, fill, fill);
+        }
+        for (uint32_t b = threadIdx.x; b < buckets; b += kPartThreads) count[b] = 0;
+        __syncthreads();
+        uint16_t* tags = reinterpret_cast<uint16_t*>(part);
+        uint32_t* words = reinterpret_cast<uint32_t*>(part);
+        for (uint64_t i = begin + threadIdx.x; i < end; i += kPartThreads) {
+            const uint4 rec = ranged[i];  // {h, position, 0}
+            const uint64_t h = ((uint64_t)rec.y << 32) | rec.x;
+            const uint32_t b = bloom_block(h, n_buckets) - first_bucket;  // wraps for the buckets before this pass
+            if (b >= buckets) continue;
+            const uint32_t k = atomicAdd(&count[b], 1u);
+            if (k >= kIndexSlots) continue;  // a crowded bucket keeps the first eight keys that arrive
+            tags[b * 32 + k] = (uint16_t)(h & kIndexTagMask);
+            words[b * 16 + 4 + k] = rec.z;
+        }
+        __syncthreads();
+        for (uint32_t b = threadIdx.x; b < buckets; b += kPartThreads)
+            if (count[b] > kIndexSlots) tags[b * 32] |= 0x8000u;  // crowded
+        __syncthreads();
+        uint4* dst = table + (uint64_t)first_bucket * 4;
+        for (uint32_t i = threadIdx.x; i < buckets * 4; i += kPartThreads) dst[i] = part[i];
+        __syncthreads();  // the LDS arrays are reused by the next pass
     }
 }
 
@@ -76,8 +84,8 @@ extern "C" int lsm_build_hash_index(const uint64_t* hashes, uint64_t n, void* ta
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     launch_range_partition<true>(hashes, n, n_buckets, l, workspace, stream);
     char* base = static_cast<char*>(workspace);
-    hipLaunchKernelGGL(index_fill_kernel, dim3(l.n_ranges), dim3(kPartThreads), 0, stream, reinterpret_cast<const uint64_t*>(base + l.ranged),
-                       reinterpret_cast<const uint32_t*>(base + l.ranged_pos), reinterpret_cast<const unsigned long long*>(base + l.totals),
-                       reinterpret_cast<const unsigned long long*>(base + l.cursors), (uint32_t)n_buckets, static_cast<uint8_t*>(table_out));
+    hipLaunchKernelGGL(index_fill_kernel, dim3(l.n_ranges), dim3(kPartThreads), 0, stream, reinterpret_cast<const uint4*>(base + l.ranged),
+                       reinterpret_cast<const unsigned long long*>(base + l.totals),
+                       reinterpret_cast<const unsigned long long*>(base + l.cursors), (uint32_t)n_buckets, static_cast<uint4*>(table_out));
     return hipGetLastError() == hipSuccess ? LSM_OK : LSM_ERR_HIP;
 }

@@ -6,7 +6,7 @@
 //             the range totals (one global atomic per range and workgroup)
 //   offsets   exclusive prefix sum over the range totals (one workgroup)
 //   scatter   every workgroup counts its chunk again, reserves its share of each range with one returning atomic per
-//             range, and copies each hash (and, if asked, its position in the input) to its range's part of the
+//             range, and copies each hash (with its position in the input, if asked) to its range's part of the
 //             workspace; afterwards cursors[r] is the END of range r's hashes and totals[r] their number
 // The order of the hashes inside a range is not defined.
 #ifndef LSM_PARTITION_H
@@ -27,11 +27,11 @@ static __global__ void range_clear_kernel(uint64_t* totals, uint32_t n_ranges) {
     for (uint32_t b = blockIdx.x * blockDim.x + threadIdx.x; b < n_ranges; b += gridDim.x * blockDim.x) totals[b] = 0;
 }
 
-// kScatter = false: count.  kScatter = true: count, reserve, copy.  kWithPos: the copy of hash i is followed by i.
+// kScatter = false: count.  kScatter = true: count, reserve, copy.  kWithPos: the copy of hash i is a 16-byte record
+// {h, i, 0}: one store per hash (an 8-byte and a 4-byte store into two arrays took a fifth longer).
 template <bool kScatter, bool kWithPos>
 __global__ void __launch_bounds__(kPartThreads) range_pass_kernel(const uint64_t* hashes, uint64_t n, uint32_t n_units, uint32_t n_ranges,
-                                                                 unsigned long long* totals, unsigned long long* cursors, uint64_t* ranged,
-                                                                 uint32_t* ranged_pos) {
+                                                                 unsigned long long* totals, unsigned long long* cursors, uint64_t* ranged) {
     __shared__ uint32_t count[kMaxRanges];
     const uint64_t first = (uint64_t)blockIdx.x * kChunkHashes;
     const uint64_t last = first + kChunkHashes < n ? first + kChunkHashes : n;
@@ -51,8 +51,8 @@ __global__ void __launch_bounds__(kPartThreads) range_pass_kernel(const uint64_t
     for (uint64_t i = first + threadIdx.x; i < last; i += kPartThreads) {
         const uint64_t h = hashes[i];
         const uint32_t at = atomicAdd(&count[bloom_block(h, n_units) / kRangeUnits], 1u);
-        ranged[at] = h;
-        if (kWithPos) ranged_pos[at] = (uint32_t)i;
+        if (kWithPos) reinterpret_cast<uint4*>(ranged)[at] = make_uint4((uint32_t)h, (uint32_t)(h >> 32), (uint32_t)i, 0);  // one 16-byte record
+        else ranged[at] = h;
     }
 }
 
@@ -84,10 +84,10 @@ static __global__ void __launch_bounds__(kPartThreads) range_offsets_kernel(cons
     }
 }
 
-// Workspace of a partition of n hashes into n_ranges ranges: totals, cursors, the hashes by range, optionally positions.
+// Workspace of a partition of n hashes into n_ranges ranges: totals, cursors, the hashes (or records) by range.
 struct RangeLayout {
     uint32_t n_ranges;
-    size_t totals, cursors, ranged, ranged_pos, total;
+    size_t totals, cursors, ranged, total;
 };
 inline RangeLayout range_layout(uint64_t n, uint64_t n_units, bool with_pos) {
     auto up = [](size_t x) { return (x + 255) & ~size_t(255); };
@@ -96,8 +96,7 @@ inline RangeLayout range_layout(uint64_t n, uint64_t n_units, bool with_pos) {
     l.totals = 0;
     l.cursors = l.totals + up((size_t)l.n_ranges * 8);
     l.ranged = l.cursors + up((size_t)l.n_ranges * 8);
-    l.ranged_pos = l.ranged + up((size_t)n * 8);
-    l.total = l.ranged_pos + (with_pos ? up((size_t)n * 4) : 0);
+    l.total = l.ranged + up((size_t)n * (with_pos ? 16 : 8));
     return l;
 }
 inline bool range_partition_applies(uint64_t n, uint64_t n_units) {
@@ -111,16 +110,15 @@ inline void launch_range_partition(const uint64_t* hashes, uint64_t n, uint64_t 
     unsigned long long* totals = reinterpret_cast<unsigned long long*>(base + l.totals);
     unsigned long long* cursors = reinterpret_cast<unsigned long long*>(base + l.cursors);
     uint64_t* ranged = reinterpret_cast<uint64_t*>(base + l.ranged);
-    uint32_t* ranged_pos = reinterpret_cast<uint32_t*>(base + l.ranged_pos);
     const uint32_t chunks = (uint32_t)((n + kChunkHashes - 1) / kChunkHashes);
     hipLaunchKernelGGL(range_clear_kernel, dim3((l.n_ranges + 255) / 256), dim3(256), 0, stream, reinterpret_cast<uint64_t*>(totals), l.n_ranges);
     if (chunks > 0)
         hipLaunchKernelGGL((range_pass_kernel<false, kWithPos>), dim3(chunks), dim3(kPartThreads), 0, stream, hashes, n, (uint32_t)n_units, l.n_ranges,
-                           totals, cursors, ranged, ranged_pos);
+                           totals, cursors, ranged);
     hipLaunchKernelGGL(range_offsets_kernel, dim3(1), dim3(kPartThreads), 0, stream, totals, cursors, l.n_ranges);
     if (chunks > 0)
         hipLaunchKernelGGL((range_pass_kernel<true, kWithPos>), dim3(chunks), dim3(kPartThreads), 0, stream, hashes, n, (uint32_t)n_units, l.n_ranges,
-                           totals, cursors, ranged, ranged_pos);
+                           totals, cursors, ranged);
 }
 
 }  // namespace lsm
