@@ -236,7 +236,9 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
             "with_hash_indices": {"ms_per_batch": ms_ix, "probes_per_s": 4096 / (ms_ix * 1e-3),
                                   "requested_keys_per_s": keys / (ms_ix * 1e-3),
                                   "without_filters_ms_per_batch": ms_ix_plain, "length_only_ms_per_batch": ms_ix_len,
-                                  "index_bytes": sum(int(ix.numel()) * 8 for ix in indices), "build_ms_all_runs": index_build_ms},
+                                  "index_bytes": sum(int(ix.numel()) * 8 for ix in indices), "build_ms_all_runs": index_build_ms,
+                                  "traffic": measured_traffic("probe_kernel_cfg4_filtered_indexed",
+                                                              os.path.join(ROOT, "paper_2511_16138_amd", "csrc", "lsm_probe.hip"))},
             "bloom_build_ms_all_runs": bloom_build_ms}
 
 
