@@ -114,7 +114,7 @@ def test_sharded_trees_with_batched_compactions(oracle):
     n_shards, window = 4, 16 * 128
     traces = [lsm.config5(device=dev(), seed=rng.SEED + 1000 * i, tree_total=200_000 + 50_000 * i, buffer_entries=360,
                           ops_per_phase=2048, batch_requests=128) for i in range(n_shards)]
-    backend = GpuBackend(bloom_bits=16)
+    backend = GpuBackend(bloom_bits=16, hash_index_from=5000)   # runs of 5,000 entries and more also get a hash index
     batches = []
     real = backend.compact_batch
     backend.compact_batch = lambda jobs: (batches.append(len(jobs)), real(jobs))[1]
@@ -158,3 +158,7 @@ def test_sharded_trees_with_batched_compactions(oracle):
                 assert np.array_equal(oracle.as_run(gr.run), cr)
                 assert np.array_equal(gr.fences.cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
                 assert np.array_equal(gr.bloom.cpu().numpy().view(np.uint8).reshape(-1, 16), oracle.build_bloom(cr, int(gr.bloom.shape[0])))
+                if cr.shape[0] >= 5000:
+                    assert oracle.hash_index_check(cr, gr.index.cpu().numpy()) == 0
+                else:
+                    assert gr.index is None
