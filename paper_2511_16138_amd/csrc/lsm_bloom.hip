@@ -68,13 +68,25 @@ __global__ void __launch_bounds__(kBloomSmallThreads) bloom_small_kernel(BloomJo
     const uint32_t n_blocks = jobs.n_blocks[blockIdx.y];  // <= kBloomSmallBlocks (checked by the host)
     for (uint32_t w = threadIdx.x; w < n_blocks * 4; w += kBloomSmallThreads) f[w] = 0;
     __syncthreads();
-    for (uint64_t i = threadIdx.x; i < n; i += kBloomSmallThreads) {
-        uint4 mask;
-        const uint32_t block = bloom_block(bloom_hash(load_key(entries + i), mask), n_blocks);
-        if (mask.x) atomicOr(&f[block * 4 + 0], mask.x);
-        if (mask.y) atomicOr(&f[block * 4 + 1], mask.y);
-        if (mask.z) atomicOr(&f[block * 4 + 2], mask.z);
-        if (mask.w) atomicOr(&f[block * 4 + 3], mask.w);
+    // four keys per thread and step, all read before the first is hashed: a short run is one or two round trips
+    constexpr int kAhead = 4;
+    for (uint64_t i0 = threadIdx.x; i0 < n; i0 += (uint64_t)kAhead * kBloomSmallThreads) {
+        Key key[kAhead];
+#pragma unroll
+        for (int a = 0; a < kAhead; a++) {
+            const uint64_t i = i0 + (uint64_t)a * kBloomSmallThreads;
+            key[a] = load_key(entries + (i < n ? i : i0));
+        }
+#pragma unroll
+        for (int a = 0; a < kAhead; a++) {
+            if (i0 + (uint64_t)a * kBloomSmallThreads >= n) break;
+            uint4 mask;
+            const uint32_t block = bloom_block(bloom_hash(key[a], mask), n_blocks);
+            if (mask.x) atomicOr(&f[block * 4 + 0], mask.x);
+            if (mask.y) atomicOr(&f[block * 4 + 1], mask.y);
+            if (mask.z) atomicOr(&f[block * 4 + 2], mask.z);
+            if (mask.w) atomicOr(&f[block * 4 + 3], mask.w);
+        }
     }
     __syncthreads();
     uint4* out = reinterpret_cast<uint4*>(jobs.words[blockIdx.y]);

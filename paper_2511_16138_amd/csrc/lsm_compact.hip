@@ -221,6 +221,26 @@ __device__ __forceinline__ uint64_t select_split(const E* run, uint64_t lo, uint
     return best;
 }
 
+// Two runs: the boundary of merged rank r by bisection on the merge path - how many entries of `a` are among the first r
+// of the merged order (equal keys: a's first) - with two independent reads per step, then moved back by one entry when
+// the two versions of a key would fall on either side of it.  Same result as select_split (the lower bounds of the key x
+// with the largest L(x) <= r) in log2 of the shorter run's length dependent steps instead of a pivoting selection.
+__device__ __forceinline__ void split_two(const lsm_entry_t* a, const uint64_t na, const lsm_entry_t* b, const uint64_t nb, const uint64_t r,
+                                          uint64_t& ia, uint64_t& ib) {
+    const uint64_t d = r < na + nb ? r : na + nb;
+    uint64_t lo = d > nb ? d - nb : 0, hi = d < na ? d : na;  // the count lies in [lo, hi]
+    while (lo < hi) {
+        const uint64_t mid = lo + (hi - lo + 1) / 2;  // lo < mid <= hi, so d - mid < nb
+        // mid entries of a fit among the first d iff a[mid - 1] does not come after b[d - mid]
+        if (key_less_equal(load_key(a + mid - 1), load_key(b + (d - mid)))) lo = mid;
+        else hi = mid - 1;
+    }
+    ia = lo;
+    ib = d - lo;
+    // a's version of a key just before the boundary and b's just after it: the key starts one entry earlier
+    if (ia > 0 && ib < nb && key_equal(load_key(a + ia - 1), load_key(b + ib))) ia--;
+}
+
 // Lane bookkeeping shared by the partition kernels: which problem and which sequence a lane has.
 struct GroupLane {
     int member, group_base;
@@ -253,6 +273,15 @@ __global__ void __launch_bounds__(256) partition_kernel(RunTable rt, Workspace w
     const GroupLane g = group_lane(group);
     const uint64_t b = g.slot + 1;
     const bool own = b < n_tiles && g.member < (int)rt.k;
+    if (rt.k == 2) {  // two runs (every merge of a leveled tree): the merge path is a plain bisection
+        if (own && g.member == 0) {
+            uint64_t ia, ib;
+            split_two(rt.ptr[0], run_len(rt, 0), rt.ptr[1], run_len(rt, 1), b * tile_nominal(2), ia, ib);
+            ws.splits[b * 2 + 0] = ia;
+            ws.splits[b * 2 + 1] = ib;
+        }
+        return;
+    }
     const lsm_entry_t* run = own ? rt.ptr[g.member] : nullptr;
     const uint64_t best = select_split<kShort>(run, 0, own ? run_len(rt, g.member) : 0, b * tile_nominal(rt.k), own, g.member, group, g.group_base);
     if (own) ws.splits[b * rt.k + g.member] = best;
@@ -1071,8 +1100,16 @@ __global__ void __launch_bounds__(256) partition_batch_kernel(Workspace ws, Mode
     const lsm_entry_t* run = own ? ma.run_ptr[d.run_off + g.member] : nullptr;
     const uint64_t len = own ? ma.run_n[d.run_off + g.member] : 0;
     const bool search = t > 0;  // the same for all lanes of a group
-    const uint64_t best = select_split<false>(run, 0, (own && search) ? len : 0, t * tile_nominal(d.k ? d.k : 1), own && search, g.member,
-                                              group, g.group_base);
+    uint64_t best = 0;
+    if (d.k == 2) {  // the two lanes of the group walk the merge path together (the same reads) and keep one bound each
+        if (own && search) {
+            uint64_t ia, ib;
+            split_two(ma.run_ptr[d.run_off], ma.run_n[d.run_off], ma.run_ptr[d.run_off + 1], ma.run_n[d.run_off + 1], t * tile_nominal(2), ia, ib);
+            best = g.member == 0 ? ia : ib;
+        }
+    } else {
+        best = select_split<false>(run, 0, (own && search) ? len : 0, t * tile_nominal(d.k ? d.k : 1), own && search, g.member, group, g.group_base);
+    }
     if (own) {
         uint64_t* rows = ws.splits + d.splits_off;
         rows[t * d.k + g.member] = search ? best : 0;
@@ -1158,7 +1195,7 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
     const uint64_t n_coarse = coarse_rows(n_tiles);  // boundaries kCoarseStride, 2 * kCoarseStride, ... < n_tiles
 
     // a compaction of a few tiles that is not validated: the partition launch does the clearing as well
-    const bool direct = n_tiles > 1 && n_tiles < kSampledMinTiles;
+    const bool direct = n_tiles > 1 && (n_tiles < kSampledMinTiles || n_runs == 2);  // two runs: bisection on the merge path at any size
     const bool fused_init = direct && !(flags & LSM_VALIDATE);
     if (!fused_init) {
         uint32_t init_blocks = (uint32_t)((n_tiles + 255) / 256);
@@ -1183,7 +1220,7 @@ static int launch_compaction(const RunTable& rt, uint32_t flags, const lsm_out_t
         while (group < (int)n_runs) group <<= 1;
         const uint64_t per_block = (uint64_t)(256 / kWave) * (kWave / group);  // selection problems per workgroup
         auto blocks = [&](uint64_t problems) { return dim3((uint32_t)((problems + per_block - 1) / per_block)); };
-        if (n_tiles < kSampledMinTiles) {
+        if (direct) {
             // a few dozen boundaries: every one searched over whole runs (a coarse pass first would be a second
             // dependent launch, which costs more than the longer searches)
             const bool brief = total <= kShortRunsTotal;
