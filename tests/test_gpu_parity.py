@@ -84,6 +84,40 @@ def test_run_counts_and_ragged_lengths(g, oracle, k):
         _check_compact(g, oracle, runs, flags)
 
 
+@pytest.mark.parametrize("case", ["same_keys", "interleaved", "one_inside_the_other", "short_and_long", "batch"])
+def test_two_runs_many_tiles(g, oracle, case):
+    """Two runs (boundaries by bisection on the merge path): every key in both runs (each boundary falls between the
+    two versions of some key), keys that alternate between the runs, one run's key range inside the other's, a short
+    run against a long one, and the same pairs as jobs of a batch - dozens of tiles each, both flags."""
+    from workloads import lsm
+    print("two runs", case, flush=True)
+    w = lsm.config3(device=dev(), scale=64)           # runs of 65,536 entries
+    base = torch.from_numpy(oracle.compact([w.runs[0].cpu(), w.runs[1].cpu()], 0).view(np.int64).reshape(-1, 8).copy()).to(dev())
+    older = base.clone()
+    older[:, 4] = older[:, 4] - 1                     # the same keys with smaller seqnos
+    if case == "same_keys":
+        pairs = [(base[:60_000], older[:60_000])]
+    elif case == "interleaved":
+        pairs = [(base[0:100_000:2].contiguous(), older[1:100_000:2].contiguous())]
+    elif case == "one_inside_the_other":
+        pairs = [(base[30_000:50_000].contiguous(), older[:90_000].contiguous()), (older[:90_000].contiguous(), base[30_000:50_000].contiguous())]
+    elif case == "short_and_long":
+        pairs = [(base[77:78].contiguous(), older[:70_000].contiguous()), (base[:70_000].contiguous(), older[5_000:5_003].contiguous())]
+    else:
+        pairs = [(base[:9_000].contiguous(), older[:9_000].contiguous()), (base[0:30_000:2].contiguous(), older[1:30_000:2].contiguous()),
+                 (base[100:101].contiguous(), older[:5_000].contiguous())]
+    for flags in (0, 1):
+        if case == "batch":
+            outs, n_out = g.lsm_compact_batch([(list(p), flags) for p in pairs])
+            torch.cuda.synchronize()
+            for p, out, n in zip(pairs, outs, n_out.cpu().tolist()):
+                want = oracle.compact([r.cpu() for r in p], flags & 1)
+                assert n == want.shape[0] and np.array_equal(as_bytes(out[:n]).reshape(-1, 64), want)
+        else:
+            for p in pairs:
+                _check_compact(g, oracle, list(p), flags)
+
+
 def test_degenerate_inputs(g, oracle):
     from workloads import lsm
     print("degenerate inputs", flush=True)
