@@ -152,12 +152,17 @@ def filter_pipeline(g, torch, dev, runs, out, n_out_d, ws, fences, n_out: int):
                                              key_hashes=hashes))
     assert int(n_out_d.item()) == n_out
     ms_hashed = timed(lambda: g.lsm_build_bloom_hashed(hashes[:n_out], n_blocks, out=f_hashed, workspace=bws))
+    index = torch.empty((g.lsm_hash_index_buckets(n_out), 8), dtype=torch.int64, device=dev)
+    iws = torch.empty(max(g.lsm_hash_index_workspace_bytes(n_out), 256), dtype=torch.uint8, device=dev)
+    ms_index = timed(lambda: g.lsm_build_hash_index(hashes[:n_out], out=index, workspace=iws))
+    del index, iws
     ms_hash_keys = timed(lambda: g.lsm_hash_keys(out[:n_out], out=h2))
     ms_atomic = timed(lambda: g.lsm_build_bloom(out[:n_out], 16, out=f_atomic))
     assert torch.equal(f_hashed, f_atomic) and torch.equal(h2, hashes[:n_out]), "the two filter builds disagree"
     return {"workload": "the same compaction, new run with fence index and Bloom filter (16 bits per key, %d blocks)" % n_blocks,
             "compact_writing_fences_and_key_hashes_ms": ms_compact, "filter_from_hashes_ms": ms_hashed,
             "total_ms": ms_compact + ms_hashed, "merged_entries_per_s": n_in / ((ms_compact + ms_hashed) * 1e-3),
+            "hash_index_from_hashes_ms": ms_index,
             "separate_builds": {"hash_keys_pass_over_the_run_ms": ms_hash_keys, "filter_by_atomics_ms": ms_atomic}}
 
 

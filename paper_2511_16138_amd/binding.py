@@ -345,6 +345,10 @@ def lsm_hash_index_buckets(n: int) -> int:
     return int(_load().lsm_hash_index_buckets(n))
 
 
+def lsm_hash_index_workspace_bytes(n: int) -> int:
+    return int(_load().lsm_hash_index_workspace_bytes(n))
+
+
 def lsm_build_hash_index(hashes: torch.Tensor, out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                          stream=None) -> torch.Tensor:
     """Hash index of the run whose keys' hashes are given in run order (int64 [n], from lsm_hash_keys or lsm_compact's
