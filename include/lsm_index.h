@@ -94,7 +94,8 @@ typedef struct {
 typedef struct {
     lsm_entry_t* entries; /* DEVICE, 64-byte aligned, room for `capacity` entries           */
     uint64_t capacity;    /* must be >= the total number of input entries                   */
-    uint64_t* n_out;      /* DEVICE, one uint64: number of entries written                  */
+    uint64_t* n_out;      /* DEVICE (or host memory the device can write, e.g. pinned), one
+                           * uint64: number of entries written                               */
     /* Optional: the fence index of the new run, written in the same pass (what lsm_build_fences
      * would give for it).  fence_keys: DEVICE, 16-byte aligned, room for ceil(capacity / fence_stride)
      * keys of 32 bytes, of which the first ceil(*n_out / fence_stride) are written; NULL = none. */

@@ -176,6 +176,16 @@ def _dev(t: torch.Tensor, what: str) -> torch.Tensor:
     return t
 
 
+def _count(t: torch.Tensor, what: str) -> torch.Tensor:
+    """A tensor the kernels write a count to: device memory, or pinned host memory (which the GPU addresses
+    directly, so that the host can read the count after a stream synchronisation, without a copy)."""
+    if not (t.is_cuda or t.is_pinned()):
+        raise ValueError(f"{what} must be a GPU tensor or pinned host memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return t
+
+
 _raw_current_stream = getattr(torch._C, "_cuda_getCurrentRawStream", None)
 
 
@@ -202,7 +212,8 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
                 fences: Optional[torch.Tensor] = None, fence_stride: int = 64,
                 key_hashes: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
     """Merge sorted runs (runs[0] newest).  Returns (out, n_out): out is int64 [capacity, 8]
-    whose first n_out rows are the result, n_out a one-element int64 tensor on the device.
+    whose first n_out rows are the result, n_out a one-element int64 tensor on the device (or, if the caller passes one, in
+    pinned host memory: the count can then be read after a stream synchronisation without a copy).
     `events` = three raw hipEvent_t handles (or 0) for lsm_compact_timed; `remap` = int64 [n_files]
     table of new pointer bases for lsm_compact_remap; `fences` = int64 [>= ceil(capacity / fence_stride), 4]
     that receives the fence index of the result (its first ceil(n_out / fence_stride) rows); `key_hashes` = int64
@@ -219,7 +230,7 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
-    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _dev(n_out, "n_out").data_ptr(),
+    od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _count(n_out, "n_out").data_ptr(),
               _dev(fences, "fences").data_ptr() if fences is not None else None, fence_stride if fences is not None else 0,
               _dev(key_hashes, "key hashes").data_ptr() if key_hashes is not None else None)
     if key_hashes is not None and key_hashes.numel() < out.shape[0]:

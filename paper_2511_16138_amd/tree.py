@@ -59,8 +59,13 @@ class GpuBackend:
         ws = getattr(self, "_workspace", None)
         if ws is None or ws.numel() < need or ws.device != runs[0].device:
             ws = self._workspace = torch.empty(max(2 * need, 1 << 20), dtype=torch.uint8, device=runs[0].device)
-        out, n_out = self._b.lsm_compact(list(runs), flags, fences=fences, fence_stride=self.fence_stride, workspace=ws)
-        n = int(n_out.item())
+        # the count goes straight to pinned host memory: one stream synchronisation instead of a device-to-host copy
+        n_host = getattr(self, "_n_host", None)
+        if n_host is None:
+            n_host = self._n_host = torch.empty(1, dtype=torch.int64, pin_memory=True)
+        out, _ = self._b.lsm_compact(list(runs), flags, n_out=n_host, fences=fences, fence_stride=self.fence_stride, workspace=ws)
+        torch.cuda.current_stream().synchronize()
+        n = int(n_host.item())
         if n < 0 or n > out.shape[0]:
             raise RuntimeError("lsm_compact reported a device-side failure")
         merged = out[:n]
