@@ -8,14 +8,19 @@
  * data-parallel part of that index on one AMD MI355X (gfx950):
  *
  *   lsm_compact       merge sorted runs into one run (section 2.2, compaction); lsm_compact_remap also rewrites
- *                     value pointers for merged tensor files (section 3.4)
+ *                     value pointers for merged tensor files (section 3.4); lsm_compact_batch runs many small
+ *                     compactions in one launch; lsm_compact_static allocates nothing
  *   lsm_flush_buffer  the write buffer as a sorted run (section 2.2)
  *   lsm_build_fences  fence-pointer index of a run (section 2.2 names fence pointers)
- *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes)
+ *   lsm_build_bloom   Bloom filter of a run (section 2.2 names Bloom filters; appendix B uses them in probes);
+ *                     lsm_hash_keys + lsm_build_bloom_hashed build the same filter of a long run from the keys'
+ *                     hashes, which lsm_compact can write for its output in its own pass
+ *   lsm_build_hash_index  hash index of a run: a lookup finds or rules out a key without the fence search
  *   lsm_probe         batched longest-cached-prefix lookup over a tree (appendix B, "Probe";
  *                     section 2.2, "Point Lookups"); lsm_probe_length gives the length alone by a
  *                     search over the prefix length
- *   lsm_range_bounds  where a key range lies in every run (section 2.2, "Range Lookups")
+ *   lsm_range_scan    the live content of many key ranges (section 2.2, "Range Lookups"; appendix B get_batch);
+ *                     lsm_range_bounds: where one key range lies in every run
  *   lsm_policy_*      the adaptive controller's cost model (section 2.2 costs, section 3.3)
  *
  * Conventions
