@@ -60,6 +60,7 @@ __global__ void bloom_insert_batch_kernel(BloomJobs jobs) {
 // A filter of at most kBloomSmallBlocks blocks (64 KiB) is built by one workgroup in LDS and written out once: one
 // launch and no global atomics, for the short runs of a tree's upper levels.  blockIdx.y = run.
 constexpr uint32_t kBloomSmallBlocks = 4096;
+constexpr uint64_t kBloomSmallKeys = 1u << 18;  // a longer run with so small a filter is left to the whole device
 constexpr int kBloomSmallThreads = 1024;
 __global__ void __launch_bounds__(kBloomSmallThreads) bloom_small_kernel(BloomJobs jobs) {
     __shared__ uint32_t f[kBloomSmallBlocks * 4];
@@ -185,7 +186,7 @@ extern "C" int lsm_build_bloom(const lsm_run_t* run, void* filter_out, uint64_t 
     if ((reinterpret_cast<uintptr_t>(filter_out) & 15) != 0 || (reinterpret_cast<uintptr_t>(run->entries) & 63) != 0)
         return LSM_ERR_BAD_ARG;
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    if (n_blocks <= kBloomSmallBlocks) {
+    if (n_blocks <= kBloomSmallBlocks && run->n <= kBloomSmallKeys) {
         BloomJobs jobs = {};
         jobs.entries[0] = run->entries;
         jobs.n[0] = run->n;
@@ -230,7 +231,7 @@ extern "C" int lsm_build_bloom_batch(const lsm_run_t* runs, void* const* filters
             most_blocks = n_blocks[first + j] > most_blocks ? n_blocks[first + j] : most_blocks;
             most_entries = runs[first + j].n > most_entries ? runs[first + j].n : most_entries;
         }
-        if (most_blocks <= kBloomSmallBlocks) {
+        if (most_blocks <= kBloomSmallBlocks && most_entries <= kBloomSmallKeys) {
             hipLaunchKernelGGL(bloom_small_kernel, dim3(1, count), dim3(kBloomSmallThreads), 0, stream, jobs);
             continue;
         }

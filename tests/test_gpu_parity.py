@@ -520,6 +520,10 @@ def test_filter_built_from_hashes_equals_the_checker(g, oracle, n, bits):
         got = g.lsm_build_bloom_hashed(hashes, n_blocks, out=torch.full((n_blocks, 4), -1, dtype=torch.int32, device=dev()), workspace=ws)
         torch.cuda.synchronize()
         assert np.array_equal(as_bytes(got).reshape(-1, 16), oracle.build_bloom(run.cpu(), n_blocks))
+    if n == 300_000 and bits == 16:   # a long run with a filter of three blocks: lsm_build_bloom's path for long runs
+        tiny = g.lsm_build_bloom(run, 16, out=torch.full((3, 4), -1, dtype=torch.int32, device=dev()))
+        torch.cuda.synchronize()
+        assert np.array_equal(as_bytes(tiny).reshape(-1, 16), oracle.build_bloom(run.cpu(), 3))
 
 
 # ------------------------------------------------------------------ prefix length by search (appendix B)
