@@ -226,8 +226,8 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
         out = torch.empty((max(total, 1), 8), dtype=torch.int64, device=dev)
     if n_out is None:
         n_out = torch.empty(1, dtype=torch.int64, device=dev)
-    need = lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs]) if runs else 0
     if workspace is None:
+        need = lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs]) if runs else 0
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     rd = (_Run * max(1, len(runs)))(*[_Run(r.data_ptr(), int(r.shape[0])) for r in runs])
     od = _Out(_dev(out, "out").data_ptr(), int(out.shape[0]), _count(n_out, "n_out").data_ptr(),
