@@ -253,6 +253,30 @@ def lsm_compact(runs: Sequence[torch.Tensor], flags: int = 0, out: Optional[torc
     return out, n_out
 
 
+class CompactCall:
+    """A reusable argument block for lsm_compact on GPU tensors: the descriptors are filled in place from call to call
+    instead of being built anew (a driver that issues thousands of small compactions spends more time building them than
+    the kernels run).  The tensors are taken as they are (the library checks pointers, alignment and sizes); returns the
+    library's status code."""
+
+    def __init__(self):
+        self._lib = _load()
+        self._runs = (_Run * LSM_MAX_RUNS)()
+        self._out = _Out()
+        self._out_ref = C.byref(self._out)
+
+    def __call__(self, runs: Sequence[torch.Tensor], flags: int, out: torch.Tensor, n_out: torch.Tensor,
+                 fences: torch.Tensor, fence_stride: int, workspace: torch.Tensor, stream=None) -> int:
+        rd = self._runs
+        for j, r in enumerate(runs):
+            rd[j].entries = r.data_ptr()
+            rd[j].n = r.shape[0]
+        od = self._out
+        od.entries, od.capacity, od.n_out = out.data_ptr(), out.shape[0], n_out.data_ptr()
+        od.fence_keys, od.fence_stride = fences.data_ptr(), fence_stride
+        return self._lib.lsm_compact(rd, len(runs), flags, self._out_ref, workspace.data_ptr(), workspace.numel(), _stream_ptr(stream))
+
+
 def lsm_compact_static(runs: Sequence[torch.Tensor], flags: int, out: torch.Tensor, n_out: torch.Tensor, stream=None,
                        fences: Optional[torch.Tensor] = None, fence_stride: int = 64,
                        key_hashes: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:

@@ -52,20 +52,29 @@ class GpuBackend:
 
     def compact(self, runs: Sequence[Any], flags: int) -> Any:
         import torch
-        total = sum(int(r.shape[0]) for r in runs)
-        fences = torch.empty(((total + self.fence_stride - 1) // self.fence_stride, 4), dtype=torch.int64, device=runs[0].device)
-        # one workspace for all compactions of this backend (they follow each other on one stream), grown when needed
-        need = self._b.lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs])
-        ws = getattr(self, "_workspace", None)
-        if ws is None or ws.numel() < need or ws.device != runs[0].device:
-            ws = self._workspace = torch.empty(max(2 * need, 1 << 20), dtype=torch.uint8, device=runs[0].device)
-        # the count goes straight to pinned host memory: one stream synchronisation instead of a device-to-host copy
-        n_host = getattr(self, "_n_host", None)
-        if n_host is None:
-            n_host = self._n_host = torch.empty(1, dtype=torch.int64, pin_memory=True)
-        out, _ = self._b.lsm_compact(list(runs), flags, n_out=n_host, fences=fences, fence_stride=self.fence_stride, workspace=ws)
+        runs = [r if r.is_contiguous() else r.contiguous() for r in runs]
+        if len(runs) > self._b.LSM_MAX_RUNS:
+            raise ValueError("too many runs for one compaction")
+        total = sum(r.shape[0] for r in runs)
+        device = runs[0].device
+        fences = torch.empty(((total + self.fence_stride - 1) // self.fence_stride, 4), dtype=torch.int64, device=device)
+        out = torch.empty((max(total, 1), 8), dtype=torch.int64, device=device)
+        # one workspace for all compactions of this backend (they follow each other on one stream), grown when the library
+        # says it is too small; the count goes straight to pinned host memory: one stream synchronisation, no copy
+        call = getattr(self, "_call", None)
+        if call is None:
+            call = self._call = self._b.CompactCall()
+            self._n_host = torch.empty(1, dtype=torch.int64, pin_memory=True)
+            self._workspace = torch.empty(1 << 20, dtype=torch.uint8, device=device)
+        rc = call(runs, flags, out, self._n_host, fences, self.fence_stride, self._workspace)
+        if rc == -4:   # LSM_ERR_WORKSPACE
+            need = self._b.lsm_compact_workspace_bytes([int(r.shape[0]) for r in runs])
+            self._workspace = torch.empty(2 * need, dtype=torch.uint8, device=device)
+            rc = call(runs, flags, out, self._n_host, fences, self.fence_stride, self._workspace)
+        if rc != 0:
+            raise self._b.LsmError(rc, "lsm_compact")
         torch.cuda.current_stream().synchronize()
-        n = int(n_host.item())
+        n = int(self._n_host.item())
         if n < 0 or n > out.shape[0]:
             raise RuntimeError("lsm_compact reported a device-side failure")
         merged = out[:n]
