@@ -482,6 +482,7 @@ def main() -> int:
     copy_gbps = 2 * half * 8 / (c0.elapsed_time(c1) / 5 * 1e-3) / 1e9
     result["copy_ceiling_gbps"] = copy_gbps
     result["compact_frac_of_copy_ceiling"] = result["compact_hbm_gbps"] / copy_gbps
+    result["merge_kernel_frac_of_copy_ceiling"] = achieved / copy_gbps
     del src, dst
     result["filter_pipeline"] = filter_pipeline(g, torch, dev, runs, out, n_out_d, ws, fences, n_out)
     cpu_sample = None if args.no_cpu_baseline else [r.cpu() for r in runs]  # the whole workload: a few seconds for the checker
