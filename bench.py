@@ -249,43 +249,62 @@ def probe_config4(g, lsm, torch, dev, n_batches: int, scale: int):
 
 def mixed_config5(g, lsm, torch, dev, scale: int):
     """Mixed shifting workload on the 6-level, 400M-entry tree: flushes, compactions chosen by the
-    adaptive controller and probe batches, replayed by the host driver.  Probe batches are generated
-    before the clock starts."""
+    adaptive controller and probe batches, replayed twice: by the library's own driver (lsm_driver_*) and by the Python
+    driver over the single entry points.  Probe batches are generated before the clock starts."""
     from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
     tr = lsm.config5(device=dev, tree_total=400_000_000 // scale, buffer_entries=max(36, 3600 // scale),
                      ops_per_phase=(1 << 18) // scale)
-    tree = AdaptiveLsmTree(GpuBackend(bloom_bits=16), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests,
-                           t_grid=(2, 16))
+    batches = {i: tr.probe_batch(i) for kind, i, _ in tr.events if kind == "probe"}
+
+    def replay(tree):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        t_probe = 0.0
+        for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
+            if n_writes:
+                tree.note_writes(n_writes)
+            if kind == "flush":
+                tree.flush(tr.flush_runs[i])
+            else:
+                torch.cuda.synchronize()
+                tp = time.perf_counter()
+                tree.probe(*batches[i])
+                torch.cuda.synchronize()
+                t_probe += time.perf_counter() - tp
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        trace = list(tree.trace)
+        comp = [e for e in trace if e[0] == "compact"]
+        merged = sum(e[3] for e in comp)
+        n_probe = sum(e[1] for e in trace if e[0] == "probe")
+        return trace, {"seconds": dt, "compactions": len(comp), "entries_merged": merged,
+                       "merged_entries_per_s_incl_host": merged / max(dt - t_probe, 1e-9),
+                       "probes": n_probe, "probes_per_s_incl_host": n_probe / max(t_probe, 1e-9)}
+
+    window = 16 * tr.batch_requests
+    native = g.LsmDriver(tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=(2, 16), bloom_bits=16)
+    for level, r in enumerate(tr.workload.runs):
+        native.load_run(level + 1, r)
+    native_trace, native_res = replay(native)
+    native_sizes, at = [], 0
+    runs = native.tree()
+    for _t, _k, n_runs in native.levels():
+        native_sizes.append([int(t.run.n) for t in runs[at:at + n_runs]])
+        at += n_runs
+    native.close()
+    tree = AdaptiveLsmTree(GpuBackend(bloom_bits=16), tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=(2, 16))
     for level, r in enumerate(tr.workload.runs):
         tree.load_level(level, [r])
-    batches = {i: tr.probe_batch(i) for kind, i, _ in tr.events if kind == "probe"}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    t_probe = 0.0
-    for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
-        if n_writes:
-            tree.note_writes(n_writes)
-        if kind == "flush":
-            tree.flush(tr.flush_runs[i])
-        else:
-            torch.cuda.synchronize()
-            tp = time.perf_counter()
-            tree.probe(*batches[i])
-            torch.cuda.synchronize()
-            t_probe += time.perf_counter() - tp
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    comp = [e for e in tree.trace if e[0] == "compact"]
-    merged = sum(e[3] for e in comp)
-    n_probe = sum(e[1] for e in tree.trace if e[0] == "probe")
+    trace, res = replay(tree)
+    sizes = [[r.n for r in lv] for lv in tree.levels]
+    assert trace == native_trace and sizes == native_sizes, "the two drivers built different trees"
     return {"workload": "configs[4]: %d-level tree of %d entries, %d flushes of %d entries, %d probe batches"
                         % (len(tr.workload.runs), sum(int(r.shape[0]) for r in tr.workload.runs), tr.flush_runs.shape[0],
                            tr.buffer_entries, len(batches)),
-            "seconds": dt, "compactions": len(comp), "entries_merged": merged,
-            "merged_entries_per_s_incl_host": merged / max(dt - t_probe, 1e-9),
-            "probes": n_probe, "probes_per_s_incl_host": n_probe / max(t_probe, 1e-9),
-            "policy_trace_T_K": [e[1:3] for e in tree.trace if e[0] == "policy"],
-            "final_level_sizes": [[r.n for r in lv] for lv in tree.levels]}
+            **native_res, "driver": "lsm_driver_* (C++, in the library)",
+            "python_driver": res,
+            "policy_trace_T_K": [e[1:3] for e in trace if e[0] == "policy"],
+            "final_level_sizes": sizes}
 
 
 def sharded_config5(g, lsm, torch, dev, n_shards: int, scale: int):

@@ -22,11 +22,14 @@
  *   lsm_range_scan    the live content of many key ranges (section 2.2, "Range Lookups"; appendix B get_batch);
  *                     lsm_range_bounds: where one key range lies in every run
  *   lsm_policy_*      the adaptive controller's cost model (section 2.2 costs, section 3.3)
+ *   lsm_driver_*      the host driver of one tree: levels, the sliding-window controller and the lazy transition of
+ *                     (T, K) (section 3.3, appendix C), sequencing the calls above
  *
  * Conventions
  *   - Pointers marked DEVICE are HIP device memory on the current device; pointers marked
- *     HOST are ordinary host memory read during the call only.  The library never allocates
- *     or frees device memory and keeps no state between calls; the caller owns every buffer.
+ *     HOST are ordinary host memory read during the call only.  Apart from lsm_driver_* (a driver
+ *     object owns the runs it creates), the library never allocates or frees device memory and
+ *     keeps no state between calls; the caller owns every buffer.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream).
  *     Calls return as soon as the work is enqueued unless stated otherwise; outputs are
  *     valid once the stream has been synchronised.
@@ -467,6 +470,99 @@ int lsm_policy_choose(const lsm_policy_input_t* in, uint32_t t_min, uint32_t t_m
  * returns 1.  About 0.0022 at 16 bits per key.
  */
 double lsm_policy_filter_fpr(uint32_t bits_per_key);
+
+/*
+ * lsm_driver_* -- the host driver of one tree: level bookkeeping (section 2.2: flushed runs enter level 1, a level
+ * holds at most K runs and M * T^level entries, full levels are merged and overflowing ones moved down), the
+ * adaptive controller (section 3.3: operation counts over a sliding window, a new (T, K) search when the mix has
+ * moved by more than a threshold) and the lazy transition (appendix C: a level takes the current T and K when data
+ * next flows into it; a smaller K merges the level at that arrival, a larger K leaves it alone).  It sequences the
+ * calls above on one stream and owns the device memory of the runs it creates (a pool that is given back only by
+ * lsm_driver_destroy).  One thread at a time per driver.  Every call returns an lsm_status; after an error other
+ * than LSM_ERR_NULL / LSM_ERR_BAD_ARG the driver's tree is undefined and it can only be destroyed.
+ *
+ * Readings where the paper gives no constants: an operation is one inserted sequence (lsm_driver_note_writes) or one
+ * probe request; a request that finds no live first block is an empty probe (z), the others count half as range
+ * reads (s) and half as point reads (r); d = mean number of blocks a successful request found; N = entries in the
+ * tree at the time of the search; the window is the shortest suffix of the reported batches that covers window_ops
+ * operations, and no search is made before it is that long; "moved" = L1 distance of (w, s, r, z) to the mix of the
+ * last search > shift_threshold.
+ */
+typedef struct lsm_driver lsm_driver_t;
+
+enum { LSM_EV_ADOPT = 1, LSM_EV_COMPACT = 2, LSM_EV_MOVE = 3, LSM_EV_PROBE = 4, LSM_EV_POLICY = 5 };
+
+/* One record of the driver's log.  Levels are 1-based.
+ *   ADOPT    level takes over new parameters:  level, a = T, b = K
+ *   COMPACT  all runs of a level merged:       level, a = number of runs, b = flags, n_in, n_out = entries in / out
+ *   MOVE     merged run moved down:            level = from, a = to, n_out = its entries
+ *   PROBE    one probe batch:                  a = requests, b = requests with hit_len > 0, n_out = sum of hit_len
+ *   POLICY   a (T, K) search:                  a = T, b = K, mix = (w, s, r, z), d                                */
+typedef struct {
+    uint32_t kind, level, a, b;
+    uint64_t n_in, n_out;
+    double mix[4];
+    double d;
+} lsm_driver_event_t;
+
+/* Called after every compaction, when its output is complete (the stream has been waited for): entries is DEVICE
+ * memory owned by the driver, valid only during the call. */
+typedef void (*lsm_driver_observer_t)(void* ctx, uint32_t level, const lsm_entry_t* entries, uint64_t n);
+
+typedef struct {
+    uint64_t buffer_entries;  /* M: entries of a full write buffer (> 0)                                 */
+    uint32_t size_ratio;      /* T the levels start with (>= 2)                                          */
+    uint32_t runs_per_level;  /* K the levels start with (>= 1)                                          */
+    uint64_t window_ops;      /* operations the sliding window covers                                    */
+    double shift_threshold;   /* L1 distance of the mix that triggers a new search                       */
+    uint32_t t_min, t_max;    /* range of T the search may choose from (t_min >= 2)                      */
+    double page_entries;      /* B of the cost model                                                     */
+    double filter_fpr;        /* p of the cost model; negative = lsm_policy_filter_fpr(bloom_bits)       */
+    uint32_t fence_stride;    /* > 0                                                                     */
+    uint32_t bloom_bits;      /* bits per key of the runs' filters; 0 = no filters                       */
+    uint64_t hash_index_from; /* runs of at least this many entries also get a hash index; 0 = none      */
+    lsm_driver_observer_t observer; /* may be NULL */
+    void* observer_ctx;
+} lsm_driver_config_t;
+
+/* stream: the HIP stream all of the driver's work is enqueued on (NULL = the default stream). */
+int lsm_driver_create(const lsm_driver_config_t* config, void* stream, lsm_driver_t** driver_out);
+/* Waits for the stream, frees everything the driver allocated. NULL is allowed. */
+void lsm_driver_destroy(lsm_driver_t* driver);
+
+/* The starting tree: appends a run as the OLDEST run of `level` (1-based) without merging anything, and builds its
+ * fence index, filter and hash index.  entries: DEVICE, borrowed - it must stay valid until the run has been merged
+ * away (it no longer appears in lsm_driver_tree) or the driver is destroyed; the driver never frees it. */
+int lsm_driver_load_run(lsm_driver_t* driver, uint32_t level, const lsm_entry_t* entries, uint64_t n);
+
+/* n_ops sequences were inserted since the last report (the controller's write count). */
+int lsm_driver_note_writes(lsm_driver_t* driver, uint64_t n_ops);
+
+/* A sorted run from the write buffer enters level 1; every compaction and move this triggers is done before the call
+ * returns.  run: DEVICE, strictly ascending; it is read only by work that the call enqueues on the driver's stream (a
+ * run that comes to rest is copied), so the caller may reuse the memory in stream order afterwards. */
+int lsm_driver_flush(lsm_driver_t* driver, const lsm_entry_t* run, uint64_t n);
+/* The same for a write buffer as it was filled (any order, repeated keys; n <= LSM_MAX_BUFFER): sorted and reduced to
+ * the newest version of every key by lsm_flush_buffer first. */
+int lsm_driver_flush_unsorted(lsm_driver_t* driver, const lsm_entry_t* buffer, uint64_t n);
+
+/* lsm_probe over the current tree (run_idx of a hit = position in lsm_driver_tree's order); the call waits for the
+ * result, counts the batch in the window and may re-run the (T, K) search.  More than LSM_MAX_RUNS runs in the tree:
+ * LSM_ERR_BAD_ARG. */
+int lsm_driver_probe(lsm_driver_t* driver, const lsm_queries_t* queries, const lsm_hits_t* out_hits);
+
+/* Inspection.  lsm_driver_levels: number of levels.  lsm_driver_level: the parameters level `level` (1-based) runs
+ * with and its number of runs.  lsm_driver_tree: the runs newest -> oldest with their lookup structures (`level`
+ * field = 1-based level), at most `capacity` of them, *n_runs = how many there are; the DEVICE pointers stay valid
+ * until the next flush.  lsm_driver_target: the (T, K) the controller currently asks for.  lsm_driver_log: copies
+ * records first .. first + capacity - 1 of the log and returns the total number of records.  lsm_driver_read: waits
+ * for the stream and copies `bytes` bytes of driver-owned DEVICE memory to dst (HOST or DEVICE). */
+uint32_t lsm_driver_levels(const lsm_driver_t* driver);
+int lsm_driver_level(const lsm_driver_t* driver, uint32_t level, uint32_t* T, uint32_t* K, uint32_t* n_runs);
+int lsm_driver_tree(const lsm_driver_t* driver, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs);
+int lsm_driver_target(const lsm_driver_t* driver, uint32_t* T, uint32_t* K);
+uint64_t lsm_driver_log(const lsm_driver_t* driver, uint64_t first, lsm_driver_event_t* out, uint64_t capacity);
+int lsm_driver_read(lsm_driver_t* driver, const void* device_src, void* dst, size_t bytes);
 
 const char* lsm_strerror(int code);
 

@@ -97,6 +97,21 @@ class _PolicyInput(C.Structure):
                 ("buffer_entries", C.c_uint64), ("B", C.c_double), ("p", C.c_double), ("d", C.c_double)]
 
 
+class _DriverEvent(C.Structure):
+    _fields_ = [("kind", C.c_uint32), ("level", C.c_uint32), ("a", C.c_uint32), ("b", C.c_uint32), ("n_in", C.c_uint64),
+                ("n_out", C.c_uint64), ("mix", C.c_double * 4), ("d", C.c_double)]
+
+
+_DriverObserver = C.CFUNCTYPE(None, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64)
+
+
+class _DriverConfig(C.Structure):
+    _fields_ = [("buffer_entries", C.c_uint64), ("size_ratio", C.c_uint32), ("runs_per_level", C.c_uint32),
+                ("window_ops", C.c_uint64), ("shift_threshold", C.c_double), ("t_min", C.c_uint32), ("t_max", C.c_uint32),
+                ("page_entries", C.c_double), ("filter_fpr", C.c_double), ("fence_stride", C.c_uint32), ("bloom_bits", C.c_uint32),
+                ("hash_index_from", C.c_uint64), ("observer", _DriverObserver), ("observer_ctx", C.c_void_p)]
+
+
 _lib: Optional[C.CDLL] = None
 
 
@@ -162,6 +177,32 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_policy_choose.argtypes = [C.POINTER(_PolicyInput), C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
     L.lsm_policy_filter_fpr.restype = C.c_double
     L.lsm_policy_filter_fpr.argtypes = [C.c_uint32]
+    L.lsm_driver_create.restype = C.c_int
+    L.lsm_driver_create.argtypes = [C.POINTER(_DriverConfig), C.c_void_p, C.POINTER(C.c_void_p)]
+    L.lsm_driver_destroy.restype = None
+    L.lsm_driver_destroy.argtypes = [C.c_void_p]
+    L.lsm_driver_load_run.restype = C.c_int
+    L.lsm_driver_load_run.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64]
+    L.lsm_driver_note_writes.restype = C.c_int
+    L.lsm_driver_note_writes.argtypes = [C.c_void_p, C.c_uint64]
+    L.lsm_driver_flush.restype = C.c_int
+    L.lsm_driver_flush.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+    L.lsm_driver_flush_unsorted.restype = C.c_int
+    L.lsm_driver_flush_unsorted.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+    L.lsm_driver_probe.restype = C.c_int
+    L.lsm_driver_probe.argtypes = [C.c_void_p, C.POINTER(_Queries), C.POINTER(_Hits)]
+    L.lsm_driver_levels.restype = C.c_uint32
+    L.lsm_driver_levels.argtypes = [C.c_void_p]
+    L.lsm_driver_level.restype = C.c_int
+    L.lsm_driver_level.argtypes = [C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    L.lsm_driver_tree.restype = C.c_int
+    L.lsm_driver_tree.argtypes = [C.c_void_p, C.POINTER(_TreeRun), C.c_uint32, C.POINTER(C.c_uint32)]
+    L.lsm_driver_target.restype = C.c_int
+    L.lsm_driver_target.argtypes = [C.c_void_p, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]
+    L.lsm_driver_log.restype = C.c_uint64
+    L.lsm_driver_log.argtypes = [C.c_void_p, C.c_uint64, C.POINTER(_DriverEvent), C.c_uint64]
+    L.lsm_driver_read.restype = C.c_int
+    L.lsm_driver_read.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
     L.lsm_strerror.restype = C.c_char_p
     L.lsm_strerror.argtypes = [C.c_int]
     _lib = L
@@ -581,3 +622,124 @@ def lsm_policy_choose(w, s, r, z, n_entries, buffer_entries, t_min, t_max, B, p,
     if rc != 0:
         raise LsmError(rc, "lsm_policy_choose")
     return int(bt.value), int(bk.value)
+
+
+class LsmDriver:
+    """lsm_driver_*: the library's own host driver of one tree (levels, controller, lazy transition; see the header).
+    The driver works on the stream that is current when it is created.  Tensors handed to load_run are borrowed and
+    kept alive here; everything the driver creates lives in its own pool until close()."""
+
+    def __init__(self, buffer_entries: int, size_ratio: int = 10, runs_per_level: int = 1, window_ops: int = 4096,
+                 shift_threshold: float = 0.2, t_grid: Tuple[int, int] = (10, 10), page_entries: float = 64.0,
+                 filter_fpr: Optional[float] = None, fence_stride: int = 64, bloom_bits: int = 0, hash_index_from: int = 0,
+                 on_compaction=None, stream=None):
+        L = _load()
+        self._on_compaction = on_compaction   # called with (level, int64 [n, 8] copy of the output on the GPU)
+        self._observer = _DriverObserver(self._observe) if on_compaction is not None else _DriverObserver()
+        cfg = _DriverConfig(buffer_entries, size_ratio, runs_per_level, window_ops, shift_threshold, t_grid[0], t_grid[1],
+                            page_entries, -1.0 if filter_fpr is None else filter_fpr, fence_stride, bloom_bits, hash_index_from,
+                            self._observer, None)
+        self._h = C.c_void_p()
+        rc = L.lsm_driver_create(C.byref(cfg), _stream_ptr(stream), C.byref(self._h))
+        if rc != 0:
+            raise LsmError(rc, "lsm_driver_create")
+        self._borrowed: List[torch.Tensor] = []
+        self._device = torch.device("cuda", torch.cuda.current_device())
+        self._events: List[tuple] = []
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            _load().lsm_driver_destroy(self._h)
+            self._h = None
+            self._borrowed = []
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:   # interpreter shutdown: the library may be gone already
+            pass
+
+    def _check(self, rc: int, where: str) -> None:
+        if rc != 0:
+            raise LsmError(rc, where)
+
+    def read(self, ptr: int, rows: int, cols: int, dtype=torch.int64) -> torch.Tensor:
+        """A copy, on the GPU, of rows x cols elements of driver-owned device memory."""
+        out = torch.empty((rows, cols), dtype=dtype, device=self._device)
+        if out.numel():
+            self._check(_load().lsm_driver_read(self._h, ptr, out.data_ptr(), out.numel() * out.element_size()), "lsm_driver_read")
+        return out
+
+    def _observe(self, _ctx, level, entries, n) -> None:
+        self._on_compaction(int(level), self.read(entries, int(n), 8))
+
+    def load_run(self, level: int, run: torch.Tensor) -> None:
+        """Appends `run` as the oldest run of `level` (1-based); nothing is merged."""
+        self._borrowed.append(_dev(run, "run"))
+        self._check(_load().lsm_driver_load_run(self._h, level, run.data_ptr(), int(run.shape[0])), "lsm_driver_load_run")
+
+    def note_writes(self, n_ops: int) -> None:
+        self._check(_load().lsm_driver_note_writes(self._h, n_ops), "lsm_driver_note_writes")
+
+    def flush(self, run: torch.Tensor) -> None:
+        self._check(_load().lsm_driver_flush(self._h, _dev(run, "run").data_ptr(), int(run.shape[0])), "lsm_driver_flush")
+
+    def flush_unsorted(self, buffer: torch.Tensor) -> None:
+        self._check(_load().lsm_driver_flush_unsorted(self._h, _dev(buffer, "buffer").data_ptr(), int(buffer.shape[0])),
+                    "lsm_driver_flush_unsorted")
+
+    def probe(self, qkeys: torch.Tensor, n_blocks: torch.Tensor, hit_len: Optional[torch.Tensor] = None,
+              hits: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+        n_req, max_blocks = int(_dev(qkeys, "qkeys").shape[0]), int(qkeys.shape[1])
+        if hit_len is None:
+            hit_len = torch.empty(n_req, dtype=torch.int32, device=qkeys.device)
+        if hits is None:
+            hits = torch.empty((n_req, max_blocks, 2), dtype=torch.int64, device=qkeys.device)
+        qd = _Queries(qkeys.data_ptr(), _dev(n_blocks, "n_blocks").data_ptr(), n_req, max_blocks)
+        hd = _Hits(_dev(hit_len, "hit_len").data_ptr(), _dev(hits, "hits").data_ptr())
+        self._check(_load().lsm_driver_probe(self._h, C.byref(qd), C.byref(hd)), "lsm_driver_probe")
+        return hit_len, hits
+
+    def target(self) -> Tuple[int, int]:
+        t, k = C.c_uint32(0), C.c_uint32(0)
+        self._check(_load().lsm_driver_target(self._h, C.byref(t), C.byref(k)), "lsm_driver_target")
+        return int(t.value), int(k.value)
+
+    def levels(self) -> List[Tuple[int, int, int]]:
+        """(T, K, number of runs) of every level, level 1 first."""
+        L, out = _load(), []
+        for level in range(1, int(L.lsm_driver_levels(self._h)) + 1):
+            t, k, n = C.c_uint32(0), C.c_uint32(0), C.c_uint32(0)
+            self._check(L.lsm_driver_level(self._h, level, C.byref(t), C.byref(k), C.byref(n)), "lsm_driver_level")
+            out.append((int(t.value), int(k.value), int(n.value)))
+        return out
+
+    def tree(self):
+        """The runs newest -> oldest as _TreeRun descriptors (device pointers, valid until the next flush)."""
+        L, n = _load(), C.c_uint32(0)
+        self._check(L.lsm_driver_tree(self._h, None, 0, C.byref(n)), "lsm_driver_tree")
+        runs = (_TreeRun * max(1, n.value))()
+        self._check(L.lsm_driver_tree(self._h, runs, n.value, C.byref(n)), "lsm_driver_tree")
+        return [runs[i] for i in range(n.value)]
+
+    @property
+    def trace(self) -> List[tuple]:
+        """The driver's log as tuples: ("adopt", level, T, K), ("compact", level, runs, n_in, n_out, flags),
+        ("move", level, to, n), ("probe", requests, hits, blocks), ("policy", T, K, mix rounded to 6 places, d likewise)."""
+        L = _load()
+        total = int(L.lsm_driver_log(self._h, 0, None, 0))
+        while len(self._events) < total:
+            buf = (_DriverEvent * min(total - len(self._events), 4096))()
+            L.lsm_driver_log(self._h, len(self._events), buf, len(buf))
+            for e in buf:
+                if e.kind == 1:
+                    self._events.append(("adopt", e.level, e.a, e.b))
+                elif e.kind == 2:
+                    self._events.append(("compact", e.level, e.a, e.n_in, e.n_out, e.b))
+                elif e.kind == 3:
+                    self._events.append(("move", e.level, e.a, e.n_out))
+                elif e.kind == 4:
+                    self._events.append(("probe", e.a, e.b, e.n_out))
+                else:
+                    self._events.append(("policy", e.a, e.b, tuple(round(x, 6) for x in e.mix), round(e.d, 6)))
+        return self._events

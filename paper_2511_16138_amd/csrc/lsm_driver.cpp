@@ -1,0 +1,493 @@
+// lsm_driver_*: the host driver of one tree.  Level bookkeeping of section 2.2 (a flushed run enters level 1; a level
+// that holds more than K runs is merged; a merged run larger than M * T^level moves down), the controller of section
+// 3.3 (operation counts over a sliding window, a new (T, K) search when the mix has moved by more than a threshold)
+// and the lazy transition of appendix C (a level takes the current T and K when a run next arrives at it).  Nothing
+// here touches entries: merging, fence indices, filters, hash indices, lookups and the cost model are the library's
+// own entry points, enqueued on one stream.
+//
+// Device memory of the runs the driver creates comes from a pool that keeps every block for reuse (hipMalloc and
+// hipFree cost more than a small compaction, and hipFree waits for the device).  A block that is given back may still
+// be read by work already enqueued; that is safe because its next user's work is enqueued later on the same stream.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <deque>
+#include <map>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "lsm_index.h"
+
+namespace {
+
+class DevicePool {
+public:
+    void* take(size_t bytes) {
+        const size_t c = size_class(bytes);
+        std::vector<void*>& idle = idle_[c];
+        if (!idle.empty()) {
+            void* p = idle.back();
+            idle.pop_back();
+            return p;
+        }
+        void* p = nullptr;
+        if (hipMalloc(&p, c) != hipSuccess) return nullptr;
+        size_of_[p] = c;
+        return p;
+    }
+    void give(const void* p) {
+        if (p == nullptr) return;
+        auto it = size_of_.find(const_cast<void*>(p));
+        if (it != size_of_.end()) idle_[it->second].push_back(it->first);
+    }
+    void free_all() {  // the caller has waited for the stream
+        for (auto& kv : size_of_) (void)hipFree(kv.first);
+        size_of_.clear();
+        idle_.clear();
+    }
+
+private:
+    // four classes per power of two from 256 bytes up: at most a quarter of a block is unused
+    static size_t size_class(size_t bytes) {
+        if (bytes > (size_t(1) << 60)) return bytes;  // no such allocation succeeds; keeps the loop below finite
+        for (size_t s = 256;; s *= 2)
+            for (size_t j = 0; j < 4; j++)
+                if (s / 4 * (4 + j) >= bytes) return s / 4 * (4 + j);
+    }
+    std::map<size_t, std::vector<void*>> idle_;
+    std::unordered_map<void*, size_t> size_of_;
+};
+
+struct Run {
+    const lsm_entry_t* entries = nullptr;
+    uint64_t n = 0;
+    bool owned = false;      // entries came from the pool
+    bool transient = false;  // entries belong to the caller of a flush: copied if the run comes to rest
+    uint8_t* fences = nullptr;
+    void* bloom = nullptr;
+    uint64_t n_blocks = 0;
+    void* index = nullptr;
+    uint64_t n_buckets = 0;
+};
+
+struct Level {
+    std::vector<Run> runs;  // newest first
+    uint32_t T, K;
+};
+
+struct Batch {
+    uint64_t writes, hits, empties;
+    double blocks;
+};
+
+uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+}  // namespace
+
+struct lsm_driver {
+    lsm_driver_config_t cfg;
+    hipStream_t stream = nullptr;
+    double p = 1.0;
+    uint32_t T = 0, K = 0;  // what the controller asks for now
+    std::vector<Level> levels;
+    std::vector<lsm_driver_event_t> log;
+    std::deque<Batch> window;
+    Batch sum{0, 0, 0, 0.0};
+    bool searched = false;
+    double last_mix[4] = {0, 0, 0, 0};
+    DevicePool pool;
+    void* workspace = nullptr;
+    size_t workspace_bytes = 0;
+    uint64_t* n_host = nullptr;  // pinned: the kernels write a compaction's count here
+    uint32_t* hit_host = nullptr;  // pinned copy of a probe batch's hit_len
+    size_t hit_host_count = 0;
+
+    void record(uint32_t kind, uint32_t level, uint32_t a, uint32_t b, uint64_t n_in, uint64_t n_out) {
+        lsm_driver_event_t e;
+        std::memset(&e, 0, sizeof(e));
+        e.kind = kind, e.level = level, e.a = a, e.b = b, e.n_in = n_in, e.n_out = n_out;
+        log.push_back(e);
+    }
+
+    void drop(Run& r) {
+        if (r.owned) pool.give(r.entries);
+        pool.give(r.fences);
+        pool.give(r.bloom);
+        pool.give(r.index);
+        r = Run();
+    }
+
+    void ensure_level(uint32_t level) {  // 0-based
+        while (levels.size() <= level) levels.push_back(Level{{}, T, K});
+    }
+
+    uint64_t total_entries() const {
+        uint64_t n = 0;
+        for (const Level& lv : levels)
+            for (const Run& r : lv.runs) n += r.n;
+        return n;
+    }
+
+    // M * T^(level + 1), saturating
+    uint64_t capacity(uint32_t level) const {
+        unsigned __int128 c = cfg.buffer_entries;
+        for (uint32_t i = 0; i <= level; i++) {
+            c *= levels[level].T;
+            if (c > UINT64_MAX) return UINT64_MAX;
+        }
+        return (uint64_t)c;
+    }
+
+    int wait() { return hipStreamSynchronize(stream) == hipSuccess ? LSM_OK : LSM_ERR_HIP; }
+
+    // Filter and hash index of a run that has come to rest; the keys are hashed once for both.
+    int build_lookup(Run& r) {
+        const bool indexed = cfg.hash_index_from != 0 && r.n >= cfg.hash_index_from && r.n <= (1ull << 27);
+        const lsm_run_t run{r.entries, r.n};
+        uint64_t* hashes = nullptr;
+        int rc = LSM_OK;
+        if (indexed) {
+            hashes = static_cast<uint64_t*>(pool.take(r.n * 8));
+            if (hashes == nullptr) return LSM_ERR_HIP;
+            rc = lsm_hash_keys(&run, hashes, stream);
+        }
+        if (rc == LSM_OK && cfg.bloom_bits != 0) {
+            r.n_blocks = lsm_bloom_blocks(r.n, cfg.bloom_bits);
+            if (r.n_blocks != 0) {
+                r.bloom = pool.take(r.n_blocks * 16);
+                if (r.bloom == nullptr) rc = LSM_ERR_HIP;
+                // a long run: the filter is built from the hashes, sorted by block range (no atomic traffic on the filter)
+                const size_t ws_bytes = (hashes != nullptr || r.n >= (1ull << 20)) ? lsm_bloom_workspace_bytes(r.n, r.n_blocks) : 0;
+                if (rc == LSM_OK && ws_bytes != 0) {
+                    if (hashes == nullptr) {
+                        hashes = static_cast<uint64_t*>(pool.take(r.n * 8));
+                        rc = hashes == nullptr ? (int)LSM_ERR_HIP : lsm_hash_keys(&run, hashes, stream);
+                    }
+                    void* ws = rc == LSM_OK ? pool.take(ws_bytes) : nullptr;
+                    if (rc == LSM_OK) rc = ws == nullptr ? (int)LSM_ERR_HIP : lsm_build_bloom_hashed(hashes, r.n, r.bloom, r.n_blocks, ws, ws_bytes, stream);
+                    pool.give(ws);
+                } else if (rc == LSM_OK) {
+                    rc = lsm_build_bloom(&run, r.bloom, r.n_blocks, stream);
+                }
+            }
+        }
+        if (rc == LSM_OK && indexed) {
+            r.n_buckets = lsm_hash_index_buckets(r.n);
+            const size_t ws_bytes = lsm_hash_index_workspace_bytes(r.n);
+            r.index = pool.take(r.n_buckets * 64);
+            void* ws = pool.take(ws_bytes);
+            rc = (r.index == nullptr || ws == nullptr) ? (int)LSM_ERR_HIP : lsm_build_hash_index(hashes, r.n, r.index, ws, ws_bytes, stream);
+            pool.give(ws);
+        }
+        pool.give(hashes);
+        return rc;
+    }
+
+    // A run that comes to rest in a level gets whatever lookup structure it still lacks.  (Runs that are merged away at
+    // once - a flushed run arriving at a full level, a run moved down onto another - never get any.)
+    int settle(Run& r) {
+        if (r.n == 0) return LSM_OK;
+        if (r.transient) {
+            void* copy = pool.take(r.n * sizeof(lsm_entry_t));
+            if (copy == nullptr) return LSM_ERR_HIP;
+            if (hipMemcpyAsync(copy, r.entries, r.n * sizeof(lsm_entry_t), hipMemcpyDeviceToDevice, stream) != hipSuccess) return LSM_ERR_HIP;
+            r.entries = static_cast<const lsm_entry_t*>(copy);
+            r.owned = true, r.transient = false;
+        }
+        if (r.fences == nullptr) {
+            r.fences = static_cast<uint8_t*>(pool.take(ceil_div(r.n, cfg.fence_stride) * LSM_KEY_BYTES));
+            if (r.fences == nullptr) return LSM_ERR_HIP;
+            const lsm_run_t run{r.entries, r.n};
+            const int rc = lsm_build_fences(&run, cfg.fence_stride, r.fences, stream);
+            if (rc != LSM_OK) return rc;
+        }
+        if (r.bloom == nullptr && r.index == nullptr) return build_lookup(r);
+        return LSM_OK;
+    }
+
+    // All runs of a level into one; the fence index of the output is written in the same pass.  Waits for the count.
+    int compact(const std::vector<Run>& in, uint32_t flags, uint32_t level, Run* merged) {
+        if (in.size() > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+        lsm_run_t runs[LSM_MAX_RUNS];
+        uint64_t lens[LSM_MAX_RUNS];
+        uint64_t total = 0;
+        for (size_t j = 0; j < in.size(); j++) {
+            runs[j] = lsm_run_t{in[j].entries, in[j].n};
+            lens[j] = in[j].n;
+            total += in[j].n;
+        }
+        const uint32_t k = (uint32_t)in.size();
+        const size_t need = lsm_compact_workspace_bytes(lens, k);
+        if (need > workspace_bytes) {
+            pool.give(workspace);
+            workspace_bytes = 2 * need;
+            workspace = pool.take(workspace_bytes);
+            if (workspace == nullptr) {
+                workspace_bytes = 0;
+                return LSM_ERR_HIP;
+            }
+        }
+        const uint64_t room = total > 0 ? total : 1;
+        lsm_entry_t* entries = static_cast<lsm_entry_t*>(pool.take(room * sizeof(lsm_entry_t)));
+        uint8_t* fences = static_cast<uint8_t*>(pool.take(ceil_div(room, cfg.fence_stride) * LSM_KEY_BYTES));
+        if (entries == nullptr || fences == nullptr) return LSM_ERR_HIP;
+        const lsm_out_t out{entries, room, n_host, fences, cfg.fence_stride, nullptr};
+        int rc = lsm_compact(runs, k, flags, &out, workspace, workspace_bytes, stream);
+        if (rc == LSM_OK) rc = wait();
+        if (rc == LSM_OK && *n_host > room) rc = LSM_ERR_INTERNAL;  // the device-side failure mark, or nonsense
+        if (rc != LSM_OK) {
+            pool.give(entries);
+            pool.give(fences);
+            return rc;
+        }
+        *merged = Run();
+        merged->n = *n_host;
+        if (cfg.observer != nullptr) cfg.observer(cfg.observer_ctx, level + 1, entries, merged->n);
+        if (merged->n == 0) {
+            pool.give(entries);
+            pool.give(fences);
+        } else {
+            merged->entries = entries, merged->owned = true, merged->fences = fences;
+        }
+        return LSM_OK;
+    }
+
+    // A run arrives at a level (0-based); the compactions and moves this triggers are done one after the other.
+    int arrive(uint32_t level, Run moving) {
+        for (;;) {
+            ensure_level(level);
+            Level& lv = levels[level];
+            if (lv.T != T || lv.K != K) record(LSM_EV_ADOPT, level + 1, T, K, 0, 0);
+            lv.T = T, lv.K = K;  // lazy transition: the level takes the current parameters when data flows into it
+            lv.runs.insert(lv.runs.begin(), moving);
+            if (lv.runs.size() <= lv.K) return settle(lv.runs[0]);
+            bool deeper_empty = true;
+            for (size_t i = level + 1; i < levels.size(); i++) deeper_empty = deeper_empty && levels[i].runs.empty();
+            const uint32_t flags = deeper_empty ? (uint32_t)LSM_BOTTOMMOST : 0u;
+            uint64_t n_in = 0;
+            for (const Run& r : lv.runs) n_in += r.n;
+            Run merged;
+            const int rc = compact(lv.runs, flags, level, &merged);
+            if (rc != LSM_OK) return rc;
+            record(LSM_EV_COMPACT, level + 1, (uint32_t)lv.runs.size(), flags, n_in, merged.n);
+            for (Run& r : lv.runs) drop(r);
+            lv.runs.clear();
+            if (merged.n > capacity(level)) {
+                record(LSM_EV_MOVE, level + 1, level + 2, 0, 0, merged.n);
+                moving = merged;
+                level++;
+                continue;
+            }
+            if (merged.n > 0) {
+                lv.runs.push_back(merged);
+                return settle(lv.runs[0]);
+            }
+            return LSM_OK;
+        }
+    }
+
+    // One batch of operation counts enters the window; the (T, K) search is re-run when the mix has moved.
+    int count(uint64_t writes, uint64_t hits, uint64_t empties, double blocks) {
+        window.push_back(Batch{writes, hits, empties, blocks});
+        sum.writes += writes, sum.hits += hits, sum.empties += empties, sum.blocks += blocks;
+        // slide: drop the oldest batches while the rest still covers window_ops operations
+        while (window.size() > 1) {
+            const Batch& f = window.front();
+            if (sum.writes + sum.hits + sum.empties - (f.writes + f.hits + f.empties) < cfg.window_ops) break;
+            sum.writes -= f.writes, sum.hits -= f.hits, sum.empties -= f.empties, sum.blocks -= f.blocks;
+            window.pop_front();
+        }
+        const uint64_t total = sum.writes + sum.hits + sum.empties;
+        if (total < cfg.window_ops) return LSM_OK;  // the window is not full yet
+        const double mix[4] = {(double)sum.writes / (double)total, (double)sum.hits / (double)total / 2, (double)sum.hits / (double)total / 2,
+                               (double)sum.empties / (double)total};  // w, s, r, z
+        const double d = sum.hits ? sum.blocks / (double)sum.hits : 0.0;
+        if (searched) {
+            double moved = 0.0;
+            for (int i = 0; i < 4; i++) moved += mix[i] > last_mix[i] ? mix[i] - last_mix[i] : last_mix[i] - mix[i];
+            if (moved <= cfg.shift_threshold) return LSM_OK;
+        }
+        std::memcpy(last_mix, mix, sizeof(mix));
+        searched = true;
+        const uint64_t n = total_entries();
+        const lsm_policy_input_t in{mix[0], mix[1], mix[2], mix[3], n > 0 ? n : 1, cfg.buffer_entries, cfg.page_entries, p, d};
+        uint32_t best_T = 0, best_K = 0;
+        const int rc = lsm_policy_choose(&in, cfg.t_min, cfg.t_max, &best_T, &best_K);
+        if (rc != LSM_OK) return rc;
+        lsm_driver_event_t e;
+        std::memset(&e, 0, sizeof(e));
+        e.kind = LSM_EV_POLICY, e.a = best_T, e.b = best_K, e.d = d;
+        std::memcpy(e.mix, mix, sizeof(mix));
+        log.push_back(e);
+        T = best_T, K = best_K;
+        return LSM_OK;
+    }
+
+    uint32_t tree(lsm_tree_run_t* out, uint32_t capacity) const {
+        uint32_t n = 0;
+        for (size_t l = 0; l < levels.size(); l++)
+            for (const Run& r : levels[l].runs) {
+                if (n < capacity) {
+                    lsm_tree_run_t t;
+                    std::memset(&t, 0, sizeof(t));
+                    t.run = lsm_run_t{r.entries, r.n};
+                    t.fence = lsm_fence_t{r.fences, r.fences ? ceil_div(r.n, cfg.fence_stride) : 0, cfg.fence_stride};
+                    t.bloom = lsm_bloom_t{r.bloom, r.bloom ? r.n_blocks : 0};
+                    t.level = (uint32_t)l + 1;
+                    t.index = lsm_hash_index_t{r.index, r.index ? r.n_buckets : 0};
+                    out[n] = t;
+                }
+                n++;
+            }
+        return n;
+    }
+};
+
+extern "C" int lsm_driver_create(const lsm_driver_config_t* config, void* stream, lsm_driver_t** driver_out) {
+    if (config == nullptr || driver_out == nullptr) return LSM_ERR_NULL;
+    *driver_out = nullptr;
+    if (config->buffer_entries == 0 || config->size_ratio < 2 || config->runs_per_level == 0 || config->window_ops == 0 ||
+        config->t_min < 2 || config->t_max < config->t_min || !(config->page_entries > 0) || config->fence_stride == 0)
+        return LSM_ERR_BAD_ARG;
+    lsm_driver* d = new (std::nothrow) lsm_driver();
+    if (d == nullptr) return LSM_ERR_HIP;
+    d->cfg = *config;
+    d->stream = static_cast<hipStream_t>(stream);
+    d->p = config->filter_fpr < 0 ? lsm_policy_filter_fpr(config->bloom_bits) : config->filter_fpr;
+    d->T = config->size_ratio, d->K = config->runs_per_level;
+    if (hipHostMalloc(reinterpret_cast<void**>(&d->n_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
+        delete d;
+        return LSM_ERR_HIP;
+    }
+    *driver_out = d;
+    return LSM_OK;
+}
+
+extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
+    if (d == nullptr) return;
+    (void)hipStreamSynchronize(d->stream);
+    d->pool.free_all();
+    if (d->n_host != nullptr) (void)hipHostFree(d->n_host);
+    if (d->hit_host != nullptr) (void)hipHostFree(d->hit_host);
+    delete d;
+}
+
+extern "C" int lsm_driver_load_run(lsm_driver_t* d, uint32_t level, const lsm_entry_t* entries, uint64_t n) {
+    if (d == nullptr || (n > 0 && entries == nullptr)) return LSM_ERR_NULL;
+    if (level == 0 || level > 64 || (reinterpret_cast<uintptr_t>(entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+    d->ensure_level(level - 1);
+    Run r;
+    r.entries = entries, r.n = n;
+    std::vector<Run>& runs = d->levels[level - 1].runs;
+    runs.push_back(r);
+    return d->settle(runs.back());
+}
+
+extern "C" int lsm_driver_note_writes(lsm_driver_t* d, uint64_t n_ops) {
+    if (d == nullptr) return LSM_ERR_NULL;
+    return d->count(n_ops, 0, 0, 0.0);
+}
+
+extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_t n) {
+    if (d == nullptr || (n > 0 && run == nullptr)) return LSM_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(run) & 63) != 0) return LSM_ERR_BAD_ARG;
+    Run r;
+    if (n > 0) r.entries = run, r.n = n, r.transient = true;
+    return d->arrive(0, r);
+}
+
+extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buffer, uint64_t n) {
+    if (d == nullptr || (n > 0 && buffer == nullptr)) return LSM_ERR_NULL;
+    if (n > LSM_MAX_BUFFER) return LSM_ERR_BAD_ARG;
+    const uint64_t room = n > 0 ? n : 1;
+    const size_t ws_bytes = lsm_flush_workspace_bytes(n);
+    lsm_entry_t* sorted = static_cast<lsm_entry_t*>(d->pool.take(room * sizeof(lsm_entry_t)));
+    void* ws = d->pool.take(ws_bytes > 0 ? ws_bytes : 4);
+    uint64_t* n_dev = static_cast<uint64_t*>(d->pool.take(sizeof(uint64_t)));  // the kernels count with atomics: device memory
+    int rc = (sorted == nullptr || ws == nullptr || n_dev == nullptr) ? (int)LSM_ERR_HIP : (int)LSM_OK;
+    if (rc == LSM_OK) {
+        const lsm_out_t out{sorted, room, n_dev, nullptr, 0, nullptr};
+        rc = lsm_flush_buffer(buffer, n, &out, ws, ws_bytes > 0 ? ws_bytes : 4, d->stream);
+    }
+    if (rc == LSM_OK && hipMemcpyAsync(d->n_host, n_dev, sizeof(uint64_t), hipMemcpyDeviceToHost, d->stream) != hipSuccess) rc = LSM_ERR_HIP;
+    if (rc == LSM_OK) rc = d->wait();
+    d->pool.give(ws);
+    d->pool.give(n_dev);
+    if (rc == LSM_OK && *d->n_host > room) rc = LSM_ERR_INTERNAL;
+    if (rc != LSM_OK) {
+        d->pool.give(sorted);
+        return rc;
+    }
+    Run r;
+    r.entries = sorted, r.n = *d->n_host, r.owned = true;
+    return d->arrive(0, r);
+}
+
+extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, const lsm_hits_t* out_hits) {
+    if (d == nullptr || queries == nullptr || out_hits == nullptr) return LSM_ERR_NULL;
+    lsm_tree_run_t runs[LSM_MAX_RUNS];
+    const uint32_t n_runs = d->tree(runs, LSM_MAX_RUNS);
+    if (n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
+    for (uint32_t i = 0; i < n_runs; i++) runs[i].level = i;
+    const lsm_tree_t tree{runs, n_runs};
+    int rc = lsm_probe(queries, &tree, out_hits, d->stream);
+    if (rc != LSM_OK) return rc;
+    const uint32_t n_req = queries->n_req;
+    if (n_req > d->hit_host_count) {
+        if (d->hit_host != nullptr) (void)hipHostFree(d->hit_host);
+        d->hit_host = nullptr, d->hit_host_count = 0;
+        if (hipHostMalloc(reinterpret_cast<void**>(&d->hit_host), (size_t)n_req * sizeof(uint32_t), hipHostMallocDefault) != hipSuccess) return LSM_ERR_HIP;
+        d->hit_host_count = n_req;
+    }
+    if (n_req > 0 && hipMemcpyAsync(d->hit_host, out_hits->hit_len, (size_t)n_req * sizeof(uint32_t), hipMemcpyDeviceToHost, d->stream) != hipSuccess)
+        return LSM_ERR_HIP;
+    rc = d->wait();
+    if (rc != LSM_OK) return rc;
+    uint64_t hits = 0, blocks = 0;
+    for (uint32_t i = 0; i < n_req; i++) {
+        hits += d->hit_host[i] > 0;
+        blocks += d->hit_host[i];
+    }
+    d->record(LSM_EV_PROBE, 0, n_req, (uint32_t)hits, 0, blocks);
+    return d->count(0, hits, n_req - hits, (double)blocks);
+}
+
+extern "C" uint32_t lsm_driver_levels(const lsm_driver_t* d) { return d ? (uint32_t)d->levels.size() : 0; }
+
+extern "C" int lsm_driver_level(const lsm_driver_t* d, uint32_t level, uint32_t* T, uint32_t* K, uint32_t* n_runs) {
+    if (d == nullptr) return LSM_ERR_NULL;
+    if (level == 0 || level > d->levels.size()) return LSM_ERR_BAD_ARG;
+    const Level& lv = d->levels[level - 1];
+    if (T) *T = lv.T;
+    if (K) *K = lv.K;
+    if (n_runs) *n_runs = (uint32_t)lv.runs.size();
+    return LSM_OK;
+}
+
+extern "C" int lsm_driver_tree(const lsm_driver_t* d, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs) {
+    if (d == nullptr || n_runs == nullptr || (capacity > 0 && runs_out == nullptr)) return LSM_ERR_NULL;
+    *n_runs = d->tree(runs_out, capacity);
+    return LSM_OK;
+}
+
+extern "C" int lsm_driver_target(const lsm_driver_t* d, uint32_t* T, uint32_t* K) {
+    if (d == nullptr) return LSM_ERR_NULL;
+    if (T) *T = d->T;
+    if (K) *K = d->K;
+    return LSM_OK;
+}
+
+extern "C" uint64_t lsm_driver_log(const lsm_driver_t* d, uint64_t first, lsm_driver_event_t* out, uint64_t capacity) {
+    if (d == nullptr) return 0;
+    const uint64_t n = d->log.size();
+    for (uint64_t i = first; out != nullptr && i < n && i - first < capacity; i++) out[i - first] = d->log[i];
+    return n;
+}
+
+extern "C" int lsm_driver_read(lsm_driver_t* d, const void* device_src, void* dst, size_t bytes) {
+    if (d == nullptr || (bytes > 0 && (device_src == nullptr || dst == nullptr))) return LSM_ERR_NULL;
+    if (bytes > 0 && hipMemcpyAsync(dst, device_src, bytes, hipMemcpyDefault, d->stream) != hipSuccess) return LSM_ERR_HIP;
+    return d->wait();
+}

@@ -39,6 +39,28 @@ def test_struct_sizes_match_the_header():
     assert C.sizeof(B._Run) == 16 and C.sizeof(B._Out) == 48 and C.sizeof(B._Fence) == 24
     assert C.sizeof(B._Bloom) == 16 and C.sizeof(B._TreeRun) == 80 and C.sizeof(B._Queries) == 24 and C.sizeof(B._Hits) == 16
     assert C.sizeof(B._PolicyInput) == 72
+    assert C.sizeof(B._DriverEvent) == 72 and C.sizeof(B._DriverConfig) == 88
+
+
+def test_driver_arguments_are_checked_before_anything_is_allocated(lib):
+    import paper_2511_16138_amd.binding as B
+    handle = C.c_void_p(123)
+    good = dict(buffer_entries=3600, size_ratio=10, runs_per_level=1, window_ops=4096, shift_threshold=0.2, t_min=2, t_max=16,
+                page_entries=64.0, filter_fpr=-1.0, fence_stride=64, bloom_bits=16, hash_index_from=0)
+    assert lib.lsm_driver_create(None, None, C.byref(handle)) == -1
+    assert lib.lsm_driver_create(C.byref(B._DriverConfig(**good)), None, None) == -1
+    for field, bad in [("buffer_entries", 0), ("size_ratio", 1), ("runs_per_level", 0), ("window_ops", 0), ("t_min", 1),
+                       ("t_max", 1), ("page_entries", 0.0), ("fence_stride", 0)]:
+        cfg = B._DriverConfig(**{**good, field: bad})
+        assert lib.lsm_driver_create(C.byref(cfg), None, C.byref(handle)) == -2, field
+        assert handle.value is None                       # no driver comes back with an error
+    for call, args in [(lib.lsm_driver_note_writes, (None, 1)), (lib.lsm_driver_flush, (None, None, 0)),
+                       (lib.lsm_driver_flush_unsorted, (None, None, 0)), (lib.lsm_driver_probe, (None, None, None)),
+                       (lib.lsm_driver_load_run, (None, 1, None, 0)), (lib.lsm_driver_target, (None, None, None)),
+                       (lib.lsm_driver_level, (None, 1, None, None, None)), (lib.lsm_driver_read, (None, None, None, 0))]:
+        assert call(*args) == -1
+    assert lib.lsm_driver_levels(None) == 0 and lib.lsm_driver_log(None, 0, None, 0) == 0
+    lib.lsm_driver_destroy(None)                          # allowed
 
 
 def test_argument_errors_are_reported_before_any_launch(lib):
