@@ -105,7 +105,8 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
 def test_config5_full_mixed_trace_on_400m_tree(oracle):
     """The mixed, shifting workload at its stated size: 6 levels, 400M entries, three phases of 2^18 operations with
     read shares 90 / 50 / 10 %, Bloom filters of 16 bits per key, (T, K) searched over T in 2..16.  Compared with the
-    plain driver on the CPU checker: every compaction output byte for byte, every probe batch, every log record."""
+    plain driver on the CPU checker: every compaction output byte for byte, every probe batch, every log record - for the
+    Python driver over the single entry points and for the library's own driver (lsm_driver_*), stepped side by side."""
     from test_gpu_mixed import replay_both
     from workloads import lsm
     print("config5 full: generating", flush=True)
@@ -117,7 +118,7 @@ def test_config5_full_mixed_trace_on_400m_tree(oracle):
     n_batches = sum(1 for e in tr.events if e[0] == "probe")
     print(f"  tree {sizes}, {n_flush} flushes, {n_batches} probe batches ({time.time() - t0:.0f} s)", flush=True)
     assert n_flush > 4000 and n_batches >= 90
-    gpu, n_probe = replay_both(oracle, tr, 16, (2, 16), 16,
+    gpu, n_probe = replay_both(oracle, tr, 16, (2, 16), 16, native=True,
                                progress=lambda msg: print(f"  {msg} ({time.time() - t0:.0f} s)", flush=True))
     assert n_probe == n_batches
     comp = [e for e in gpu.trace if e[0] == "compact"]

@@ -11,9 +11,10 @@ from gpu_util import dev
 pytestmark = pytest.mark.gpu
 
 
-def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, progress=None, hash_index_from=0):
+def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, progress=None, hash_index_from=0, native=False):
     """Run the trace through both drivers in step: every compaction output and every probe batch is compared as it is
-    produced (so that no more than one of each is alive at a time), the logs after every event."""
+    produced (so that no more than one of each is alive at a time), the logs after every event.  native: the library's own
+    driver (lsm_driver_*) is stepped along as a third participant and compared with the plain driver in the same way."""
     from gpu_util import oracle_probe_threads
     from oracle import lsm_driver_oracle as drv
     from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
@@ -31,37 +32,62 @@ def replay_both(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, pr
     cpu = drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=t_grid,
                            page_entries=64.0, fpr=drv.bloom_fpr(bloom_bits), on_compact=cpu_out.append,
                            probe_fn=lambda q, nb, runs: oracle_probe_threads(oracle, q, nb, runs))
+    nat, nat_out = None, []
+    if native:
+        from paper_2511_16138_amd import LsmDriver
+        nat = LsmDriver(tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=t_grid, bloom_bits=bloom_bits,
+                        hash_index_from=hash_index_from, on_compaction=lambda level, out: nat_out.append(out))
     for level, r in enumerate(tr.workload.runs):
         gpu.load_level(level, [r])
         cpu.install(level + 1, [r.cpu()])
+        if nat:
+            nat.load_run(level + 1, r)
     n_probe = 0
     for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
         if n_writes:
             gpu.note_writes(n_writes)
             cpu.writes(n_writes)
+            if nat:
+                nat.note_writes(n_writes)
         if kind == "flush":
             run = tr.flush_runs[i]
             if shuffle is not None:   # the GPU side gets the write buffer in the order it was "written" and sorts it itself
                 gpu.flush_unsorted(run[shuffle(i, int(run.shape[0]))])
             else:
                 gpu.flush(run)
+            if nat:
+                nat.flush_unsorted(run[shuffle(i, int(run.shape[0]))].contiguous()) if shuffle is not None else nat.flush(run)
             cpu.flush(run.cpu())
-            assert len(gpu_out) == len(cpu_out)
+            assert len(gpu_out) == len(cpu_out) and (nat is None or len(nat_out) == len(cpu_out))
             for got, want in zip(gpu_out, cpu_out):   # every compaction of this flush, byte for byte
                 assert np.array_equal(oracle.as_run(got), want), f"flush {i}: a compaction output differs"
+            for got, want in zip(nat_out, cpu_out):
+                assert np.array_equal(oracle.as_run(got), want), f"flush {i}: a compaction output of the library's driver differs"
             gpu_out.clear()
             cpu_out.clear()
+            nat_out.clear()
         else:
             q, nb = tr.probe_batch(i)
             ghl, ghits = gpu.probe(q, nb)
             chl, chits = cpu.probe(q.cpu(), nb.cpu())
             assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl), f"probe batch {i}: hit_len"
             assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits), f"probe batch {i}"
+            if nat:
+                nhl, nhits = nat.probe(q, nb)
+                assert np.array_equal(nhl.cpu().numpy().astype(np.uint32), chl), f"probe batch {i}: hit_len (library's driver)"
+                assert np.array_equal(nhits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits), f"probe batch {i} (library's driver)"
             n_probe += 1
             if progress:
                 progress(f"probe batch {i} ok, {len(gpu.trace)} log records")
         assert len(gpu.trace) == len(cpu.log) and gpu.trace[-1:] == cpu.log[-1:], (kind, i, gpu.trace[-3:], cpu.log[-3:])
+        if nat:
+            log = nat.trace
+            assert len(log) == len(cpu.log) and log[-1:] == cpu.log[-1:], (kind, i, log[-3:], cpu.log[-3:])
     assert gpu.trace == cpu.log
+    if nat:
+        assert nat.trace == cpu.log
+        check_native_tree(oracle, nat, cpu, bloom_bits, hash_index_from)
+        nat.close()
     assert [len(lv) for lv in gpu.levels] == [len(lv.runs) for lv in cpu.levels]
     for glv, clv in zip(gpu.levels, cpu.levels):
         for gr, cr in zip(glv, clv.runs):
@@ -102,6 +128,33 @@ def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries,
         assert any(e[0] == "compact" and e[2] > 2 for e in gpu.trace)   # several runs of a level merged at once
     if t_grid[0] != t_grid[1]:
         assert len({t for t, _ in pol}) > 1 or pol[0][0] != tr.size_ratio, pol   # the size ratio moves as well
+
+
+def check_native_tree(oracle, gpu, cpu, bloom_bits, hash_index_from):
+    """The tree of the library's driver against the plain driver's: levels, parameters, every run with its fence index,
+    filter and hash index."""
+    assert gpu.levels() == [(lv.T, lv.K, len(lv.runs)) for lv in cpu.levels]
+    assert gpu.target() == (cpu.target_T, cpu.target_K)
+    want_runs = [(li + 1, r) for li, lv in enumerate(cpu.levels) for r in lv.runs]
+    tree = gpu.tree()
+    assert len(tree) == len(want_runs)
+    for t, (level, cr) in zip(tree, want_runs):
+        n = int(cr.shape[0])
+        assert (t.level, t.run.n) == (level, n)
+        assert np.array_equal(oracle.as_run(gpu.read(t.run.entries, n, 8)), cr)
+        assert (t.fence.n, t.fence.stride) == ((n + 63) // 64, 64)
+        assert np.array_equal(gpu.read(t.fence.keys, t.fence.n, 4).cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
+        if bloom_bits:
+            assert t.bloom.n_blocks == (n * bloom_bits + 127) // 128
+            assert np.array_equal(gpu.read(t.bloom.blocks, t.bloom.n_blocks, 4, torch.int32).cpu().numpy().view(np.uint8).reshape(-1, 16),
+                                  oracle.build_bloom(cr, int(t.bloom.n_blocks)))
+        else:
+            assert not t.bloom.blocks
+        if hash_index_from and n >= hash_index_from:
+            assert t.index.n_buckets == oracle.hash_index_buckets(n)
+            assert oracle.hash_index_check(cr, gpu.read(t.index.buckets, t.index.n_buckets, 8).cpu().numpy()) == 0
+        else:
+            assert not t.index.buckets
 
 
 def replay_native(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, hash_index_from=0):
@@ -148,28 +201,7 @@ def replay_native(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, 
         log = gpu.trace
         assert len(log) == len(cpu.log) and log[-1:] == cpu.log[-1:], (kind, i, log[-3:], cpu.log[-3:])
     assert gpu.trace == cpu.log
-    assert gpu.levels() == [(lv.T, lv.K, len(lv.runs)) for lv in cpu.levels]
-    assert gpu.target() == (cpu.target_T, cpu.target_K)
-    want_runs = [(li + 1, r) for li, lv in enumerate(cpu.levels) for r in lv.runs]
-    tree = gpu.tree()
-    assert len(tree) == len(want_runs)
-    for t, (level, cr) in zip(tree, want_runs):
-        n = int(cr.shape[0])
-        assert (t.level, t.run.n) == (level, n)
-        assert np.array_equal(oracle.as_run(gpu.read(t.run.entries, n, 8)), cr)
-        assert (t.fence.n, t.fence.stride) == ((n + 63) // 64, 64)
-        assert np.array_equal(gpu.read(t.fence.keys, t.fence.n, 4).cpu().numpy().view(np.uint8).reshape(-1, 32), oracle.build_fences(cr, 64))
-        if bloom_bits:
-            assert t.bloom.n_blocks == (n * bloom_bits + 127) // 128
-            assert np.array_equal(gpu.read(t.bloom.blocks, t.bloom.n_blocks, 4, torch.int32).cpu().numpy().view(np.uint8).reshape(-1, 16),
-                                  oracle.build_bloom(cr, int(t.bloom.n_blocks)))
-        else:
-            assert not t.bloom.blocks
-        if hash_index_from and n >= hash_index_from:
-            assert t.index.n_buckets == oracle.hash_index_buckets(n)
-            assert oracle.hash_index_check(cr, gpu.read(t.index.buckets, t.index.n_buckets, 8).cpu().numpy()) == 0
-        else:
-            assert not t.index.buckets
+    check_native_tree(oracle, gpu, cpu, bloom_bits, hash_index_from)
     log = list(gpu.trace)
     gpu.close()
     return log, n_probe
