@@ -477,8 +477,9 @@ double lsm_policy_filter_fpr(uint32_t bits_per_key);
  * adaptive controller (section 3.3: operation counts over a sliding window, a new (T, K) search when the mix has
  * moved by more than a threshold) and the lazy transition (appendix C: a level takes the current T and K when data
  * next flows into it; a smaller K merges the level at that arrival, a larger K leaves it alone).  It sequences the
- * calls above on one stream and owns the device memory of the runs it creates (a pool that is given back only by
- * lsm_driver_destroy).  One thread at a time per driver.  Every call returns an lsm_status; after an error other
+ * calls above on the caller's stream (the lookup structures of a run that has come to rest are built on a second
+ * stream of the driver's own, beside the next compaction; lookups and inspection wait for them) and owns the device
+ * memory of the runs it creates (a pool that is given back only by lsm_driver_destroy).  One thread at a time per driver.  Every call returns an lsm_status; after an error other
  * than LSM_ERR_NULL / LSM_ERR_BAD_ARG the driver's tree is undefined and it can only be destroyed.
  *
  * Readings where the paper gives no constants: an operation is one inserted sequence (lsm_driver_note_writes) or one
@@ -553,13 +554,13 @@ int lsm_driver_probe(lsm_driver_t* driver, const lsm_queries_t* queries, const l
 
 /* Inspection.  lsm_driver_levels: number of levels.  lsm_driver_level: the parameters level `level` (1-based) runs
  * with and its number of runs.  lsm_driver_tree: the runs newest -> oldest with their lookup structures (`level`
- * field = 1-based level), at most `capacity` of them, *n_runs = how many there are; the DEVICE pointers stay valid
- * until the next flush.  lsm_driver_target: the (T, K) the controller currently asks for.  lsm_driver_log: copies
+ * field = 1-based level), at most `capacity` of them, *n_runs = how many there are; the call waits until the
+ * structures are built, and the DEVICE pointers stay valid until the next flush.  lsm_driver_target: the (T, K) the controller currently asks for.  lsm_driver_log: copies
  * records first .. first + capacity - 1 of the log and returns the total number of records.  lsm_driver_read: waits
  * for the stream and copies `bytes` bytes of driver-owned DEVICE memory to dst (HOST or DEVICE). */
 uint32_t lsm_driver_levels(const lsm_driver_t* driver);
 int lsm_driver_level(const lsm_driver_t* driver, uint32_t level, uint32_t* T, uint32_t* K, uint32_t* n_runs);
-int lsm_driver_tree(const lsm_driver_t* driver, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs);
+int lsm_driver_tree(lsm_driver_t* driver, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs);
 int lsm_driver_target(const lsm_driver_t* driver, uint32_t* T, uint32_t* K);
 uint64_t lsm_driver_log(const lsm_driver_t* driver, uint64_t first, lsm_driver_event_t* out, uint64_t capacity);
 int lsm_driver_read(lsm_driver_t* driver, const void* device_src, void* dst, size_t bytes);

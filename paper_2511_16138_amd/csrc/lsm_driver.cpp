@@ -3,11 +3,16 @@
 // 3.3 (operation counts over a sliding window, a new (T, K) search when the mix has moved by more than a threshold)
 // and the lazy transition of appendix C (a level takes the current T and K when a run next arrives at it).  Nothing
 // here touches entries: merging, fence indices, filters, hash indices, lookups and the cost model are the library's
-// own entry points, enqueued on one stream.
+// own entry points.  Merges, flushes and lookups are enqueued on the caller's stream; the lookup structures of a run
+// that has come to rest (fence index, filter, hash index) are built on a second stream of the driver's own, beside the
+// next compaction: a small merge and the filter of the run before it each keep the GPU busy for some 20 us on a few
+// compute units, and nothing but a lookup has to wait for the filter.
 //
 // Device memory of the runs the driver creates comes from a pool that keeps every block for reuse (hipMalloc and
 // hipFree cost more than a small compaction, and hipFree waits for the device).  A block that is given back may still
-// be read by work already enqueued; that is safe because its next user's work is enqueued later on the same stream.
+// be read by work already enqueued on the caller's stream; that is safe because its next user's work is enqueued later
+// on the same stream.  Memory that work on the second stream may still touch is given back only after that stream has
+// been waited for (finish_builds).
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -88,7 +93,11 @@ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 struct lsm_driver {
     lsm_driver_config_t cfg;
-    hipStream_t stream = nullptr;
+    hipStream_t stream = nullptr;  // the caller's
+    hipStream_t side = nullptr;    // builds of lookup structures
+    hipEvent_t ordered = nullptr;  // makes `side` wait for what `stream` has been given so far
+    bool builds_pending = false;
+    std::vector<void*> build_scratch;  // temporaries of builds in flight
     double p = 1.0;
     uint32_t T = 0, K = 0;  // what the controller asks for now
     std::vector<Level> levels;
@@ -142,14 +151,31 @@ struct lsm_driver {
 
     int wait() { return hipStreamSynchronize(stream) == hipSuccess ? LSM_OK : LSM_ERR_HIP; }
 
-    // Filter and hash index of a run that has come to rest; the keys are hashed once for both.
+    // Waits for the builds on the second stream.  Needed before a lookup uses the structures, and before any memory the
+    // builds read or write goes back to the pool.
+    int finish_builds() {
+        if (!builds_pending) return LSM_OK;
+        builds_pending = false;
+        const bool ok = hipStreamSynchronize(side) == hipSuccess;
+        for (void* p : build_scratch) pool.give(p);
+        build_scratch.clear();
+        return ok ? LSM_OK : LSM_ERR_HIP;
+    }
+
+    // Filter and hash index of a run that has come to rest; the keys are hashed once for both.  Second stream.
     int build_lookup(Run& r) {
+        hipStream_t stream = side;
+        auto scratch = [this](size_t bytes) {
+            void* p = pool.take(bytes);
+            if (p != nullptr) build_scratch.push_back(p);
+            return p;
+        };
         const bool indexed = cfg.hash_index_from != 0 && r.n >= cfg.hash_index_from && r.n <= (1ull << 27);
         const lsm_run_t run{r.entries, r.n};
         uint64_t* hashes = nullptr;
         int rc = LSM_OK;
         if (indexed) {
-            hashes = static_cast<uint64_t*>(pool.take(r.n * 8));
+            hashes = static_cast<uint64_t*>(scratch(r.n * 8));
             if (hashes == nullptr) return LSM_ERR_HIP;
             rc = lsm_hash_keys(&run, hashes, stream);
         }
@@ -162,12 +188,11 @@ struct lsm_driver {
                 const size_t ws_bytes = (hashes != nullptr || r.n >= (1ull << 20)) ? lsm_bloom_workspace_bytes(r.n, r.n_blocks) : 0;
                 if (rc == LSM_OK && ws_bytes != 0) {
                     if (hashes == nullptr) {
-                        hashes = static_cast<uint64_t*>(pool.take(r.n * 8));
+                        hashes = static_cast<uint64_t*>(scratch(r.n * 8));
                         rc = hashes == nullptr ? (int)LSM_ERR_HIP : lsm_hash_keys(&run, hashes, stream);
                     }
-                    void* ws = rc == LSM_OK ? pool.take(ws_bytes) : nullptr;
+                    void* ws = rc == LSM_OK ? scratch(ws_bytes) : nullptr;
                     if (rc == LSM_OK) rc = ws == nullptr ? (int)LSM_ERR_HIP : lsm_build_bloom_hashed(hashes, r.n, r.bloom, r.n_blocks, ws, ws_bytes, stream);
-                    pool.give(ws);
                 } else if (rc == LSM_OK) {
                     rc = lsm_build_bloom(&run, r.bloom, r.n_blocks, stream);
                 }
@@ -177,18 +202,20 @@ struct lsm_driver {
             r.n_buckets = lsm_hash_index_buckets(r.n);
             const size_t ws_bytes = lsm_hash_index_workspace_bytes(r.n);
             r.index = pool.take(r.n_buckets * 64);
-            void* ws = pool.take(ws_bytes);
+            void* ws = scratch(ws_bytes);
             rc = (r.index == nullptr || ws == nullptr) ? (int)LSM_ERR_HIP : lsm_build_hash_index(hashes, r.n, r.index, ws, ws_bytes, stream);
-            pool.give(ws);
         }
-        pool.give(hashes);
         return rc;
     }
 
     // A run that comes to rest in a level gets whatever lookup structure it still lacks.  (Runs that are merged away at
     // once - a flushed run arriving at a full level, a run moved down onto another - never get any.)
+    // The entries of a merged run are complete (its count has been waited for, and with it the caller's stream); those of
+    // a flushed or loaded run are whatever the caller's stream has been given so far, so the second stream is made to
+    // wait for that.
     int settle(Run& r) {
         if (r.n == 0) return LSM_OK;
+        const bool from_caller = r.transient || !r.owned;
         if (r.transient) {
             void* copy = pool.take(r.n * sizeof(lsm_entry_t));
             if (copy == nullptr) return LSM_ERR_HIP;
@@ -196,18 +223,22 @@ struct lsm_driver {
             r.entries = static_cast<const lsm_entry_t*>(copy);
             r.owned = true, r.transient = false;
         }
+        if (from_caller && (hipEventRecord(ordered, stream) != hipSuccess || hipStreamWaitEvent(side, ordered, 0) != hipSuccess)) return LSM_ERR_HIP;
+        builds_pending = true;
         if (r.fences == nullptr) {
             r.fences = static_cast<uint8_t*>(pool.take(ceil_div(r.n, cfg.fence_stride) * LSM_KEY_BYTES));
             if (r.fences == nullptr) return LSM_ERR_HIP;
             const lsm_run_t run{r.entries, r.n};
-            const int rc = lsm_build_fences(&run, cfg.fence_stride, r.fences, stream);
+            const int rc = lsm_build_fences(&run, cfg.fence_stride, r.fences, side);
             if (rc != LSM_OK) return rc;
         }
         if (r.bloom == nullptr && r.index == nullptr) return build_lookup(r);
         return LSM_OK;
     }
 
-    // All runs of a level into one; the fence index of the output is written in the same pass.  Waits for the count.
+    // All runs of a level into one; the fence index of the output is written in the same pass.  Waits for the count
+    // (the kernels store it to pinned host memory).  Watching that word from the host instead of synchronising the
+    // stream was measured and is no faster: the store becomes visible when the kernel ends.
     int compact(const std::vector<Run>& in, uint32_t flags, uint32_t level, Run* merged) {
         if (in.size() > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
         lsm_run_t runs[LSM_MAX_RUNS];
@@ -272,6 +303,8 @@ struct lsm_driver {
             const int rc = compact(lv.runs, flags, level, &merged);
             if (rc != LSM_OK) return rc;
             record(LSM_EV_COMPACT, level + 1, (uint32_t)lv.runs.size(), flags, n_in, merged.n);
+            const int built = finish_builds();  // a run that is merged away may still be read by the build of its own filter
+            if (built != LSM_OK) return built;
             for (Run& r : lv.runs) drop(r);
             lv.runs.clear();
             if (merged.n > capacity(level)) {
@@ -357,8 +390,10 @@ extern "C" int lsm_driver_create(const lsm_driver_config_t* config, void* stream
     d->stream = static_cast<hipStream_t>(stream);
     d->p = config->filter_fpr < 0 ? lsm_policy_filter_fpr(config->bloom_bits) : config->filter_fpr;
     d->T = config->size_ratio, d->K = config->runs_per_level;
-    if (hipHostMalloc(reinterpret_cast<void**>(&d->n_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess) {
-        delete d;
+    if (hipHostMalloc(reinterpret_cast<void**>(&d->n_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess ||
+        hipStreamCreateWithFlags(&d->side, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&d->ordered, hipEventDisableTiming) != hipSuccess) {
+        lsm_driver_destroy(d);
         return LSM_ERR_HIP;
     }
     *driver_out = d;
@@ -368,7 +403,10 @@ extern "C" int lsm_driver_create(const lsm_driver_config_t* config, void* stream
 extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
     if (d == nullptr) return;
     (void)hipStreamSynchronize(d->stream);
+    if (d->side != nullptr) (void)hipStreamSynchronize(d->side);
     d->pool.free_all();
+    if (d->side != nullptr) (void)hipStreamDestroy(d->side);
+    if (d->ordered != nullptr) (void)hipEventDestroy(d->ordered);
     if (d->n_host != nullptr) (void)hipHostFree(d->n_host);
     if (d->hit_host != nullptr) (void)hipHostFree(d->hit_host);
     delete d;
@@ -432,7 +470,8 @@ extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, c
     if (n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
     for (uint32_t i = 0; i < n_runs; i++) runs[i].level = i;
     const lsm_tree_t tree{runs, n_runs};
-    int rc = lsm_probe(queries, &tree, out_hits, d->stream);
+    int rc = d->finish_builds();
+    if (rc == LSM_OK) rc = lsm_probe(queries, &tree, out_hits, d->stream);
     if (rc != LSM_OK) return rc;
     const uint32_t n_req = queries->n_req;
     if (n_req > d->hit_host_count) {
@@ -466,10 +505,10 @@ extern "C" int lsm_driver_level(const lsm_driver_t* d, uint32_t level, uint32_t*
     return LSM_OK;
 }
 
-extern "C" int lsm_driver_tree(const lsm_driver_t* d, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs) {
+extern "C" int lsm_driver_tree(lsm_driver_t* d, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs) {
     if (d == nullptr || n_runs == nullptr || (capacity > 0 && runs_out == nullptr)) return LSM_ERR_NULL;
     *n_runs = d->tree(runs_out, capacity);
-    return LSM_OK;
+    return d->finish_builds();
 }
 
 extern "C" int lsm_driver_target(const lsm_driver_t* d, uint32_t* T, uint32_t* K) {
@@ -488,6 +527,8 @@ extern "C" uint64_t lsm_driver_log(const lsm_driver_t* d, uint64_t first, lsm_dr
 
 extern "C" int lsm_driver_read(lsm_driver_t* d, const void* device_src, void* dst, size_t bytes) {
     if (d == nullptr || (bytes > 0 && (device_src == nullptr || dst == nullptr))) return LSM_ERR_NULL;
+    const int rc = d->finish_builds();
+    if (rc != LSM_OK) return rc;
     if (bytes > 0 && hipMemcpyAsync(dst, device_src, bytes, hipMemcpyDefault, d->stream) != hipSuccess) return LSM_ERR_HIP;
     return d->wait();
 }
