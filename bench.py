@@ -345,15 +345,48 @@ def sharded_config5(g, lsm, torch, dev, n_shards: int, scale: int):
         comp = [e for t in trees for e in t.trace if e[0] == "compact"]
         return dt, len(comp), sum(e[3] for e in comp), [[r.n for r in lv] for lv in trees[0].levels]
 
+    def replay_library(batched: bool):
+        """The same rounds through the library's own driver: lsm_driver_flush per tree, or lsm_driver_flush_many per round."""
+        trees = [g.LsmDriver(tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=16 * tr.batch_requests, t_grid=(2, 16),
+                             bloom_bits=16) for tr in traces]
+        for tr, tree in zip(traces, trees):
+            for level, r in enumerate(tr.workload.runs):
+                tree.load_run(level + 1, r)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for f in range(rounds):
+            runs = [tr.flush_runs[f] if f < tr.flush_runs.shape[0] else None for tr in traces]
+            if batched:
+                g.lsm_driver_flush_many(trees, runs)
+            else:
+                for tree, run in zip(trees, runs):
+                    if run is not None:
+                        tree.flush(run)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        comp = [e for t in trees for e in t.trace if e[0] == "compact"]
+        first = trees[0].tree()
+        shape, at = [], 0
+        for _t, _k, n_runs in trees[0].levels():
+            shape.append([int(t.run.n) for t in first[at:at + n_runs]])
+            at += n_runs
+        for t in trees:
+            t.close()
+        return dt, len(comp), sum(e[3] for e in comp), shape
+
     dt_one, n_comp, merged, shape_one = replay(False)
     dt_batch, n_comp_b, merged_b, shape_batch = replay(True)
     assert (n_comp, merged, shape_one) == (n_comp_b, merged_b, shape_batch), "the batched replay built another tree"
+    lib_one, lib_batch = replay_library(False), replay_library(True)
+    assert lib_one[1:] == (n_comp, merged, shape_one) and lib_batch[1:] == (n_comp, merged, shape_one), "the library's driver built another tree"
     return {"workload": "%d independent trees of %d entries, %d flush rounds of %d entries per tree"
                         % (n_shards, sum(int(r.shape[0]) for r in traces[0].workload.runs), rounds, traces[0].buffer_entries),
             "compactions": n_comp, "entries_merged": merged,
             "one_call_per_compaction": {"seconds": dt_one, "merged_entries_per_s_incl_host": merged / dt_one},
             "batched": {"seconds": dt_batch, "merged_entries_per_s_incl_host": merged / dt_batch},
-            "speedup": dt_one / dt_batch}
+            "speedup": dt_one / dt_batch,
+            "library_driver": {"one_call_per_compaction": {"seconds": lib_one[0], "merged_entries_per_s_incl_host": merged / lib_one[0]},
+                               "batched": {"seconds": lib_batch[0], "merged_entries_per_s_incl_host": merged / lib_batch[0]}}}
 
 
 def main() -> int:

@@ -547,6 +547,14 @@ int lsm_driver_flush(lsm_driver_t* driver, const lsm_entry_t* run, uint64_t n);
  * the newest version of every key by lsm_flush_buffer first. */
 int lsm_driver_flush_unsorted(lsm_driver_t* driver, const lsm_entry_t* buffer, uint64_t n);
 
+/* One flush for each of `count` independent trees (key-range shards of one index, or one index per tenant), stepped
+ * together: the compactions that the trees' cascades need at the same step go to the GPU as one lsm_compact_batch (the
+ * fence indices written in the same pass) and the filters of their outputs as one lsm_build_bloom_batch, until every tree
+ * is settled; a compaction of 2^21 entries or more is run on its own.  Every tree ends exactly as after its own
+ * lsm_driver_flush.  drivers, runs, n: HOST arrays of `count` elements; runs[i] == NULL = tree i has nothing to flush.
+ * The drivers must be distinct and share one stream (LSM_ERR_BAD_ARG otherwise). */
+int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_entry_t* const* runs, const uint64_t* n, uint32_t count);
+
 /* lsm_probe over the current tree (run_idx of a hit = position in lsm_driver_tree's order); the call waits for the
  * result, counts the batch in the window and may re-run the (T, K) search.  More than LSM_MAX_RUNS runs in the tree:
  * LSM_ERR_BAD_ARG. */

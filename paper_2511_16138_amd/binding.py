@@ -189,6 +189,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_driver_flush.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
     L.lsm_driver_flush_unsorted.restype = C.c_int
     L.lsm_driver_flush_unsorted.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
+    L.lsm_driver_flush_many.restype = C.c_int
+    L.lsm_driver_flush_many.argtypes = [C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_uint64), C.c_uint32]
     L.lsm_driver_probe.restype = C.c_int
     L.lsm_driver_probe.argtypes = [C.c_void_p, C.POINTER(_Queries), C.POINTER(_Hits)]
     L.lsm_driver_levels.restype = C.c_uint32
@@ -743,3 +745,18 @@ class LsmDriver:
                 else:
                     self._events.append(("policy", e.a, e.b, tuple(round(x, 6) for x in e.mix), round(e.d, 6)))
         return self._events
+
+
+def lsm_driver_flush_many(drivers: Sequence[LsmDriver], runs: Sequence[Optional[torch.Tensor]]) -> None:
+    """One flush for each of several independent trees, stepped together: the compactions their cascades need at the same
+    step run as one batch.  runs[i] is tree i's sorted write buffer, or None if it has nothing to flush."""
+    count = len(drivers)
+    if count == 0:
+        return
+    assert len(runs) == count
+    hd = (C.c_void_p * count)(*[d._h for d in drivers])
+    ptr = (C.c_void_p * count)(*[None if r is None else _dev(r, "run").data_ptr() for r in runs])
+    n = (C.c_uint64 * count)(*[0 if r is None else int(r.shape[0]) for r in runs])
+    rc = _load().lsm_driver_flush_many(hd, ptr, n, count)
+    if rc != 0:
+        raise LsmError(rc, "lsm_driver_flush_many")

@@ -112,6 +112,10 @@ struct lsm_driver {
     uint64_t* n_host = nullptr;  // pinned: the kernels write a compaction's count here
     uint32_t* hit_host = nullptr;  // pinned copy of a probe batch's hit_len
     size_t hit_host_count = 0;
+    uint64_t* counts_host = nullptr;  // pinned: the counts of a batch of compactions (lsm_driver_flush_many)
+    size_t counts_host_count = 0;
+    void* batch_workspace = nullptr;
+    size_t batch_workspace_bytes = 0;
 
     void record(uint32_t kind, uint32_t level, uint32_t a, uint32_t b, uint64_t n_in, uint64_t n_out) {
         lsm_driver_event_t e;
@@ -179,7 +183,7 @@ struct lsm_driver {
             if (hashes == nullptr) return LSM_ERR_HIP;
             rc = lsm_hash_keys(&run, hashes, stream);
         }
-        if (rc == LSM_OK && cfg.bloom_bits != 0) {
+        if (rc == LSM_OK && cfg.bloom_bits != 0 && r.bloom == nullptr) {
             r.n_blocks = lsm_bloom_blocks(r.n, cfg.bloom_bits);
             if (r.n_blocks != 0) {
                 r.bloom = pool.take(r.n_blocks * 16);
@@ -232,7 +236,8 @@ struct lsm_driver {
             const int rc = lsm_build_fences(&run, cfg.fence_stride, r.fences, side);
             if (rc != LSM_OK) return rc;
         }
-        if (r.bloom == nullptr && r.index == nullptr) return build_lookup(r);
+        const bool wants_index = cfg.hash_index_from != 0 && r.n >= cfg.hash_index_from && r.n <= (1ull << 27);
+        if (r.index == nullptr && (r.bloom == nullptr || wants_index)) return build_lookup(r);  // the filter may be there already (batch)
         return LSM_OK;
     }
 
@@ -285,40 +290,62 @@ struct lsm_driver {
         return LSM_OK;
     }
 
-    // A run arrives at a level (0-based); the compactions and moves this triggers are done one after the other.
-    int arrive(uint32_t level, Run moving) {
-        for (;;) {
-            ensure_level(level);
-            Level& lv = levels[level];
-            if (lv.T != T || lv.K != K) record(LSM_EV_ADOPT, level + 1, T, K, 0, 0);
-            lv.T = T, lv.K = K;  // lazy transition: the level takes the current parameters when data flows into it
-            lv.runs.insert(lv.runs.begin(), moving);
-            if (lv.runs.size() <= lv.K) return settle(lv.runs[0]);
-            bool deeper_empty = true;
-            for (size_t i = level + 1; i < levels.size(); i++) deeper_empty = deeper_empty && levels[i].runs.empty();
-            const uint32_t flags = deeper_empty ? (uint32_t)LSM_BOTTOMMOST : 0u;
-            uint64_t n_in = 0;
-            for (const Run& r : lv.runs) n_in += r.n;
-            Run merged;
-            const int rc = compact(lv.runs, flags, level, &merged);
-            if (rc != LSM_OK) return rc;
-            record(LSM_EV_COMPACT, level + 1, (uint32_t)lv.runs.size(), flags, n_in, merged.n);
-            const int built = finish_builds();  // a run that is merged away may still be read by the build of its own filter
-            if (built != LSM_OK) return built;
-            for (Run& r : lv.runs) drop(r);
-            lv.runs.clear();
-            if (merged.n > capacity(level)) {
-                record(LSM_EV_MOVE, level + 1, level + 2, 0, 0, merged.n);
-                moving = merged;
-                level++;
-                continue;
-            }
-            if (merged.n > 0) {
-                lv.runs.push_back(merged);
-                return settle(lv.runs[0]);
-            }
-            return LSM_OK;
+    // A run arrives at a level (0-based).  The cascade this starts is cut into steps, so that a caller who drives several
+    // trees can run the compactions of their current steps as one batch: arrive_begin places the run and either
+    // settles it or leaves a compaction to be done in `due`; arrive_merged takes that compaction's output and either
+    // places it, or moves it down (arrive_begin at the next level, which may leave the next compaction in `due`).
+    struct Due {
+        bool active = false;
+        uint32_t level = 0, flags = 0;
+        uint64_t n_in = 0;
+    } due;
+
+    int arrive_begin(uint32_t level, const Run& moving) {
+        ensure_level(level);
+        Level& lv = levels[level];
+        if (lv.T != T || lv.K != K) record(LSM_EV_ADOPT, level + 1, T, K, 0, 0);
+        lv.T = T, lv.K = K;  // lazy transition: the level takes the current parameters when data flows into it
+        lv.runs.insert(lv.runs.begin(), moving);
+        if (lv.runs.size() <= lv.K) return settle(lv.runs[0]);
+        bool deeper_empty = true;
+        for (size_t i = level + 1; i < levels.size(); i++) deeper_empty = deeper_empty && levels[i].runs.empty();
+        due.active = true, due.level = level, due.flags = deeper_empty ? (uint32_t)LSM_BOTTOMMOST : 0u, due.n_in = 0;
+        for (const Run& r : lv.runs) due.n_in += r.n;
+        return LSM_OK;
+    }
+
+    int arrive_merged(const Run& merged) {
+        const uint32_t level = due.level;
+        Level& lv = levels[level];
+        due.active = false;
+        record(LSM_EV_COMPACT, level + 1, (uint32_t)lv.runs.size(), due.flags, due.n_in, merged.n);
+        const int built = finish_builds();  // a run that is merged away may still be read by the build of its own filter
+        if (built != LSM_OK) return built;
+        for (Run& r : lv.runs) drop(r);
+        lv.runs.clear();
+        if (merged.n > capacity(level)) {
+            record(LSM_EV_MOVE, level + 1, level + 2, 0, 0, merged.n);
+            return arrive_begin(level + 1, merged);
         }
+        if (merged.n > 0) {
+            lv.runs.push_back(merged);
+            return settle(lv.runs[0]);
+        }
+        return LSM_OK;
+    }
+
+    // The compaction that is due, on its own (one lsm_compact).
+    int compact_due() {
+        Run merged;
+        const int rc = compact(levels[due.level].runs, due.flags, due.level, &merged);
+        return rc != LSM_OK ? rc : arrive_merged(merged);
+    }
+
+    // The whole cascade of one arrival, one compaction after the other.
+    int arrive(uint32_t level, const Run& moving) {
+        int rc = arrive_begin(level, moving);
+        while (rc == LSM_OK && due.active) rc = compact_due();
+        return rc;
     }
 
     // One batch of operation counts enters the window; the (T, K) search is re-run when the mix has moved.
@@ -409,6 +436,7 @@ extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
     if (d->ordered != nullptr) (void)hipEventDestroy(d->ordered);
     if (d->n_host != nullptr) (void)hipHostFree(d->n_host);
     if (d->hit_host != nullptr) (void)hipHostFree(d->hit_host);
+    if (d->counts_host != nullptr) (void)hipHostFree(d->counts_host);
     delete d;
 }
 
@@ -461,6 +489,118 @@ extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buf
     Run r;
     r.entries = sorted, r.n = *d->n_host, r.owned = true;
     return d->arrive(0, r);
+}
+
+// Jobs of at least this many input entries are merged on their own: lsm_compact_batch takes jobs below 2,048 tiles.
+static constexpr uint64_t kBatchJobEntries = 1ull << 21;
+
+extern "C" int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_entry_t* const* runs, const uint64_t* n, uint32_t count) {
+    if (count == 0) return LSM_OK;
+    if (drivers == nullptr || runs == nullptr || n == nullptr) return LSM_ERR_NULL;
+    for (uint32_t i = 0; i < count; i++) {
+        if (drivers[i] == nullptr || (n[i] > 0 && runs[i] == nullptr)) return LSM_ERR_NULL;
+        if (drivers[i]->stream != drivers[0]->stream || (reinterpret_cast<uintptr_t>(runs[i]) & 63) != 0) return LSM_ERR_BAD_ARG;
+        for (uint32_t j = 0; j < i; j++)
+            if (drivers[j] == drivers[i]) return LSM_ERR_BAD_ARG;
+    }
+    lsm_driver_t* const first = drivers[0];
+    if (count > first->counts_host_count) {
+        if (first->counts_host != nullptr) (void)hipHostFree(first->counts_host);
+        first->counts_host = nullptr, first->counts_host_count = 0;
+        if (hipHostMalloc(reinterpret_cast<void**>(&first->counts_host), (size_t)count * sizeof(uint64_t), hipHostMallocDefault) != hipSuccess)
+            return LSM_ERR_HIP;
+        first->counts_host_count = count;
+    }
+    for (uint32_t i = 0; i < count; i++) {
+        if (runs[i] == nullptr) continue;  // nothing to flush for this tree
+        Run r;
+        if (n[i] > 0) r.entries = runs[i], r.n = n[i], r.transient = true;
+        const int rc = drivers[i]->arrive_begin(0, r);
+        if (rc != LSM_OK) return rc;
+    }
+    std::vector<lsm_driver_t*> active;
+    std::vector<std::vector<lsm_run_t>> inputs;
+    std::vector<lsm_compact_job_t> jobs;
+    std::vector<Run> merged;
+    std::vector<lsm_run_t> filtered;
+    std::vector<void*> filters;
+    std::vector<uint64_t> filter_blocks;
+    for (;;) {
+        // the compactions that are due now: the long ones on their own, the others as one batch
+        active.clear();
+        for (uint32_t i = 0; i < count; i++) {
+            lsm_driver_t* d = drivers[i];
+            while (d->due.active && d->due.n_in >= kBatchJobEntries) {
+                const int rc = d->compact_due();
+                if (rc != LSM_OK) return rc;
+            }
+            if (d->due.active) active.push_back(d);
+        }
+        if (active.empty()) return LSM_OK;
+        const uint32_t n_jobs = (uint32_t)active.size();
+        inputs.assign(n_jobs, {});
+        jobs.assign(n_jobs, lsm_compact_job_t{});
+        merged.assign(n_jobs, Run());
+        int rc = LSM_OK;
+        for (uint32_t j = 0; j < n_jobs && rc == LSM_OK; j++) {
+            lsm_driver_t* d = active[j];
+            const std::vector<Run>& in = d->levels[d->due.level].runs;
+            if (in.size() > LSM_MAX_RUNS) rc = LSM_ERR_BAD_ARG;
+            for (const Run& r : in) inputs[j].push_back(lsm_run_t{r.entries, r.n});
+            const uint64_t room = d->due.n_in > 0 ? d->due.n_in : 1;
+            lsm_entry_t* entries = static_cast<lsm_entry_t*>(d->pool.take(room * sizeof(lsm_entry_t)));
+            uint8_t* fences = static_cast<uint8_t*>(d->pool.take(ceil_div(room, d->cfg.fence_stride) * LSM_KEY_BYTES));
+            if (entries == nullptr || fences == nullptr) rc = LSM_ERR_HIP;
+            merged[j].entries = entries, merged[j].owned = true, merged[j].fences = fences;  // given back through drop() on failure
+            jobs[j].runs = inputs[j].data(), jobs[j].n_runs = (uint32_t)inputs[j].size(), jobs[j].flags = d->due.flags;
+            jobs[j].out = lsm_out_t{entries, room, first->counts_host + j, fences, d->cfg.fence_stride, nullptr};
+        }
+        const size_t need = rc == LSM_OK ? lsm_compact_batch_workspace_bytes(jobs.data(), n_jobs) : 0;
+        if (rc == LSM_OK && need == 0) rc = LSM_ERR_BAD_ARG;
+        if (rc == LSM_OK && need > first->batch_workspace_bytes) {
+            first->pool.give(first->batch_workspace);
+            first->batch_workspace_bytes = 2 * need;
+            first->batch_workspace = first->pool.take(first->batch_workspace_bytes);
+            if (first->batch_workspace == nullptr) first->batch_workspace_bytes = 0, rc = LSM_ERR_HIP;
+        }
+        if (rc == LSM_OK) rc = lsm_compact_batch(jobs.data(), n_jobs, first->batch_workspace, first->batch_workspace_bytes, first->stream);
+        if (rc == LSM_OK) rc = first->wait();
+        for (uint32_t j = 0; j < n_jobs && rc == LSM_OK; j++)
+            if (first->counts_host[j] > jobs[j].out.capacity) rc = LSM_ERR_INTERNAL;  // the device-side failure mark, or nonsense
+        if (rc != LSM_OK) {
+            for (uint32_t j = 0; j < n_jobs; j++) active[j]->drop(merged[j]);
+            return rc;
+        }
+        // the filters of all outputs in one call
+        filtered.clear(), filters.clear(), filter_blocks.clear();
+        for (uint32_t j = 0; j < n_jobs; j++) {
+            lsm_driver_t* d = active[j];
+            merged[j].n = first->counts_host[j];
+            if (d->cfg.observer != nullptr) d->cfg.observer(d->cfg.observer_ctx, d->due.level + 1, merged[j].entries, merged[j].n);
+            if (merged[j].n == 0) {
+                d->drop(merged[j]);
+                continue;
+            }
+            const uint64_t n_blocks = d->cfg.bloom_bits != 0 ? lsm_bloom_blocks(merged[j].n, d->cfg.bloom_bits) : 0;
+            if (n_blocks == 0) continue;
+            merged[j].bloom = d->pool.take(n_blocks * 16);
+            merged[j].n_blocks = n_blocks;
+            if (merged[j].bloom == nullptr) rc = LSM_ERR_HIP;
+            filtered.push_back(lsm_run_t{merged[j].entries, merged[j].n});
+            filters.push_back(merged[j].bloom);
+            filter_blocks.push_back(n_blocks);
+        }
+        if (rc == LSM_OK && !filtered.empty())
+            rc = lsm_build_bloom_batch(filtered.data(), filters.data(), filter_blocks.data(), (uint32_t)filtered.size(), first->stream);
+        for (uint32_t j = 0; j < n_jobs; j++) {
+            if (rc != LSM_OK) {
+                active[j]->drop(merged[j]);
+                continue;
+            }
+            rc = active[j]->arrive_merged(merged[j]);
+        }
+        if (rc != LSM_OK) return rc;
+    }
 }
 
 extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, const lsm_hits_t* out_hits) {

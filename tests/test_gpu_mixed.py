@@ -284,3 +284,65 @@ def test_sharded_trees_with_batched_compactions(oracle):
                     assert oracle.hash_index_check(cr, gr.index.cpu().numpy()) == 0
                 else:
                     assert gr.index is None
+
+
+def test_sharded_trees_in_the_library_driver(oracle):
+    """The same four trees driven by the library (lsm_driver_flush_many): every compaction output, probe batch, log and
+    final tree equal the plain driver's for that tree alone.  One tree also gets hash indices, one has no filters."""
+    from oracle import lsm_driver_oracle as drv
+    from paper_2511_16138_amd import LsmDriver, lsm_driver_flush_many
+    from workloads import lsm, rng
+    print("sharded trees, library driver", flush=True)
+    n_shards, window = 4, 16 * 128
+    traces = [lsm.config5(device=dev(), seed=rng.SEED + 1000 * i, tree_total=200_000 + 50_000 * i, buffer_entries=360,
+                          ops_per_phase=2048, batch_requests=128) for i in range(n_shards)]
+    bits = [16, 16, 0, 16]
+    index_from = [0, 5000, 0, 0]
+    outs = [[] for _ in range(n_shards)]
+    want_outs = [[] for _ in range(n_shards)]
+    trees = [LsmDriver(tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=(2, 16), bloom_bits=bits[i],
+                       hash_index_from=index_from[i], on_compaction=(lambda level, out, i=i: outs[i].append(out)))
+             for i, tr in enumerate(traces)]
+    cpus = [drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=(2, 16),
+                             page_entries=64.0, fpr=drv.bloom_fpr(bits[i]), on_compact=want_outs[i].append) for i, tr in enumerate(traces)]
+    for tr, tree, cpu in zip(traces, trees, cpus):
+        for level, r in enumerate(tr.workload.runs):
+            tree.load_run(level + 1, r)
+            cpu.install(level + 1, [r.cpu()])
+    at = [0] * n_shards
+    rounds = together = 0
+    while any(at[i] < len(traces[i].events) for i in range(n_shards)):
+        runs = [None] * n_shards
+        for i, (tr, tree, cpu) in enumerate(zip(traces, trees, cpus)):
+            if at[i] >= len(tr.events):
+                continue
+            (kind, idx, _phase), n_writes = tr.events[at[i]], tr.write_ops_between[at[i]]
+            at[i] += 1
+            if n_writes:
+                tree.note_writes(n_writes)
+                cpu.writes(n_writes)
+            if kind == "flush":
+                runs[i] = tr.flush_runs[idx]
+                cpu.flush(runs[i].cpu())
+            else:
+                q, nb = tr.probe_batch(idx)
+                ghl, ghits = tree.probe(q, nb)
+                chl, chits = cpu.probe(q.cpu(), nb.cpu())
+                assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl)
+                assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits)
+        lsm_driver_flush_many(trees, runs)
+        rounds += 1
+        together += sum(1 for r in runs if r is not None) > 1
+        for i, (tree, cpu) in enumerate(zip(trees, cpus)):
+            assert len(outs[i]) == len(want_outs[i])
+            for got, want in zip(outs[i], want_outs[i]):
+                assert np.array_equal(oracle.as_run(got), want), f"tree {i}: a compaction output differs"
+            outs[i].clear()
+            want_outs[i].clear()
+            log = tree.trace
+            assert log[-2:] == cpu.log[-2:] and len(log) == len(cpu.log), (i, log[-3:], cpu.log[-3:])
+    assert together > rounds // 2          # most rounds flushed several trees at once
+    for i, (tree, cpu) in enumerate(zip(trees, cpus)):
+        assert tree.trace == cpu.log and any(e[0] == "move" for e in cpu.log)
+        check_native_tree(oracle, tree, cpu, bits[i], index_from[i])
+        tree.close()

@@ -59,6 +59,10 @@ def test_driver_arguments_are_checked_before_anything_is_allocated(lib):
                        (lib.lsm_driver_load_run, (None, 1, None, 0)), (lib.lsm_driver_target, (None, None, None)),
                        (lib.lsm_driver_level, (None, 1, None, None, None)), (lib.lsm_driver_read, (None, None, None, 0))]:
         assert call(*args) == -1
+    one = (C.c_void_p * 1)(None)
+    assert lib.lsm_driver_flush_many(None, None, None, 0) == 0          # nothing to do
+    assert lib.lsm_driver_flush_many(None, None, None, 1) == -1
+    assert lib.lsm_driver_flush_many(one, (C.c_void_p * 1)(None), (C.c_uint64 * 1)(0), 1) == -1   # a NULL driver
     assert lib.lsm_driver_levels(None) == 0 and lib.lsm_driver_log(None, 0, None, 0) == 0
     lib.lsm_driver_destroy(None)                          # allowed
 
