@@ -539,6 +539,11 @@ int lsm_driver_load_run(lsm_driver_t* driver, uint32_t level, const lsm_entry_t*
 /* n_ops sequences were inserted since the last report (the controller's write count). */
 int lsm_driver_note_writes(lsm_driver_t* driver, uint64_t n_ops);
 
+/* Lookups answered elsewhere (the caller's own lsm_probe calls over lsm_driver_tree, say): `successful` requests
+ * that found `blocks` blocks in all, and `empty` requests that found nothing; logged and counted like one probe batch.
+ * Neither this call nor lsm_driver_note_writes touches the GPU. */
+int lsm_driver_note_reads(lsm_driver_t* driver, uint64_t successful, uint64_t empty, uint64_t blocks);
+
 /* A sorted run from the write buffer enters level 1; every compaction and move this triggers is done before the call
  * returns.  run: DEVICE, strictly ascending; it is read only by work that the call enqueues on the driver's stream (a
  * run that comes to rest is copied), so the caller may reuse the memory in stream order afterwards. */

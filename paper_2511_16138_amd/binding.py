@@ -185,6 +185,8 @@ def _load(path: Optional[str] = None) -> C.CDLL:
     L.lsm_driver_load_run.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64]
     L.lsm_driver_note_writes.restype = C.c_int
     L.lsm_driver_note_writes.argtypes = [C.c_void_p, C.c_uint64]
+    L.lsm_driver_note_reads.restype = C.c_int
+    L.lsm_driver_note_reads.argtypes = [C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint64]
     L.lsm_driver_flush.restype = C.c_int
     L.lsm_driver_flush.argtypes = [C.c_void_p, C.c_void_p, C.c_uint64]
     L.lsm_driver_flush_unsorted.restype = C.c_int
@@ -642,11 +644,13 @@ class LsmDriver:
                             page_entries, -1.0 if filter_fpr is None else filter_fpr, fence_stride, bloom_bits, hash_index_from,
                             self._observer, None)
         self._h = C.c_void_p()
-        rc = L.lsm_driver_create(C.byref(cfg), _stream_ptr(stream), C.byref(self._h))
+        # without a GPU only the controller can be used (note_writes, note_reads, trace, target): no stream to name
+        on_gpu = stream is not None or torch.cuda.is_available()
+        rc = L.lsm_driver_create(C.byref(cfg), _stream_ptr(stream) if on_gpu else None, C.byref(self._h))
         if rc != 0:
             raise LsmError(rc, "lsm_driver_create")
         self._borrowed: List[torch.Tensor] = []
-        self._device = torch.device("cuda", torch.cuda.current_device())
+        self._device = torch.device("cuda", torch.cuda.current_device()) if on_gpu else None
         self._events: List[tuple] = []
 
     def close(self) -> None:
@@ -682,6 +686,10 @@ class LsmDriver:
 
     def note_writes(self, n_ops: int) -> None:
         self._check(_load().lsm_driver_note_writes(self._h, n_ops), "lsm_driver_note_writes")
+
+    def note_reads(self, successful: int, empty: int, blocks: int) -> None:
+        """Read statistics of lookups done elsewhere: counted like one probe batch."""
+        self._check(_load().lsm_driver_note_reads(self._h, successful, empty, blocks), "lsm_driver_note_reads")
 
     def flush(self, run: torch.Tensor) -> None:
         self._check(_load().lsm_driver_flush(self._h, _dev(run, "run").data_ptr(), int(run.shape[0])), "lsm_driver_flush")

@@ -155,6 +155,15 @@ struct lsm_driver {
 
     int wait() { return hipStreamSynchronize(stream) == hipSuccess ? LSM_OK : LSM_ERR_HIP; }
 
+    // What the driver needs of the GPU runtime is created by the first call that works on runs, so that the controller
+    // (note_writes, note_reads, the log) can be used, and tested, on its own.
+    int gpu_ready() {
+        if (n_host != nullptr) return LSM_OK;
+        if (hipStreamCreateWithFlags(&side, hipStreamNonBlocking) != hipSuccess) return LSM_ERR_HIP;
+        if (hipEventCreateWithFlags(&ordered, hipEventDisableTiming) != hipSuccess) return LSM_ERR_HIP;
+        return hipHostMalloc(reinterpret_cast<void**>(&n_host), sizeof(uint64_t), hipHostMallocDefault) == hipSuccess ? LSM_OK : LSM_ERR_HIP;
+    }
+
     // Waits for the builds on the second stream.  Needed before a lookup uses the structures, and before any memory the
     // builds read or write goes back to the pool.
     int finish_builds() {
@@ -417,19 +426,13 @@ extern "C" int lsm_driver_create(const lsm_driver_config_t* config, void* stream
     d->stream = static_cast<hipStream_t>(stream);
     d->p = config->filter_fpr < 0 ? lsm_policy_filter_fpr(config->bloom_bits) : config->filter_fpr;
     d->T = config->size_ratio, d->K = config->runs_per_level;
-    if (hipHostMalloc(reinterpret_cast<void**>(&d->n_host), sizeof(uint64_t), hipHostMallocDefault) != hipSuccess ||
-        hipStreamCreateWithFlags(&d->side, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&d->ordered, hipEventDisableTiming) != hipSuccess) {
-        lsm_driver_destroy(d);
-        return LSM_ERR_HIP;
-    }
     *driver_out = d;
     return LSM_OK;
 }
 
 extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
     if (d == nullptr) return;
-    (void)hipStreamSynchronize(d->stream);
+    if (d->n_host != nullptr || d->side != nullptr) (void)hipStreamSynchronize(d->stream);  // else no GPU call was ever made
     if (d->side != nullptr) (void)hipStreamSynchronize(d->side);
     d->pool.free_all();
     if (d->side != nullptr) (void)hipStreamDestroy(d->side);
@@ -443,6 +446,8 @@ extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
 extern "C" int lsm_driver_load_run(lsm_driver_t* d, uint32_t level, const lsm_entry_t* entries, uint64_t n) {
     if (d == nullptr || (n > 0 && entries == nullptr)) return LSM_ERR_NULL;
     if (level == 0 || level > 64 || (reinterpret_cast<uintptr_t>(entries) & 63) != 0) return LSM_ERR_BAD_ARG;
+    const int ready = d->gpu_ready();
+    if (ready != LSM_OK) return ready;
     d->ensure_level(level - 1);
     Run r;
     r.entries = entries, r.n = n;
@@ -456,9 +461,18 @@ extern "C" int lsm_driver_note_writes(lsm_driver_t* d, uint64_t n_ops) {
     return d->count(n_ops, 0, 0, 0.0);
 }
 
+extern "C" int lsm_driver_note_reads(lsm_driver_t* d, uint64_t successful, uint64_t empty, uint64_t blocks) {
+    if (d == nullptr) return LSM_ERR_NULL;
+    if (successful + empty > UINT32_MAX) return LSM_ERR_BAD_ARG;
+    d->record(LSM_EV_PROBE, 0, (uint32_t)(successful + empty), (uint32_t)successful, 0, blocks);
+    return d->count(0, successful, empty, (double)blocks);
+}
+
 extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_t n) {
     if (d == nullptr || (n > 0 && run == nullptr)) return LSM_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(run) & 63) != 0) return LSM_ERR_BAD_ARG;
+    const int ready = d->gpu_ready();
+    if (ready != LSM_OK) return ready;
     Run r;
     if (n > 0) r.entries = run, r.n = n, r.transient = true;
     return d->arrive(0, r);
@@ -467,6 +481,8 @@ extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_
 extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buffer, uint64_t n) {
     if (d == nullptr || (n > 0 && buffer == nullptr)) return LSM_ERR_NULL;
     if (n > LSM_MAX_BUFFER) return LSM_ERR_BAD_ARG;
+    const int ready = d->gpu_ready();
+    if (ready != LSM_OK) return ready;
     const uint64_t room = n > 0 ? n : 1;
     const size_t ws_bytes = lsm_flush_workspace_bytes(n);
     lsm_entry_t* sorted = static_cast<lsm_entry_t*>(d->pool.take(room * sizeof(lsm_entry_t)));
@@ -504,6 +520,10 @@ extern "C" int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_ent
             if (drivers[j] == drivers[i]) return LSM_ERR_BAD_ARG;
     }
     lsm_driver_t* const first = drivers[0];
+    for (uint32_t i = 0; i < count; i++) {
+        const int ready = drivers[i]->gpu_ready();
+        if (ready != LSM_OK) return ready;
+    }
     if (count > first->counts_host_count) {
         if (first->counts_host != nullptr) (void)hipHostFree(first->counts_host);
         first->counts_host = nullptr, first->counts_host_count = 0;
@@ -610,7 +630,8 @@ extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, c
     if (n_runs > LSM_MAX_RUNS) return LSM_ERR_BAD_ARG;
     for (uint32_t i = 0; i < n_runs; i++) runs[i].level = i;
     const lsm_tree_t tree{runs, n_runs};
-    int rc = d->finish_builds();
+    int rc = d->gpu_ready();
+    if (rc == LSM_OK) rc = d->finish_builds();
     if (rc == LSM_OK) rc = lsm_probe(queries, &tree, out_hits, d->stream);
     if (rc != LSM_OK) return rc;
     const uint32_t n_req = queries->n_req;
@@ -667,7 +688,8 @@ extern "C" uint64_t lsm_driver_log(const lsm_driver_t* d, uint64_t first, lsm_dr
 
 extern "C" int lsm_driver_read(lsm_driver_t* d, const void* device_src, void* dst, size_t bytes) {
     if (d == nullptr || (bytes > 0 && (device_src == nullptr || dst == nullptr))) return LSM_ERR_NULL;
-    const int rc = d->finish_builds();
+    int rc = d->gpu_ready();
+    if (rc == LSM_OK) rc = d->finish_builds();
     if (rc != LSM_OK) return rc;
     if (bytes > 0 && hipMemcpyAsync(dst, device_src, bytes, hipMemcpyDefault, d->stream) != hipSuccess) return LSM_ERR_HIP;
     return d->wait();
