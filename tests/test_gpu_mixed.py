@@ -1,5 +1,6 @@
-"""Configuration 5 (mixed, shifting workload): the package's host driver on the GPU library against the plain driver
-of oracle/lsm_driver_oracle.py on the CPU checker.  The two share no code.  Every probe batch (all hit bytes), the
+"""Configuration 5 (mixed, shifting workload): the two host drivers of the GPU library (the Python one of tree.py and
+the library's own, lsm_driver_*), each against the plain driver of oracle/lsm_driver_oracle.py on the CPU checker.
+They share no code with it.  Every probe batch (all hit bytes), the
 sequence of compactions (level, run count, sizes in and out, last-level flag), the moves between levels, the policy
 decisions, the levels' transitions of (T, K) and the final tree must be identical."""
 import numpy as np
@@ -116,7 +117,7 @@ def test_mixed_trace_gpu_equals_plain_driver(oracle, tree_total, buffer_entries,
     tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=128)
     assert len([e for e in tr.events if e[0] == "flush"]) > 50 and len([e for e in tr.events if e[0] == "probe"]) >= 6
     shuffle = (lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())) if shuffled else None
-    gpu, n_probe = replay_both(oracle, tr, bloom_bits, t_grid, 16, shuffle, hash_index_from=hash_index_from)
+    gpu, n_probe = replay_both(oracle, tr, bloom_bits, t_grid, 16, shuffle, hash_index_from=hash_index_from, native=True)
     kinds = {e[0] for e in gpu.trace}
     assert {"compact", "probe", "policy", "move"} <= kinds and n_probe >= 6
     pol = [(e[1], e[2]) for e in gpu.trace if e[0] == "policy"]
@@ -155,75 +156,6 @@ def check_native_tree(oracle, gpu, cpu, bloom_bits, hash_index_from):
             assert oracle.hash_index_check(cr, gpu.read(t.index.buckets, t.index.n_buckets, 8).cpu().numpy()) == 0
         else:
             assert not t.index.buckets
-
-
-def replay_native(oracle, tr, bloom_bits, t_grid, window_batches, shuffle=None, hash_index_from=0):
-    """The same comparison for the library's own driver (lsm_driver_*): every compaction output as it is produced, every
-    probe batch, the log after every event, and at the end the tree with its fence indices, filters and hash indices."""
-    from gpu_util import oracle_probe_threads
-    from oracle import lsm_driver_oracle as drv
-    from paper_2511_16138_amd import LsmDriver
-    window = window_batches * tr.batch_requests
-    gpu_out, cpu_out = [], []
-    gpu = LsmDriver(tr.buffer_entries, size_ratio=tr.size_ratio, window_ops=window, t_grid=t_grid, bloom_bits=bloom_bits,
-                    hash_index_from=hash_index_from, on_compaction=lambda level, out: gpu_out.append((level, out)))
-    cpu = drv.DriverOracle(tr.buffer_entries, T=tr.size_ratio, K=1, window_ops=window, threshold=0.2, t_grid=t_grid,
-                           page_entries=64.0, fpr=drv.bloom_fpr(bloom_bits), on_compact=cpu_out.append,
-                           probe_fn=lambda q, nb, runs: oracle_probe_threads(oracle, q, nb, runs))
-    for level, r in enumerate(tr.workload.runs):
-        gpu.load_run(level + 1, r)
-        cpu.install(level + 1, [r.cpu()])
-    n_probe = 0
-    for (kind, i, _phase), n_writes in zip(tr.events, tr.write_ops_between):
-        if n_writes:
-            gpu.note_writes(n_writes)
-            cpu.writes(n_writes)
-        if kind == "flush":
-            run = tr.flush_runs[i]
-            if shuffle is not None:
-                gpu.flush_unsorted(run[shuffle(i, int(run.shape[0]))].contiguous())
-            else:
-                gpu.flush(run)
-            cpu.flush(run.cpu())
-            assert len(gpu_out) == len(cpu_out)
-            compacts = [e for e in cpu.log if e[0] == "compact"][-len(cpu_out):] if cpu_out else []
-            for (level, got), want, ev in zip(gpu_out, cpu_out, compacts):
-                assert level == ev[1] and np.array_equal(oracle.as_run(got), want), f"flush {i}: a compaction output differs"
-            gpu_out.clear()
-            cpu_out.clear()
-        else:
-            q, nb = tr.probe_batch(i)
-            ghl, ghits = gpu.probe(q, nb)
-            chl, chits = cpu.probe(q.cpu(), nb.cpu())
-            assert np.array_equal(ghl.cpu().numpy().astype(np.uint32), chl), f"probe batch {i}: hit_len"
-            assert np.array_equal(ghits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(chits.shape), chits), f"probe batch {i}"
-            n_probe += 1
-        log = gpu.trace
-        assert len(log) == len(cpu.log) and log[-1:] == cpu.log[-1:], (kind, i, log[-3:], cpu.log[-3:])
-    assert gpu.trace == cpu.log
-    check_native_tree(oracle, gpu, cpu, bloom_bits, hash_index_from)
-    log = list(gpu.trace)
-    gpu.close()
-    return log, n_probe
-
-
-@pytest.mark.parametrize("tree_total,buffer_entries,ops,bloom_bits,t_grid,shuffled,hash_index_from", [
-    (400_000, 360, 4096, 16, (2, 16), False, 0),     # filters on, the full (T, K) grid
-    (2_000_000, 900, 8192, 16, (10, 10), False, 0),  # T fixed at 10: only K moves
-    (400_000, 360, 4096, 0, (2, 16), False, 0),      # no filters: p = 1
-    (400_000, 360, 4096, 16, (2, 16), True, 0),      # write buffers handed over unsorted
-    (400_000, 360, 4096, 16, (2, 16), False, 2000),  # runs of 2,000 entries and more also get a hash index
-])
-def test_mixed_trace_native_driver_equals_plain_driver(oracle, tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, hash_index_from):
-    from workloads import lsm
-    print("mixed trace, native driver", tree_total, buffer_entries, ops, bloom_bits, t_grid, shuffled, hash_index_from, flush=True)
-    tr = lsm.config5(device=dev(), tree_total=tree_total, buffer_entries=buffer_entries, ops_per_phase=ops, batch_requests=128)
-    shuffle = (lambda i, n: torch.from_numpy(np.random.RandomState(i).permutation(n)).to(dev())) if shuffled else None
-    log, n_probe = replay_native(oracle, tr, bloom_bits, t_grid, 16, shuffle, hash_index_from=hash_index_from)
-    kinds = {e[0] for e in log}
-    assert {"compact", "probe", "policy", "move"} <= kinds and n_probe >= 6
-    if bloom_bits:
-        assert "adopt" in kinds and max(e[2] for e in log if e[0] == "policy") > 1
 
 
 def test_sharded_trees_with_batched_compactions(oracle):
