@@ -479,8 +479,10 @@ double lsm_policy_filter_fpr(uint32_t bits_per_key);
  * next flows into it; a smaller K merges the level at that arrival, a larger K leaves it alone).  It sequences the
  * calls above on the caller's stream (the lookup structures of a run that has come to rest are built on a second
  * stream of the driver's own, beside the next compaction; lookups and inspection wait for them) and owns the device
- * memory of the runs it creates (a pool that is given back only by lsm_driver_destroy).  One thread at a time per driver.  Every call returns an lsm_status; after an error other
- * than LSM_ERR_NULL / LSM_ERR_BAD_ARG the driver's tree is undefined and it can only be destroyed.
+ * memory of the runs it creates (a pool that is given back only by lsm_driver_destroy).  One thread at a time per
+ * driver.  Every call returns an lsm_status (LSM_ERR_HIP also when device memory runs out, LSM_ERR_INTERNAL also when
+ * host memory does); after an error other than LSM_ERR_NULL / LSM_ERR_BAD_ARG the driver's tree is undefined and it
+ * can only be destroyed.
  *
  * Readings where the paper gives no constants: an operation is one inserted sequence (lsm_driver_note_writes) or one
  * probe request; a request that finds no live first block is an empty probe (z), the others count half as range

@@ -443,7 +443,7 @@ extern "C" void lsm_driver_destroy(lsm_driver_t* d) {
     delete d;
 }
 
-extern "C" int lsm_driver_load_run(lsm_driver_t* d, uint32_t level, const lsm_entry_t* entries, uint64_t n) {
+extern "C" int lsm_driver_load_run(lsm_driver_t* d, uint32_t level, const lsm_entry_t* entries, uint64_t n) try {
     if (d == nullptr || (n > 0 && entries == nullptr)) return LSM_ERR_NULL;
     if (level == 0 || level > 64 || (reinterpret_cast<uintptr_t>(entries) & 63) != 0) return LSM_ERR_BAD_ARG;
     const int ready = d->gpu_ready();
@@ -454,21 +454,27 @@ extern "C" int lsm_driver_load_run(lsm_driver_t* d, uint32_t level, const lsm_en
     std::vector<Run>& runs = d->levels[level - 1].runs;
     runs.push_back(r);
     return d->settle(runs.back());
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
-extern "C" int lsm_driver_note_writes(lsm_driver_t* d, uint64_t n_ops) {
+extern "C" int lsm_driver_note_writes(lsm_driver_t* d, uint64_t n_ops) try {
     if (d == nullptr) return LSM_ERR_NULL;
     return d->count(n_ops, 0, 0, 0.0);
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
-extern "C" int lsm_driver_note_reads(lsm_driver_t* d, uint64_t successful, uint64_t empty, uint64_t blocks) {
+extern "C" int lsm_driver_note_reads(lsm_driver_t* d, uint64_t successful, uint64_t empty, uint64_t blocks) try {
     if (d == nullptr) return LSM_ERR_NULL;
     if (successful + empty > UINT32_MAX) return LSM_ERR_BAD_ARG;
     d->record(LSM_EV_PROBE, 0, (uint32_t)(successful + empty), (uint32_t)successful, 0, blocks);
     return d->count(0, successful, empty, (double)blocks);
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
-extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_t n) {
+extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_t n) try {
     if (d == nullptr || (n > 0 && run == nullptr)) return LSM_ERR_NULL;
     if ((reinterpret_cast<uintptr_t>(run) & 63) != 0) return LSM_ERR_BAD_ARG;
     const int ready = d->gpu_ready();
@@ -476,9 +482,11 @@ extern "C" int lsm_driver_flush(lsm_driver_t* d, const lsm_entry_t* run, uint64_
     Run r;
     if (n > 0) r.entries = run, r.n = n, r.transient = true;
     return d->arrive(0, r);
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
-extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buffer, uint64_t n) {
+extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buffer, uint64_t n) try {
     if (d == nullptr || (n > 0 && buffer == nullptr)) return LSM_ERR_NULL;
     if (n > LSM_MAX_BUFFER) return LSM_ERR_BAD_ARG;
     const int ready = d->gpu_ready();
@@ -505,12 +513,14 @@ extern "C" int lsm_driver_flush_unsorted(lsm_driver_t* d, const lsm_entry_t* buf
     Run r;
     r.entries = sorted, r.n = *d->n_host, r.owned = true;
     return d->arrive(0, r);
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
 // Jobs of at least this many input entries are merged on their own: lsm_compact_batch takes jobs below 2,048 tiles.
 static constexpr uint64_t kBatchJobEntries = 1ull << 21;
 
-extern "C" int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_entry_t* const* runs, const uint64_t* n, uint32_t count) {
+extern "C" int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_entry_t* const* runs, const uint64_t* n, uint32_t count) try {
     if (count == 0) return LSM_OK;
     if (drivers == nullptr || runs == nullptr || n == nullptr) return LSM_ERR_NULL;
     for (uint32_t i = 0; i < count; i++) {
@@ -621,9 +631,11 @@ extern "C" int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_ent
         }
         if (rc != LSM_OK) return rc;
     }
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
-extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, const lsm_hits_t* out_hits) {
+extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, const lsm_hits_t* out_hits) try {
     if (d == nullptr || queries == nullptr || out_hits == nullptr) return LSM_ERR_NULL;
     lsm_tree_run_t runs[LSM_MAX_RUNS];
     const uint32_t n_runs = d->tree(runs, LSM_MAX_RUNS);
@@ -652,6 +664,8 @@ extern "C" int lsm_driver_probe(lsm_driver_t* d, const lsm_queries_t* queries, c
     }
     d->record(LSM_EV_PROBE, 0, n_req, (uint32_t)hits, 0, blocks);
     return d->count(0, hits, n_req - hits, (double)blocks);
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
 extern "C" uint32_t lsm_driver_levels(const lsm_driver_t* d) { return d ? (uint32_t)d->levels.size() : 0; }
@@ -666,10 +680,12 @@ extern "C" int lsm_driver_level(const lsm_driver_t* d, uint32_t level, uint32_t*
     return LSM_OK;
 }
 
-extern "C" int lsm_driver_tree(lsm_driver_t* d, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs) {
+extern "C" int lsm_driver_tree(lsm_driver_t* d, lsm_tree_run_t* runs_out, uint32_t capacity, uint32_t* n_runs) try {
     if (d == nullptr || n_runs == nullptr || (capacity > 0 && runs_out == nullptr)) return LSM_ERR_NULL;
     *n_runs = d->tree(runs_out, capacity);
     return d->finish_builds();
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
 
 extern "C" int lsm_driver_target(const lsm_driver_t* d, uint32_t* T, uint32_t* K) {
@@ -686,11 +702,13 @@ extern "C" uint64_t lsm_driver_log(const lsm_driver_t* d, uint64_t first, lsm_dr
     return n;
 }
 
-extern "C" int lsm_driver_read(lsm_driver_t* d, const void* device_src, void* dst, size_t bytes) {
+extern "C" int lsm_driver_read(lsm_driver_t* d, const void* device_src, void* dst, size_t bytes) try {
     if (d == nullptr || (bytes > 0 && (device_src == nullptr || dst == nullptr))) return LSM_ERR_NULL;
     int rc = d->gpu_ready();
     if (rc == LSM_OK) rc = d->finish_builds();
     if (rc != LSM_OK) return rc;
     if (bytes > 0 && hipMemcpyAsync(dst, device_src, bytes, hipMemcpyDefault, d->stream) != hipSuccess) return LSM_ERR_HIP;
     return d->wait();
+} catch (...) {  // host memory ran out: nothing may be thrown through the C ABI
+    return LSM_ERR_INTERNAL;
 }
