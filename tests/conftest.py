@@ -18,3 +18,13 @@ def oracle():
     from oracle import lsm_oracle
     lsm_oracle.build()
     return lsm_oracle
+
+
+@pytest.fixture
+def say(capsys):
+    """print() for the long tests: shown even when pytest captures output, so that a run of several minutes is not
+    silent."""
+    def say(*args):
+        with capsys.disabled():
+            print(*args, flush=True)
+    return say

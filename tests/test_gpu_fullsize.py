@@ -54,11 +54,11 @@ def test_config3_full_tiered_16_way(g, oracle):
     assert 0.66 < ratio < 0.70  # about 0.95 / 1.4 of the inputs survive
 
 
-def test_config4_full_tree_all_probe_batches(g, oracle):
+def test_config4_full_tree_all_probe_batches(g, oracle, say):
     """5-level, 100M-entry tree; all 256 batches of 4,096 requests (2^20 requests): hit_len and every hit byte.
     Every 16th batch is also run with Bloom filters and through the search over the prefix length."""
     from workloads import lsm
-    print("config4 full tree", flush=True)
+    say("config4 full tree")
     w = lsm.config4(device=dev())
     assert sum(int(r.shape[0]) for r in w.runs) == 100_000_000 and len(w.runs) == 5
     tree = build_tree(g, w.runs)
@@ -82,7 +82,7 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
         assert oracle.hash_index_check(r, index.cpu().numpy()) == 0
         indexed.append(g.TreeRun(t.run, t.fences, t.stride, t.level, None, index))
         both.append(g.TreeRun(t.run, t.fences, t.stride, t.level, f.bloom, index))
-    print("  filters and hash indices ok", flush=True)
+    say("  filters and hash indices ok")
     t0, misses, requests = time.time(), 0, 0
     for stream in range(256):
         q, nb = lsm.queries_config4(w, 4096, stream=stream)
@@ -92,7 +92,7 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
         misses += int((want[0] == 0).sum())
         requests += int(want[0].shape[0])
         if stream % 16 == 0:
-            print(f"  batch {stream} ok ({time.time() - t0:.0f} s)", flush=True)
+            say(f"  batch {stream} ok ({time.time() - t0:.0f} s)")
             assert_probe_equal(oracle, probe_gpu(g, q, nb, filtered), want)
             assert_probe_equal(oracle, probe_gpu(g, q, nb, indexed), want)
             assert_probe_equal(oracle, probe_gpu(g, q, nb, both), want)
@@ -102,28 +102,28 @@ def test_config4_full_tree_all_probe_batches(g, oracle):
     assert requests == 1 << 20 and 0.25 < misses / requests < 0.45
 
 
-def test_config5_full_mixed_trace_on_400m_tree(oracle):
+def test_config5_full_mixed_trace_on_400m_tree(oracle, say):
     """The mixed, shifting workload at its stated size: 6 levels, 400M entries, three phases of 2^18 operations with
     read shares 90 / 50 / 10 %, Bloom filters of 16 bits per key, (T, K) searched over T in 2..16.  Compared with the
     plain driver on the CPU checker: every compaction output byte for byte, every probe batch, every log record - for the
     Python driver over the single entry points and for the library's own driver (lsm_driver_*), stepped side by side."""
     from test_gpu_mixed import replay_both
     from workloads import lsm
-    print("config5 full: generating", flush=True)
+    say("config5 full: generating")
     t0 = time.time()
     tr = lsm.config5(device=dev())
     sizes = [int(r.shape[0]) for r in tr.workload.runs]
     assert sum(sizes) == 400_000_000 and len(sizes) == 6 and tr.buffer_entries == 3600
     n_flush = sum(1 for e in tr.events if e[0] == "flush")
     n_batches = sum(1 for e in tr.events if e[0] == "probe")
-    print(f"  tree {sizes}, {n_flush} flushes, {n_batches} probe batches ({time.time() - t0:.0f} s)", flush=True)
+    say(f"  tree {sizes}, {n_flush} flushes, {n_batches} probe batches ({time.time() - t0:.0f} s)")
     assert n_flush > 4000 and n_batches >= 90
     gpu, n_probe = replay_both(oracle, tr, 16, (2, 16), 16, native=True,
-                               progress=lambda msg: print(f"  {msg} ({time.time() - t0:.0f} s)", flush=True))
+                               progress=lambda msg: say(f"  {msg} ({time.time() - t0:.0f} s)"))
     assert n_probe == n_batches
     comp = [e for e in gpu.trace if e[0] == "compact"]
     pol = [(e[1], e[2]) for e in gpu.trace if e[0] == "policy"]
-    print("  policy (T, K):", pol, "compactions:", len(comp), "entries merged:", sum(e[3] for e in comp), flush=True)
+    say("  policy (T, K):", pol, "compactions:", len(comp), "entries merged:", sum(e[3] for e in comp))
     assert len(comp) > 2000 and max(e[3] for e in comp) > 10_000_000    # compactions down to the fourth level
     assert pol[0][1] == 1 and max(k for _, k in pol) > 1, pol            # leveling under reads, more runs under writes
     assert len({t for t, _ in pol}) > 1 or pol[0][0] != 10, pol
