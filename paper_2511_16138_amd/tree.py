@@ -193,6 +193,8 @@ class AdaptiveLsmTree:
         """A run that comes to rest in a level gets whatever lookup structure it still lacks.  (Runs that are merged
         away at once - a flushed run arriving at a full level, a run moved down onto another - never get any.)"""
         if lr.n == 0:
+            if lr.fences is None:
+                lr.fences = self.backend.build_fences(lr.run)   # an empty index, so that lookups can name the run
             return lr
         if lr.fences is None:
             lr.fences = self.backend.build_fences(lr.run)

@@ -146,6 +146,9 @@ def check_native_tree(oracle, gpu, cpu, bloom_bits, hash_index_from, progress=No
     for t, (level, cr) in zip(tree, want_runs):
         n = int(cr.shape[0])
         assert (t.level, t.run.n) == (level, n)
+        if n == 0:                       # an empty write buffer that came to rest: a run without structures
+            assert not t.bloom.blocks and not t.index.buckets and t.fence.n == 0
+            continue
         if progress:
             progress(f"final tree of the library's driver: run of {n} entries")
         if t.run.entries in borrowed:   # the right one of them: its two ends
@@ -289,3 +292,69 @@ def test_sharded_trees_in_the_library_driver(oracle):
         assert tree.trace == cpu.log and any(e[0] == "move" for e in cpu.log)
         check_native_tree(oracle, tree, cpu, bits[i], index_from[i])
         tree.close()
+
+
+@pytest.mark.parametrize("seed,start_k,t_grid", [(11, 1, (2, 5)), (12, 3, (2, 5)), (13, 2, (4, 4))])
+def test_drivers_on_degenerate_trees(oracle, seed, start_k, t_grid):
+    """Both drivers against the plain one where the trees are tiny and awkward: a key space of 300 keys with half of
+    all writes tombstones (compactions whose output is empty, levels that empty out again), empty write buffers,
+    several runs per level from the start, a window so short that (T, K) is searched again every few operations."""
+    import brute
+    from gpu_util import to_dev
+    from oracle import lsm_driver_oracle as drv
+    from paper_2511_16138_amd import LsmDriver
+    from paper_2511_16138_amd.tree import AdaptiveLsmTree, GpuBackend
+    print("degenerate trees", seed, start_k, t_grid, flush=True)
+    rs = np.random.RandomState(seed)
+    key_of = lambda k: int(k).to_bytes(32, "big")
+    M, window = 40, 64
+    py = AdaptiveLsmTree(GpuBackend(bloom_bits=16, hash_index_from=50), M, size_ratio=4, runs_per_level=start_k, window_ops=window,
+                         t_grid=t_grid)
+    nat = LsmDriver(M, size_ratio=4, runs_per_level=start_k, window_ops=window, t_grid=t_grid, bloom_bits=16, hash_index_from=50)
+    cpu = drv.DriverOracle(M, T=4, K=start_k, window_ops=window, threshold=0.2, t_grid=t_grid, page_entries=64.0, fpr=drv.bloom_fpr(16))
+    seq = 0
+    empties = empty_outputs = 0
+    for step in range(260):
+        if step < 4 or rs.rand() < 0.7:
+            n = 0 if rs.rand() < 0.1 else int(rs.randint(1, M + 1))
+            keys = sorted(rs.choice(300, size=n, replace=False).tolist())
+            raw = []
+            for k in keys:
+                seq += 1
+                tomb = step < 4 or rs.rand() < 0.5     # the first buffers hold deletions only: they merge to nothing
+                raw.append(brute.pack_entry(key_of(k), seq, brute.TOMBSTONE if tomb else brute.PUT, vptr=seq, vlen=k))
+            run = brute.run_from_raw(raw)
+            empties += n == 0
+            for d in (py, nat):
+                d.note_writes(max(n, 1))
+            cpu.writes(max(n, 1))
+            g_run = to_dev(run)
+            py.flush(g_run)
+            nat.flush(g_run)
+            cpu.flush(run)
+        else:
+            n_req, max_blocks = 24, 6
+            q = np.zeros((n_req, max_blocks, 32), np.uint8)
+            nb = rs.randint(0, max_blocks + 1, size=n_req).astype(np.int32)
+            for r in range(n_req):
+                for j in range(max_blocks):
+                    q[r, j] = np.frombuffer(key_of(rs.randint(0, 300)), np.uint8)
+            gq = torch.from_numpy(q.view(np.int64).reshape(n_req, max_blocks, 4).copy()).to(dev())
+            gnb = torch.from_numpy(nb).to(dev())
+            want_len, want_hits = cpu.probe(q, nb.astype(np.uint32))
+            for d in (py, nat):
+                hl, hits = d.probe(gq, gnb)
+                assert np.array_equal(hl.cpu().numpy().astype(np.uint32), want_len), step
+                assert np.array_equal(hits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(want_hits.shape), want_hits), step
+        assert py.trace == cpu.log and nat.trace == cpu.log, (step, py.trace[-3:], nat.trace[-3:], cpu.log[-3:])
+        empty_outputs = sum(1 for e in cpu.log if e[0] == "compact" and e[4] == 0)
+    assert empties >= 5 and (empty_outputs >= 1 or start_k == 3)   # with three runs per level the deletions are not merged alone
+    kinds = {e[0] for e in cpu.log}
+    assert {"compact", "move", "policy", "adopt", "probe"} <= kinds
+    assert len({e[1:3] for e in cpu.log if e[0] == "policy"}) > 1
+    assert [len(lv) for lv in py.levels] == [len(lv.runs) for lv in cpu.levels]
+    for glv, clv in zip(py.levels, cpu.levels):
+        for gr, cr in zip(glv, clv.runs):
+            assert np.array_equal(oracle.as_run(gr.run), cr)
+    check_native_tree(oracle, nat, cpu, 16, 50)
+    nat.close()
