@@ -558,7 +558,8 @@ int lsm_driver_flush_unsorted(lsm_driver_t* driver, const lsm_entry_t* buffer, u
  * together: the compactions that the trees' cascades need at the same step go to the GPU as one lsm_compact_batch (the
  * fence indices written in the same pass) and the filters of their outputs as one lsm_build_bloom_batch, until every tree
  * is settled; a compaction of 2^21 entries or more is run on its own.  Every tree ends exactly as after its own
- * lsm_driver_flush.  drivers, runs, n: HOST arrays of `count` elements; runs[i] == NULL = tree i has nothing to flush.
+ * lsm_driver_flush.  drivers, runs, n: HOST arrays of `count` elements; runs[i] == NULL = tree i has nothing to flush
+ * (an empty write buffer, which is still a flush, is a non-NULL runs[i] with n[i] == 0).
  * The drivers must be distinct and share one stream (LSM_ERR_BAD_ARG otherwise). */
 int lsm_driver_flush_many(lsm_driver_t* const* drivers, const lsm_entry_t* const* runs, const uint64_t* n, uint32_t count);
 

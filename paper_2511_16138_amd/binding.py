@@ -763,7 +763,8 @@ def lsm_driver_flush_many(drivers: Sequence[LsmDriver], runs: Sequence[Optional[
         return
     assert len(runs) == count
     hd = (C.c_void_p * count)(*[d._h for d in drivers])
-    ptr = (C.c_void_p * count)(*[None if r is None else _dev(r, "run").data_ptr() for r in runs])
+    # an empty write buffer is still a flush (an empty run arrives): any non-null address says so, it is never read
+    ptr = (C.c_void_p * count)(*[None if r is None else (_dev(r, "run").data_ptr() or 64) for r in runs])
     n = (C.c_uint64 * count)(*[0 if r is None else int(r.shape[0]) for r in runs])
     rc = _load().lsm_driver_flush_many(hd, ptr, n, count)
     if rc != 0:

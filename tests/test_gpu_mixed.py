@@ -358,3 +358,62 @@ def test_drivers_on_degenerate_trees(oracle, seed, start_k, t_grid):
             assert np.array_equal(oracle.as_run(gr.run), cr)
     check_native_tree(oracle, nat, cpu, 16, 50)
     nat.close()
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3, 4])
+def test_flush_many_on_degenerate_trees(oracle, seed):
+    """lsm_driver_flush_many where it is awkward: one to four tiny trees with different settings, trees that sit a round
+    out, empty write buffers (still a flush), deletion-only buffers that merge to nothing."""
+    import brute
+    from gpu_util import to_dev
+    from oracle import lsm_driver_oracle as drv
+    from paper_2511_16138_amd import LsmDriver, lsm_driver_flush_many
+    print("flush_many on degenerate trees", seed, flush=True)
+    rs = np.random.RandomState(1000 + seed)
+    key_of = lambda k: int(k).to_bytes(32, "big")
+    n_trees, M, window = int(rs.randint(2, 5)), 40, 64
+    cfgs = [(int(rs.randint(1, 4)), (2, int(rs.randint(2, 6))), int(rs.choice([0, 16])), int(rs.choice([0, 30]))) for _ in range(n_trees)]
+    nats = [LsmDriver(M, size_ratio=4, runs_per_level=k, window_ops=window, t_grid=tg, bloom_bits=b, hash_index_from=ix) for k, tg, b, ix in cfgs]
+    cpus = [drv.DriverOracle(M, T=4, K=k, window_ops=window, threshold=0.2, t_grid=tg, page_entries=64.0, fpr=drv.bloom_fpr(b))
+            for k, tg, b, ix in cfgs]
+    seq = skipped = empty = 0
+    for step in range(150):
+        runs = []
+        for i in range(n_trees):
+            if rs.rand() < 0.25:
+                runs.append(None)               # this tree has nothing to flush in this round
+                skipped += 1
+                continue
+            n = 0 if rs.rand() < 0.1 else int(rs.randint(1, M + 1))
+            empty += n == 0
+            raw = []
+            for k in sorted(rs.choice(300, size=n, replace=False).tolist()):
+                seq += 1
+                tomb = step < 3 or rs.rand() < 0.5
+                raw.append(brute.pack_entry(key_of(k), seq, brute.TOMBSTONE if tomb else brute.PUT, vptr=seq, vlen=k))
+            run = brute.run_from_raw(raw)
+            nats[i].note_writes(max(n, 1))
+            cpus[i].writes(max(n, 1))
+            cpus[i].flush(run)
+            runs.append(to_dev(run))
+        lsm_driver_flush_many(nats, runs)
+        if step % 5 == 4:
+            n_req, max_blocks = 16, 5
+            q = np.zeros((n_req, max_blocks, 32), np.uint8)
+            nb = rs.randint(0, max_blocks + 1, size=n_req).astype(np.int32)
+            for r in range(n_req):
+                for j in range(max_blocks):
+                    q[r, j] = np.frombuffer(key_of(rs.randint(0, 300)), np.uint8)
+            gq = torch.from_numpy(q.view(np.int64).reshape(n_req, max_blocks, 4).copy()).to(dev())
+            gnb = torch.from_numpy(nb).to(dev())
+            for nat, cpu in zip(nats, cpus):
+                want_len, want_hits = cpu.probe(q, nb.astype(np.uint32))
+                hl, hits = nat.probe(gq, gnb)
+                assert np.array_equal(hl.cpu().numpy().astype(np.uint32), want_len), step
+                assert np.array_equal(hits.cpu().numpy().view(oracle.HIT_DTYPE).reshape(want_hits.shape), want_hits), step
+        for i, (nat, cpu) in enumerate(zip(nats, cpus)):
+            assert nat.trace == cpu.log, (step, i, nat.trace[-3:], cpu.log[-3:])
+    assert skipped > 20 and empty > 5
+    for (k, tg, b, ix), nat, cpu in zip(cfgs, nats, cpus):
+        check_native_tree(oracle, nat, cpu, b, ix)
+        nat.close()
